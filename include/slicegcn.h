@@ -1,0 +1,219 @@
+/*
+ * slicegcn.h -- C ABI of the MI355X (gfx950) SliceGCN hot path.
+ *
+ * The library evaluates, for one feature slice at a time, the full-graph layer of the
+ * SliceGCN model (arXiv 2408.11500): sparse aggregation with the symmetric-normalised
+ * adjacency held as CSR over the whole graph, the dense slice transform with bias, ReLU and
+ * self term, the backward pass of both, and slice encoding + concatenation of the slice
+ * outputs.  Every step runs in hand-written HIP kernels; nothing falls back to the CPU.
+ *
+ * General conventions
+ *  - Every function returns an int status: SLICEGCN_OK (0) or a negative SLICEGCN_E* code.
+ *    No exception or abort crosses this boundary.  slicegcn_last_error() returns a
+ *    thread-local text for the most recent failure in the calling thread.
+ *  - Unless marked HOST, array pointers are DEVICE pointers on the current HIP device.
+ *  - Matrices are fp32, row-major, with an explicit leading dimension counted in elements
+ *    (ld >= width), so column slices and concatenation targets are plain views.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
+ *    are asynchronous with respect to the host and ordered on that stream, except
+ *    slicegcn_build_norm_csr, which synchronises the stream before returning.
+ *  - Ownership: the caller owns every tensor, workspace and edge-list buffer.  The library
+ *    owns only what a slicegcn_graph handle holds (the CSR arrays), from
+ *    slicegcn_build_norm_csr until slicegcn_graph_destroy.  Apart from building a graph,
+ *    no call allocates or frees device memory.
+ *  - Results are deterministic: kernels use no floating-point atomics, so two calls on the
+ *    same inputs give bitwise equal outputs.
+ */
+#ifndef SLICEGCN_H
+#define SLICEGCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLICEGCN_OK 0
+#define SLICEGCN_EINVAL (-1)       /* NULL / misaligned / inconsistent argument            */
+#define SLICEGCN_ERANGE (-2)       /* node id outside [0, n_nodes) or a count beyond int32  */
+#define SLICEGCN_ENOMEM (-3)       /* device or host allocation failed                      */
+#define SLICEGCN_EHIP (-4)         /* a HIP runtime call failed (text in last_error)        */
+#define SLICEGCN_EUNSUPPORTED (-5) /* valid request this build does not implement           */
+#define SLICEGCN_EWORKSPACE (-6)   /* workspace pointer NULL or smaller than required       */
+
+/* flags of slicegcn_build_norm_csr */
+#define SLICEGCN_SYMMETRIZE 1u     /* store A | A^T (undirected graph)                      */
+#define SLICEGCN_ADD_SELF_LOOPS 2u /* add exactly one diagonal entry per row (A + I)        */
+
+/* activation of slicegcn_layer_desc.act */
+#define SLICEGCN_ACT_NONE 0
+#define SLICEGCN_ACT_RELU 1
+
+typedef struct slicegcn_graph slicegcn_graph; /* opaque; owns the CSR arrays on the device */
+
+/* Borrowed device pointers into a graph handle; valid until the handle is destroyed. */
+typedef struct {
+    int64_t n_nodes;
+    int64_t nnz;
+    const int32_t *rowptr; /* [n_nodes + 1]                                   */
+    const int32_t *colidx; /* [nnz], strictly ascending within each row       */
+    const int32_t *deg;    /* [n_nodes] stored entries per row (d~_v)         */
+    const float *dinv;     /* [n_nodes] 1/sqrt(max(d~_v, 1))                  */
+    const float *vals;     /* [nnz] dinv[row] * dinv[col]                     */
+    int32_t symmetric;     /* 1 when the pattern was symmetrised              */
+} slicegcn_csr_view;
+
+typedef struct {
+    int32_t w_in;  /* width of the layer input  (columns of Hin, rows of W)    */
+    int32_t w_out; /* width of the layer output (columns of Hout, cols of W)   */
+    int32_t act;   /* SLICEGCN_ACT_*                                           */
+} slicegcn_layer_desc;
+
+/* Parameters of one layer of one slice.  W_* are row-major w_in x w_out, contiguous
+ * (leading dimension w_out).  b, W_self, b_self may be NULL (term absent). */
+typedef struct {
+    const float *W_agg;
+    const float *b;      /* [w_out] bias inside the activation                  */
+    const float *W_self;
+    const float *b_self; /* [w_out] bias of the self term, outside the activation */
+} slicegcn_layer_params;
+
+/* What the forward pass keeps for the backward pass (caller-owned buffers).
+ * Z    : n x w_in aggregation result A^ Hin, leading dimension ldz (>= w_in, multiple of 4,
+ *        16-byte aligned base).
+ * mask : n x mask_words uint32; bit (j % 32) of word (j / 32) of row v is 1 where the
+ *        pre-activation P[v, j] > 0.  mask_words >= ceil(w_out / 32).  For ACT_NONE the
+ *        mask is neither written nor read and may be NULL. */
+typedef struct {
+    float *Z;
+    int64_t ldz;
+    uint32_t *mask;
+    int64_t mask_words;
+} slicegcn_layer_saved;
+
+/* Gradient outputs of one layer, same shapes as the parameters; NULL entries are skipped. */
+typedef struct {
+    float *dW_agg;
+    float *db;
+    float *dW_self;
+    float *db_self;
+} slicegcn_layer_grads;
+
+/* ---------------------------------------------------------------------------------------
+ * Slice strategy (HOST only).  Algorithm "Slice Strategy Generation" of the paper, equal to
+ * its closed-form start/end equation when slice_size_scale = 1:
+ *   slice_size = ceil(in_d / p); slice i = [i*slice_size, i*slice_size + int(slice_size*scale));
+ *   a slice that would pass in_d is shifted left to end at in_d (so it may overlap).
+ * starts/ends: HOST arrays of p entries (0-based, half-open).  slice_size: HOST scalar out.
+ * EINVAL: NULL output, p < 1, p > in_d, scale <= 0 or int(slice_size*scale) outside [1, in_d].
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_slice_strategy(int32_t in_d, int32_t p, double slice_size_scale,
+                            int32_t *starts, int32_t *ends, int32_t *slice_size);
+
+/* ---------------------------------------------------------------------------------------
+ * Normalised adjacency.  From n_edges pairs (src[e], dst[e]) (DEVICE int64 arrays, any order,
+ * repeats and self pairs allowed) builds A~ = A (| A^T) (+ I) as a 0/1 pattern -- the paper's
+ * binary adjacency matrix with every node counted among its own neighbours -- and the
+ * normalisation 1/c_vu = 1/(sqrt(d~_v) sqrt(d~_u)) of the paper's GCN layer equation, with
+ * d~_v the number of stored entries of row v.  Input self pairs are dropped and repeats
+ * collapsed, so the diagonal is exactly 1 entry when ADD_SELF_LOOPS is set.
+ * On success *out holds a new handle (free it with slicegcn_graph_destroy).  Allocates device
+ * memory, synchronises `stream`.  rowptr/colidx/deg are exact integers; dinv/vals are fp32.
+ * EINVAL: NULL out, n_nodes < 1, n_edges < 0, NULL src/dst with n_edges > 0, unknown flag.
+ * ERANGE: n_nodes > 2^31-1, more than 2^31-1 stored entries, or a node id outside [0, n_nodes).
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, int64_t n_edges,
+                            int64_t n_nodes, uint32_t flags, void *stream, slicegcn_graph **out);
+int slicegcn_graph_view(const slicegcn_graph *g, slicegcn_csr_view *view /* HOST struct out */);
+int slicegcn_graph_destroy(slicegcn_graph *g); /* NULL is accepted */
+
+/* ---------------------------------------------------------------------------------------
+ * Direct feature slicing: Xs = X[:, start:end] (the paper's direct-slicing equation and its
+ * "Feature Slicing" algorithm, without the device copy).  X: n x (>= end) with leading
+ * dimension ldx; Xs: n x ldxs, ldxs >= end - start.  Columns [end-start, ldxs) of Xs are
+ * written as zeros, so a padded slice can be read with vector loads.
+ * EINVAL: NULL pointer, n < 1, start < 0, start >= end, end > ldx, ldxs < end - start.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, int32_t start, int32_t end,
+                           float *Xs, int64_t ldxs, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Slice aggregation, the inner sum of the SliceGCN layer equation:
+ *   Y[v, 0:width] = sum over stored (v,u) of vals_vu * X[u, 0:width]       (transpose = 0)
+ *   Y = A^^T X                                                              (transpose != 0)
+ * X, Y: n_nodes x width with leading dimensions ldx, ldy.  X and Y must not overlap.
+ * The fast path needs X 16-byte aligned with ldx a multiple of 4 and ldx >= width rounded up
+ * to 4 (padding columns are read but never used); other layouts take a scalar path.  Only
+ * columns [0, width) of Y are written.  A symmetrised graph serves transpose != 0 with the
+ * same arrays; otherwise the handle holds the transposed pattern as well.
+ * EINVAL: NULL pointer, width < 1, ldx < width, ldy < width.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+                        int32_t width, float *Y, int64_t ldy, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * One layer of one slice, forward (the SliceGCN layer equation as typeset, self term outside
+ * the activation):
+ *   Z = A^ Hin;  P = b + Z W_agg;  Hout = act(P) + Hin W_self + b_self.
+ * Hin: n x w_in (ldi); Hout: n x w_out (ldo, any value >= w_out: the last layer can store
+ * straight into its column block of the concatenated representation).  saved->Z is always
+ * written (it is the staging buffer of the aggregation); saved->mask is written for ACT_RELU.
+ * Hin must satisfy the fast-path layout of slicegcn_spmm_slice or the scalar path is taken.
+ * No workspace is needed.
+ * EINVAL: NULL Hin/Hout/W_agg/saved->Z, widths < 1, ld too small, ldz not a multiple of 4,
+ *         mask NULL or mask_words too small with ACT_RELU, unknown act.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
+                       const slicegcn_layer_params *params, const float *Hin, int64_t ldi,
+                       float *Hout, int64_t ldo, slicegcn_layer_saved *saved, void *stream);
+
+/* Bytes of workspace slicegcn_layer_bwd needs for this graph size and layer (0 on bad input).
+ * need_dHin = 0 when the input gradient is not wanted (first layer over raw features). */
+size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slicegcn_layer_desc *desc, int need_dHin);
+
+/* ---------------------------------------------------------------------------------------
+ * One layer of one slice, backward (chain rule of the forward above; ReLU'(0) = 0):
+ *   dP = dHout * mask;  db = colsum dP;  db_self = colsum dHout;
+ *   dW_agg = Z^T dP;    dW_self = Hin^T dHout;
+ *   dHin = A^^T (dP W_agg^T) + dHout W_self^T         (skipped when dHin == NULL).
+ * saved holds Z and mask exactly as slicegcn_layer_fwd wrote them (read only here).
+ * Reductions over the nodes run in fp32 over short row blocks and are combined in fp64 in a
+ * fixed order.  ws: workspace of at least slicegcn_layer_bwd_workspace_bytes bytes, 256-byte
+ * aligned; its contents are scratch.
+ * EINVAL as for the forward; EWORKSPACE when ws is NULL or ws_bytes too small.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
+                       const slicegcn_layer_params *params, const float *Hin, int64_t ldi,
+                       const slicegcn_layer_saved *saved, const float *dHout, int64_t ldo,
+                       float *dHin, int64_t ldgi, slicegcn_layer_grads *grads,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Slice encoding + concatenation (the paper's slice-encoding and CONCAT equations):
+ *   H[v, off_i + j] = Hs[i][v, j] + E[i, j],  off_i = widths[0] + ... + widths[i-1].
+ * Hs: HOST array of k DEVICE pointers (n x widths[i], leading dimension lds[i]);
+ * lds, widths: HOST arrays.  E: DEVICE k x lde matrix, or NULL for plain concatenation.
+ * If Hs[i] already is the column block H + off_i with lds[i] == ldh, the slice is encoded in
+ * place (no copy).  EINVAL: NULL pointer, k < 1, n < 1, width < 1, ld too small,
+ * sum of widths > ldh, lde < max width.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t *lds, const int32_t *widths,
+                    const float *E, int64_t lde, int64_t n, float *H, int64_t ldh, void *stream);
+
+size_t slicegcn_concat_bwd_workspace_bytes(int64_t n, int32_t k, const int32_t *widths /* HOST */);
+
+/* Backward of the above: dHs[i] = dH[:, off_i : off_i + widths[i]] (copied only when dHs is
+ * non-NULL and dHs[i] is non-NULL -- callers normally use the column view of dH instead) and
+ * dE[i, j] = sum over nodes of dH[v, off_i + j] (skipped when dE == NULL; needs ws). */
+int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, const int32_t *widths,
+                        float *const *dHs, const int64_t *lds, float *dE, int64_t lde,
+                        void *ws, size_t ws_bytes, void *stream);
+
+const char *slicegcn_strerror(int status);
+const char *slicegcn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLICEGCN_H */

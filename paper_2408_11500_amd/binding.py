@@ -1,0 +1,326 @@
+"""ctypes binding of ``libslicegcn.so``: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device memory: every function passes
+``data_ptr()``, the row stride as leading dimension and the current HIP stream to the library.
+No arithmetic of the method happens here, and there is no CPU fallback: if the library has not
+been built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libslicegcn.so")
+
+SYMMETRIZE = 1
+ADD_SELF_LOOPS = 2
+ACT_NONE = 0
+ACT_RELU = 1
+
+OK, EINVAL, ERANGE, ENOMEM, EHIP, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "slicegcn_slice_strategy", "slicegcn_build_norm_csr", "slicegcn_graph_view", "slicegcn_graph_destroy",
+    "slicegcn_slice_feature", "slicegcn_spmm_slice", "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
+    "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
+    "slicegcn_strerror", "slicegcn_last_error",
+]
+
+
+class SliceGCNError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"slicegcn status {status}: {text}")
+        self.status = status
+
+
+class _CsrView(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_int64), ("nnz", ctypes.c_int64), ("rowptr", ctypes.c_void_p),
+                ("colidx", ctypes.c_void_p), ("deg", ctypes.c_void_p), ("dinv", ctypes.c_void_p),
+                ("vals", ctypes.c_void_p), ("symmetric", ctypes.c_int32)]
+
+
+class _LayerDesc(ctypes.Structure):
+    _fields_ = [("w_in", ctypes.c_int32), ("w_out", ctypes.c_int32), ("act", ctypes.c_int32)]
+
+
+class _LayerParams(ctypes.Structure):
+    _fields_ = [("W_agg", ctypes.c_void_p), ("b", ctypes.c_void_p), ("W_self", ctypes.c_void_p), ("b_self", ctypes.c_void_p)]
+
+
+class _LayerSaved(ctypes.Structure):
+    _fields_ = [("Z", ctypes.c_void_p), ("ldz", ctypes.c_int64), ("mask", ctypes.c_void_p), ("mask_words", ctypes.c_int64)]
+
+
+class _LayerGrads(ctypes.Structure):
+    _fields_ = [("dW_agg", ctypes.c_void_p), ("db", ctypes.c_void_p), ("dW_self", ctypes.c_void_p), ("db_self", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded HIP library.  Raises if it has not been built (there is no other path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_11500_amd.build` "
+                               "(or __graft_entry__.build()); the library has no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.slicegcn_slice_strategy.argtypes = [i32, i32, ctypes.c_double, vp, vp, vp]
+        L.slicegcn_build_norm_csr.argtypes = [vp, vp, i64, i64, ctypes.c_uint32, vp, ctypes.POINTER(vp)]
+        L.slicegcn_graph_view.argtypes = [vp, ctypes.POINTER(_CsrView)]
+        L.slicegcn_graph_destroy.argtypes = [vp]
+        L.slicegcn_slice_feature.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp]
+        L.slicegcn_spmm_slice.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp]
+        L.slicegcn_layer_fwd.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.POINTER(_LayerParams), vp, i64, vp, i64,
+                                         ctypes.POINTER(_LayerSaved), vp]
+        L.slicegcn_layer_bwd_workspace_bytes.argtypes = [i64, ctypes.POINTER(_LayerDesc), ctypes.c_int]
+        L.slicegcn_layer_bwd_workspace_bytes.restype = sz
+        L.slicegcn_layer_bwd.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.POINTER(_LayerParams), vp, i64,
+                                         ctypes.POINTER(_LayerSaved), vp, i64, vp, i64, ctypes.POINTER(_LayerGrads),
+                                         vp, sz, vp]
+        L.slicegcn_concat.argtypes = [i32, vp, vp, vp, vp, i64, i64, vp, i64, vp]
+        L.slicegcn_concat_bwd_workspace_bytes.argtypes = [i64, i32, vp]
+        L.slicegcn_concat_bwd_workspace_bytes.restype = sz
+        L.slicegcn_concat_bwd.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, i64, vp, sz, vp]
+        L.slicegcn_strerror.argtypes = [ctypes.c_int]
+        L.slicegcn_strerror.restype = ctypes.c_char_p
+        L.slicegcn_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        L = lib()
+        detail = L.slicegcn_last_error().decode()
+        raise SliceGCNError(rc, f"{L.slicegcn_strerror(rc).decode()}: {detail}")
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _mat(t: torch.Tensor, name: str, dtype=torch.float32):
+    """(pointer, leading dimension) of a 2-D device tensor with unit column stride."""
+    if not t.is_cuda or t.dtype != dtype or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise TypeError(f"{name}: expected a 2-D {dtype} device tensor with unit column stride")
+    return t.data_ptr(), int(t.stride(0)) if t.shape[0] > 1 else max(int(t.stride(0)), int(t.shape[1]))
+
+
+def _vec(t, name: str, dtype=torch.float32):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype} device tensor")
+    return t.data_ptr()
+
+
+# ---------------------------------------------------------------------------------------
+def slicegcn_slice_strategy(in_d: int, p: int, slice_size_scale: float = 1.0):
+    """Host call: returns ([(start, end)] * p, slice_size)."""
+    n = max(int(p), 1)
+    starts = (ctypes.c_int32 * n)()
+    ends = (ctypes.c_int32 * n)()
+    size = ctypes.c_int32(0)
+    _check(lib().slicegcn_slice_strategy(in_d, p, slice_size_scale, ctypes.addressof(starts), ctypes.addressof(ends),
+                                         ctypes.addressof(size)))
+    return [(int(starts[i]), int(ends[i])) for i in range(p)], int(size.value)
+
+
+@dataclass
+class CsrView:
+    n_nodes: int
+    nnz: int
+    rowptr: int
+    colidx: int
+    deg: int
+    dinv: int
+    vals: int
+    symmetric: int
+
+
+class Graph:
+    """Owner of a ``slicegcn_graph`` handle."""
+
+    def __init__(self, handle: int):
+        self._h = handle
+
+    @property
+    def handle(self) -> int:
+        if not self._h:
+            raise ValueError("graph handle already destroyed")
+        return self._h
+
+    def view(self) -> CsrView:
+        v = _CsrView()
+        _check(lib().slicegcn_graph_view(self.handle, ctypes.byref(v)))
+        return CsrView(v.n_nodes, v.nnz, v.rowptr or 0, v.colidx or 0, v.deg or 0, v.dinv or 0, v.vals or 0, v.symmetric)
+
+    def to_host(self) -> dict:
+        """Copies of the CSR arrays as numpy arrays (for checks)."""
+        v = self.view()
+        return dict(n=v.n_nodes, nnz=v.nnz,
+                    rowptr=_to_host(v.rowptr, v.n_nodes + 1, np.int32), colidx=_to_host(v.colidx, v.nnz, np.int32),
+                    deg=_to_host(v.deg, v.n_nodes, np.int32), dinv=_to_host(v.dinv, v.n_nodes, np.float32),
+                    vals=_to_host(v.vals, v.nnz, np.float32))
+
+    def destroy(self):
+        if self._h:
+            lib().slicegcn_graph_destroy(self._h)
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+_hip = None
+
+
+def _to_host(ptr: int, count: int, dtype) -> np.ndarray:
+    """Device-to-host copy of a raw device array (hipMemcpy)."""
+    global _hip
+    out = np.empty(count, dtype=dtype)
+    if count == 0:
+        return out
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    torch.cuda.synchronize()
+    rc = _hip.hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)  # 2 = device to host
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy failed with {rc}")
+    return out
+
+
+def slicegcn_build_norm_csr(src: torch.Tensor, dst: torch.Tensor, n_nodes: int,
+                            flags: int = SYMMETRIZE | ADD_SELF_LOOPS) -> Graph:
+    ps = _vec(src, "src", torch.int64) if src.numel() else None
+    pd = _vec(dst, "dst", torch.int64) if dst.numel() else None
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst differ in length")
+    h = ctypes.c_void_p(0)
+    _check(lib().slicegcn_build_norm_csr(ps, pd, src.numel(), n_nodes, flags, _stream(), ctypes.byref(h)))
+    return Graph(h.value)
+
+
+def slicegcn_slice_feature(X: torch.Tensor, start: int, end: int, Xs: torch.Tensor):
+    px, ldx = _mat(X, "X")
+    pxs, ldxs = _mat(Xs, "Xs")
+    if Xs.shape[0] != X.shape[0]:
+        raise ValueError("Xs has the wrong number of rows")
+    _check(lib().slicegcn_slice_feature(px, X.shape[0], ldx, start, end, pxs, ldxs, _stream()))
+    return Xs
+
+
+def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False):
+    px, ldx = _mat(X, "X")
+    py, ldy = _mat(Y, "Y")
+    if X.shape[0] != Y.shape[0]:
+        raise ValueError("X and Y differ in rows")
+    w = int(X.shape[1] if width is None else width)
+    _check(lib().slicegcn_spmm_slice(g.handle, int(transpose), px, ldx, w, py, ldy, _stream()))
+    return Y
+
+
+def _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self):
+    desc = _LayerDesc(w_in, w_out, act)
+    for name, W in (("W_agg", W_agg), ("W_self", W_self)):
+        if W is not None and (tuple(W.shape) != (w_in, w_out)):
+            raise ValueError(f"{name} must be w_in x w_out")
+    params = _LayerParams(_vec(W_agg, "W_agg"), _vec(b, "b"), _vec(W_self, "W_self"), _vec(b_self, "b_self"))
+    return desc, params
+
+
+def _saved_struct(Z: torch.Tensor, mask):
+    pz, ldz = _mat(Z, "Z")
+    if mask is None:
+        return _LayerSaved(pz, ldz, None, 0)
+    pm, ldm = _mat(mask, "mask", torch.int32)
+    return _LayerSaved(pz, ldz, pm, ldm)
+
+
+def slicegcn_layer_fwd(g: Graph, Hin, W_agg, b, W_self, b_self, Hout, Z, mask, act: int = ACT_RELU,
+                       w_in: int | None = None, w_out: int | None = None):
+    """Hout = act(A^ Hin W_agg + b) + Hin W_self + b_self; fills Z (and mask for ReLU)."""
+    w_in = int(W_agg.shape[0] if w_in is None else w_in)
+    w_out = int(W_agg.shape[1] if w_out is None else w_out)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self)
+    pi, ldi = _mat(Hin, "Hin")
+    po, ldo = _mat(Hout, "Hout")
+    saved = _saved_struct(Z, mask)
+    _check(lib().slicegcn_layer_fwd(g.handle, ctypes.byref(desc), ctypes.byref(params), pi, ldi, po, ldo,
+                                    ctypes.byref(saved), _stream()))
+    return Hout
+
+
+def slicegcn_layer_bwd_workspace_bytes(n_nodes: int, w_in: int, w_out: int, need_dHin: bool) -> int:
+    desc = _LayerDesc(w_in, w_out, ACT_RELU)
+    return int(lib().slicegcn_layer_bwd_workspace_bytes(n_nodes, ctypes.byref(desc), int(need_dHin)))
+
+
+def slicegcn_layer_bwd(g: Graph, Hin, W_agg, W_self, Z, mask, dHout, dHin, dW_agg, db, dW_self, db_self, ws,
+                       act: int = ACT_RELU):
+    """Gradients of one layer.  ``dHin`` may be None (skipped).  ``ws`` is a uint8 workspace tensor."""
+    w_in, w_out = int(W_agg.shape[0]), int(W_agg.shape[1])
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, None, W_self, None)
+    pi, ldi = _mat(Hin, "Hin")
+    pg, ldo = _mat(dHout, "dHout")
+    pgi, ldgi = _mat(dHin, "dHin") if dHin is not None else (None, 0)
+    saved = _saved_struct(Z, mask)
+    grads = _LayerGrads(_vec(dW_agg, "dW_agg"), _vec(db, "db"), _vec(dW_self, "dW_self"), _vec(db_self, "db_self"))
+    _check(lib().slicegcn_layer_bwd(g.handle, ctypes.byref(desc), ctypes.byref(params), pi, ldi, ctypes.byref(saved),
+                                    pg, ldo, pgi, ldgi, ctypes.byref(grads),
+                                    ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
+                                    _stream()))
+
+
+def slicegcn_concat(Hs, E, H: torch.Tensor):
+    """H[:, off_i : off_i + w_i] = Hs[i] + E[i, :w_i]  (E may be None)."""
+    k = len(Hs)
+    ptrs = (ctypes.c_void_p * k)()
+    lds = (ctypes.c_int64 * k)()
+    widths = (ctypes.c_int32 * k)()
+    for i, h in enumerate(Hs):
+        ptrs[i], lds[i] = _mat(h, f"Hs[{i}]")
+        widths[i] = h.shape[1]
+    pe, lde = _mat(E, "E") if E is not None else (None, 0)
+    ph, ldh = _mat(H, "H")
+    _check(lib().slicegcn_concat(k, ctypes.addressof(ptrs), ctypes.addressof(lds), ctypes.addressof(widths), pe, lde,
+                                 H.shape[0], ph, ldh, _stream()))
+    return H
+
+
+def slicegcn_concat_bwd_workspace_bytes(n: int, widths) -> int:
+    k = len(widths)
+    w = (ctypes.c_int32 * k)(*[int(x) for x in widths])
+    return int(lib().slicegcn_concat_bwd_workspace_bytes(n, k, ctypes.addressof(w)))
+
+
+def slicegcn_concat_bwd(dH: torch.Tensor, widths, dHs=None, dE=None, ws=None):
+    """dE[i, :w_i] = column sums of dH's block i; optional copies of the blocks into dHs[i]."""
+    k = len(widths)
+    w = (ctypes.c_int32 * k)(*[int(x) for x in widths])
+    pdh, ldh = _mat(dH, "dH")
+    ptrs = lds = None
+    if dHs is not None:
+        ptrs = (ctypes.c_void_p * k)()
+        lds = (ctypes.c_int64 * k)()
+        for i, t in enumerate(dHs):
+            if t is not None:
+                ptrs[i], lds[i] = _mat(t, f"dHs[{i}]")
+    pe, lde = _mat(dE, "dE") if dE is not None else (None, 0)
+    _check(lib().slicegcn_concat_bwd(k, pdh, ldh, dH.shape[0], ctypes.addressof(w),
+                                     ctypes.addressof(ptrs) if ptrs is not None else None,
+                                     ctypes.addressof(lds) if lds is not None else None, pe, lde,
+                                     ws.data_ptr() if ws is not None else None,
+                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream()))

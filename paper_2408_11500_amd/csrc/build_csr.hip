@@ -1,0 +1,385 @@
+// Normalised-adjacency builder: edge pairs -> canonical CSR of A^ = D~^-1/2 (A + I) D~^-1/2
+// (the normalisation 1/c_vu of the paper's GCN layer equation), plus the row schedule the
+// aggregation kernels use.  Integer work only, apart from one rsqrt per node and one multiply
+// per stored entry.  Sorting, scanning and duplicate removal use rocPRIM device primitives on
+// 64-bit keys (row << 32 | col); everything else is a small kernel below.
+#include "common.h"
+
+#include <rocprim/rocprim.hpp>
+
+#include <cstdarg>
+#include <new>
+
+namespace slicegcn {
+
+namespace {
+
+struct DevBuf { // frees on scope exit; release() hands the pointer over
+    void *p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    int alloc(size_t bytes) {
+        hipError_t e = hipMalloc(&p, bytes ? bytes : 1);
+        if (e != hipSuccess) {
+            p = nullptr;
+            set_error("hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+            return e == hipErrorOutOfMemory ? SLICEGCN_ENOMEM : SLICEGCN_EHIP;
+        }
+        return SLICEGCN_OK;
+    }
+    template <class T> T *as() const { return static_cast<T *>(p); }
+    template <class T> T *release() { T *r = static_cast<T *>(p); p = nullptr; return r; }
+};
+
+constexpr int TPB = 256;
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + TPB - 1) / TPB); }
+
+// One key per directed candidate entry.  Self pairs and out-of-range pairs become the
+// sentinel key (row n), which sorts behind every real row and is dropped later.
+__global__ void make_keys_kernel(const int64_t *__restrict__ src, const int64_t *__restrict__ dst,
+                                 int64_t n_edges, int64_t n, int sym, int loops,
+                                 uint64_t *__restrict__ keys, int *__restrict__ n_bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    const uint64_t sentinel = (uint64_t)n << 32;
+    if (i < n_edges) {
+        const int64_t u = src[i], v = dst[i];
+        uint64_t k1 = sentinel, k2 = sentinel;
+        if (u < 0 || u >= n || v < 0 || v >= n) {
+            atomicAdd(n_bad, 1);
+        } else if (u != v) {
+            k1 = ((uint64_t)u << 32) | (uint64_t)v;
+            k2 = ((uint64_t)v << 32) | (uint64_t)u;
+        }
+        keys[i] = k1;
+        if (sym) keys[n_edges + i] = k2;
+    } else if (loops && i < n_edges + n) {
+        const uint64_t v = (uint64_t)(i - n_edges);
+        keys[(sym ? 2 : 1) * n_edges + (int64_t)v] = (v << 32) | v;
+    }
+}
+
+// rowptr[r] = number of keys with row < r = lower bound of (r << 32) in the sorted keys.
+__global__ void rowptr_kernel(const uint64_t *__restrict__ keys, int64_t nnz, int64_t n,
+                              int32_t *__restrict__ rowptr)
+{
+    const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (r > n) return;
+    const uint64_t target = (uint64_t)r << 32;
+    int64_t lo = 0, hi = nnz;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (keys[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    rowptr[r] = (int32_t)lo;
+}
+
+__global__ void degree_kernel(const int32_t *__restrict__ rowptr, int64_t n,
+                              int32_t *__restrict__ deg, float *__restrict__ dinv)
+{
+    const int64_t v = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (v >= n) return;
+    const int32_t d = rowptr[v + 1] - rowptr[v];
+    deg[v] = d;
+    dinv[v] = (float)(1.0 / sqrt((double)(d > 0 ? d : 1)));
+}
+
+__global__ void entries_kernel(const uint64_t *__restrict__ keys, int64_t nnz,
+                               const float *__restrict__ dinv,
+                               int32_t *__restrict__ colidx, float *__restrict__ vals)
+{
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nnz) return;
+    const uint64_t k = keys[i];
+    const uint32_t row = (uint32_t)(k >> 32), col = (uint32_t)(k & 0xffffffffu);
+    colidx[i] = (int32_t)col;
+    vals[i] = dinv[row] * dinv[col];
+}
+
+__global__ void swap_keys_kernel(const uint64_t *__restrict__ in, int64_t nnz, uint64_t *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nnz) return;
+    const uint64_t k = in[i];
+    out[i] = (k << 32) | (k >> 32);
+}
+
+// ---- schedule ---------------------------------------------------------------------------
+__device__ inline int segments_of(int32_t d) { return d > LONG_ROW ? (d + SEG_NNZ - 1) / SEG_NNZ : 0; }
+
+__global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, int64_t n,
+                                   int32_t *__restrict__ c_seg, int32_t *__restrict__ c_slot,
+                                   int32_t *__restrict__ c_fix)
+{
+    const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (r > n) return;
+    int s = 0;
+    if (r < n) s = segments_of(rowptr[r + 1] - rowptr[r]);
+    c_seg[r] = s;
+    c_slot[r] = s > 1 ? s : 0;
+    c_fix[r] = s > 1 ? 1 : 0;
+}
+
+__global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, int64_t n,
+                                  const int32_t *__restrict__ o_seg, const int32_t *__restrict__ o_slot,
+                                  const int32_t *__restrict__ o_fix,
+                                  Segment *__restrict__ segs, FixRow *__restrict__ fix)
+{
+    const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (r >= n) return;
+    const int32_t beg = rowptr[r], end = rowptr[r + 1];
+    const int s = segments_of(end - beg);
+    if (s == 0) return;
+    const int32_t len = (end - beg + s - 1) / s; // equal cuts, last one takes the remainder
+    for (int j = 0; j < s; ++j) {
+        Segment sg;
+        sg.row = (int32_t)r;
+        sg.beg = beg + j * len;
+        sg.end = min(end, beg + (j + 1) * len);
+        sg.dst = s == 1 ? (int32_t)r : -(o_slot[r] + j + 1);
+        segs[o_seg[r] + j] = sg;
+    }
+    if (s > 1) {
+        FixRow f;
+        f.row = (int32_t)r;
+        f.slot_beg = o_slot[r];
+        f.slot_end = o_slot[r] + s;
+        f.pad = 0;
+        fix[o_fix[r]] = f;
+    }
+}
+
+int scan_i32(const int32_t *in, int32_t *out, int64_t count, hipStream_t stream)
+{
+    size_t bytes = 0;
+    SG_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), stream));
+    DevBuf tmp;
+    if (int rc = tmp.alloc(bytes)) return rc;
+    SG_HIP(rocprim::exclusive_scan(tmp.p, bytes, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), stream));
+    SG_HIP(hipStreamSynchronize(stream));
+    return SLICEGCN_OK;
+}
+
+int sort_keys(const uint64_t *in, uint64_t *out, int64_t count, unsigned end_bit, hipStream_t stream)
+{
+    size_t bytes = 0;
+    SG_HIP(rocprim::radix_sort_keys(nullptr, bytes, in, out, (size_t)count, 0u, end_bit, stream));
+    DevBuf tmp;
+    if (int rc = tmp.alloc(bytes)) return rc;
+    SG_HIP(rocprim::radix_sort_keys(tmp.p, bytes, in, out, (size_t)count, 0u, end_bit, stream));
+    SG_HIP(hipStreamSynchronize(stream));
+    return SLICEGCN_OK;
+}
+
+// rowptr / colidx / vals of the pattern whose sorted distinct keys are given
+int pattern_from_keys(const uint64_t *keys, int64_t nnz, int64_t n, const float *dinv, Csr &m, hipStream_t stream)
+{
+    DevBuf col, val;
+    if (int rc = col.alloc((size_t)nnz * sizeof(int32_t))) return rc;
+    if (int rc = val.alloc((size_t)nnz * sizeof(float))) return rc;
+    if (nnz > 0) {
+        entries_kernel<<<blocks_for(nnz), TPB, 0, stream>>>(keys, nnz, dinv, col.as<int32_t>(), val.as<float>());
+        SG_LAUNCH_CHECK();
+    }
+    m.colidx = col.release<int32_t>();
+    m.vals = val.release<float>();
+    return SLICEGCN_OK;
+}
+
+} // namespace
+
+void free_csr(Csr &m, bool owns_pattern)
+{
+    if (owns_pattern) {
+        (void)hipFree(m.rowptr);
+        (void)hipFree(m.colidx);
+        (void)hipFree(m.vals);
+    }
+    (void)hipFree(m.segs);
+    (void)hipFree(m.fix);
+    m = Csr();
+}
+
+int build_schedule(int64_t n, Csr &m, hipStream_t stream)
+{
+    DevBuf cnt, off;
+    const size_t stride = (size_t)(n + 1);
+    if (int rc = cnt.alloc(3 * stride * sizeof(int32_t))) return rc;
+    if (int rc = off.alloc(3 * stride * sizeof(int32_t))) return rc;
+    int32_t *c = cnt.as<int32_t>(), *o = off.as<int32_t>();
+    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, n, c, c + stride, c + 2 * stride);
+    SG_LAUNCH_CHECK();
+    for (int a = 0; a < 3; ++a)
+        if (int rc = scan_i32(c + a * stride, o + a * stride, n + 1, stream)) return rc;
+    int32_t totals[3];
+    for (int a = 0; a < 3; ++a)
+        SG_HIP(hipMemcpy(&totals[a], o + a * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
+    m.n_segs = totals[0];
+    m.n_slots = totals[1];
+    m.n_fix = totals[2];
+    DevBuf segs, fix;
+    if (int rc = segs.alloc((size_t)m.n_segs * sizeof(Segment))) return rc;
+    if (int rc = fix.alloc((size_t)m.n_fix * sizeof(FixRow))) return rc;
+    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, n, o, o + stride, o + 2 * stride,
+                                                         segs.as<Segment>(), fix.as<FixRow>());
+    SG_LAUNCH_CHECK();
+    SG_HIP(hipStreamSynchronize(stream));
+    m.segs = segs.release<Segment>();
+    m.fix = fix.release<FixRow>();
+    return SLICEGCN_OK;
+}
+
+} // namespace slicegcn
+
+using namespace slicegcn;
+
+extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, int64_t n_edges,
+                                       int64_t n_nodes, uint32_t flags, void *stream_, slicegcn_graph **out)
+{
+    SG_REQUIRE(out != nullptr, SLICEGCN_EINVAL, "build_norm_csr: out is NULL");
+    *out = nullptr;
+    SG_REQUIRE(n_nodes >= 1, SLICEGCN_EINVAL, "build_norm_csr: n_nodes = %lld < 1", (long long)n_nodes);
+    SG_REQUIRE(n_edges >= 0, SLICEGCN_EINVAL, "build_norm_csr: n_edges = %lld < 0", (long long)n_edges);
+    SG_REQUIRE(n_edges == 0 || (src && dst), SLICEGCN_EINVAL, "build_norm_csr: NULL edge arrays");
+    SG_REQUIRE((flags & ~(SLICEGCN_SYMMETRIZE | SLICEGCN_ADD_SELF_LOOPS)) == 0, SLICEGCN_EINVAL,
+               "build_norm_csr: unknown flag bits 0x%x", flags);
+    SG_REQUIRE(n_nodes <= INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: n_nodes exceeds int32");
+    const int sym = (flags & SLICEGCN_SYMMETRIZE) != 0, loops = (flags & SLICEGCN_ADD_SELF_LOOPS) != 0;
+    SG_REQUIRE(n_edges <= (int64_t)INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: n_edges exceeds int32");
+    const int64_t n_keys = n_edges * (sym ? 2 : 1) + (loops ? n_nodes : 0);
+    SG_REQUIRE(n_keys <= (int64_t)INT32_MAX, SLICEGCN_ERANGE,
+               "build_norm_csr: %lld candidate entries exceed int32 indexing", (long long)n_keys);
+    hipStream_t stream = as_stream(stream_);
+
+    slicegcn_graph *g = new (std::nothrow) slicegcn_graph();
+    SG_REQUIRE(g != nullptr, SLICEGCN_ENOMEM, "build_norm_csr: host allocation failed");
+    struct Guard { // destroys the half-built handle on any early return
+        slicegcn_graph *g;
+        ~Guard() { if (g) slicegcn_graph_destroy(g); }
+    } guard{g};
+    g->n = n_nodes;
+    g->symmetric = sym;
+    SG_HIP(hipGetDevice(&g->device));
+
+    DevBuf keys_a, keys_b, counters;
+    if (int rc = keys_a.alloc((size_t)n_keys * sizeof(uint64_t))) return rc;
+    if (int rc = keys_b.alloc((size_t)n_keys * sizeof(uint64_t))) return rc;
+    if (int rc = counters.alloc(64)) return rc;
+    SG_HIP(hipMemsetAsync(counters.p, 0, 64, stream));
+    int *d_bad = counters.as<int>();
+    size_t *d_count = reinterpret_cast<size_t *>(counters.as<char>() + 16);
+
+    int64_t nnz = 0;
+    if (n_keys > 0) {
+        make_keys_kernel<<<blocks_for(n_edges + (loops ? n_nodes : 0)), TPB, 0, stream>>>(
+            src, dst, n_edges, n_nodes, sym, loops, keys_a.as<uint64_t>(), d_bad);
+        SG_LAUNCH_CHECK();
+        int h_bad = 0;
+        SG_HIP(hipMemcpyAsync(&h_bad, d_bad, sizeof(int), hipMemcpyDeviceToHost, stream));
+        SG_HIP(hipStreamSynchronize(stream));
+        SG_REQUIRE(h_bad == 0, SLICEGCN_ERANGE, "build_norm_csr: %d edge(s) name a node outside [0, %lld)", h_bad,
+                   (long long)n_nodes);
+
+        unsigned row_bits = 1;
+        while (((uint64_t)n_nodes >> row_bits) != 0) ++row_bits; // bits needed for the value n_nodes (sentinel row)
+        if (int rc = sort_keys(keys_a.as<uint64_t>(), keys_b.as<uint64_t>(), n_keys, 32 + row_bits, stream)) return rc;
+
+        size_t bytes = 0;
+        SG_HIP(rocprim::unique(nullptr, bytes, keys_b.as<uint64_t>(), keys_a.as<uint64_t>(), d_count, (size_t)n_keys,
+                               rocprim::equal_to<uint64_t>(), stream));
+        {
+            DevBuf tmp;
+            if (int rc = tmp.alloc(bytes)) return rc;
+            SG_HIP(rocprim::unique(tmp.p, bytes, keys_b.as<uint64_t>(), keys_a.as<uint64_t>(), d_count, (size_t)n_keys,
+                                   rocprim::equal_to<uint64_t>(), stream));
+            SG_HIP(hipStreamSynchronize(stream));
+        }
+        size_t h_count = 0;
+        SG_HIP(hipMemcpy(&h_count, d_count, sizeof(size_t), hipMemcpyDeviceToHost));
+        nnz = (int64_t)h_count;
+        if (nnz > 0) { // drop the sentinel (it is the largest key, so the last distinct one)
+            uint64_t last = 0;
+            SG_HIP(hipMemcpy(&last, keys_a.as<uint64_t>() + (nnz - 1), sizeof(uint64_t), hipMemcpyDeviceToHost));
+            if ((last >> 32) == (uint64_t)n_nodes) --nnz;
+        }
+    }
+    g->nnz = nnz;
+    const uint64_t *uniq = keys_a.as<uint64_t>(); // sorted distinct keys [0, nnz)
+
+    {
+        DevBuf rowptr, deg, dinv;
+        if (int rc = rowptr.alloc((size_t)(n_nodes + 1) * sizeof(int32_t))) return rc;
+        if (int rc = deg.alloc((size_t)n_nodes * sizeof(int32_t))) return rc;
+        if (int rc = dinv.alloc((size_t)n_nodes * sizeof(float))) return rc;
+        rowptr_kernel<<<blocks_for(n_nodes + 1), TPB, 0, stream>>>(uniq, nnz, n_nodes, rowptr.as<int32_t>());
+        SG_LAUNCH_CHECK();
+        degree_kernel<<<blocks_for(n_nodes), TPB, 0, stream>>>(rowptr.as<int32_t>(), n_nodes, deg.as<int32_t>(),
+                                                              dinv.as<float>());
+        SG_LAUNCH_CHECK();
+        g->fwd.rowptr = rowptr.release<int32_t>();
+        g->deg = deg.release<int32_t>();
+        g->dinv = dinv.release<float>();
+    }
+    if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
+    if (int rc = build_schedule(n_nodes, g->fwd, stream)) return rc;
+
+    if (sym) {
+        g->tr = g->fwd; // A^ is symmetric: the same arrays serve the transposed product
+    } else {
+        uint64_t *swapped = keys_b.as<uint64_t>();
+        if (nnz > 0) {
+            swap_keys_kernel<<<blocks_for(nnz), TPB, 0, stream>>>(uniq, nnz, swapped);
+            SG_LAUNCH_CHECK();
+        }
+        DevBuf keys_c;
+        if (int rc = keys_c.alloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint64_t))) return rc;
+        unsigned row_bits = 1;
+        while (((uint64_t)n_nodes >> row_bits) != 0) ++row_bits;
+        if (nnz > 0)
+            if (int rc = sort_keys(swapped, keys_c.as<uint64_t>(), nnz, 32 + row_bits, stream)) return rc;
+        DevBuf rowptr;
+        if (int rc = rowptr.alloc((size_t)(n_nodes + 1) * sizeof(int32_t))) return rc;
+        rowptr_kernel<<<blocks_for(n_nodes + 1), TPB, 0, stream>>>(keys_c.as<uint64_t>(), nnz, n_nodes, rowptr.as<int32_t>());
+        SG_LAUNCH_CHECK();
+        g->tr.rowptr = rowptr.release<int32_t>();
+        if (int rc = pattern_from_keys(keys_c.as<uint64_t>(), nnz, n_nodes, g->dinv, g->tr, stream)) return rc;
+        if (int rc = build_schedule(n_nodes, g->tr, stream)) return rc;
+        SG_HIP(hipStreamSynchronize(stream));
+    }
+
+    const int64_t slots = g->fwd.n_slots > g->tr.n_slots ? g->fwd.n_slots : g->tr.n_slots;
+    if (slots > 0) {
+        DevBuf scratch;
+        if (int rc = scratch.alloc((size_t)slots * SCRATCH_COLS * sizeof(float))) return rc;
+        g->scratch = scratch.release<float>();
+    }
+    SG_HIP(hipStreamSynchronize(stream));
+    guard.g = nullptr;
+    *out = g;
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_graph_view(const slicegcn_graph *g, slicegcn_csr_view *view)
+{
+    SG_REQUIRE(g && view, SLICEGCN_EINVAL, "graph_view: NULL argument");
+    view->n_nodes = g->n;
+    view->nnz = g->nnz;
+    view->rowptr = g->fwd.rowptr;
+    view->colidx = g->fwd.colidx;
+    view->deg = g->deg;
+    view->dinv = g->dinv;
+    view->vals = g->fwd.vals;
+    view->symmetric = g->symmetric;
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_graph_destroy(slicegcn_graph *g)
+{
+    if (!g) return SLICEGCN_OK;
+    if (!g->symmetric) free_csr(g->tr, true);
+    free_csr(g->fwd, true);
+    (void)hipFree(g->deg);
+    (void)hipFree(g->dinv);
+    (void)hipFree(g->scratch);
+    delete g;
+    return SLICEGCN_OK;
+}

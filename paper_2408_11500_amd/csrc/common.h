@@ -1,0 +1,102 @@
+// Internal declarations shared by the translation units of libslicegcn (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "slicegcn.h"
+
+namespace slicegcn {
+
+// ---- error plumbing ------------------------------------------------------------------
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+
+#define SG_REQUIRE(cond, code, ...)        \
+    do {                                   \
+        if (!(cond)) {                     \
+            ::slicegcn::set_error(__VA_ARGS__); \
+            return (code);                 \
+        }                                  \
+    } while (0)
+
+#define SG_HIP(call)                                                                       \
+    do {                                                                                   \
+        hipError_t sg_e_ = (call);                                                         \
+        if (sg_e_ != hipSuccess) {                                                         \
+            ::slicegcn::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(sg_e_), \
+                                  __FILE__, __LINE__);                                     \
+            return sg_e_ == hipErrorOutOfMemory ? SLICEGCN_ENOMEM : SLICEGCN_EHIP;         \
+        }                                                                                  \
+    } while (0)
+
+#define SG_LAUNCH_CHECK() SG_HIP(hipGetLastError())
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- aggregation schedule -------------------------------------------------------------
+// Rows with more than LONG_ROW stored entries are cut into segments of at most SEG_NNZ
+// entries, one wavefront each; a row cut into several segments gets one partial-sum slot per
+// segment and is finished by a fix-up pass that adds the slots in order.
+constexpr int LONG_ROW = 32;
+constexpr int SEG_NNZ = 2048;
+constexpr int SCRATCH_COLS = 256; // columns one aggregation pass covers (= floats per slot)
+
+struct Segment { // 16 bytes, read as one int4
+    int32_t row;
+    int32_t beg;
+    int32_t end;
+    int32_t dst; // >= 0: final (write the row); < 0: partial slot index -(dst+1)
+};
+
+struct FixRow { // a row whose segments went to partial slots [slot_beg, slot_end)
+    int32_t row;
+    int32_t slot_beg;
+    int32_t slot_end;
+    int32_t pad;
+};
+
+struct Csr {
+    int32_t *rowptr = nullptr;
+    int32_t *colidx = nullptr;
+    float *vals = nullptr;
+    Segment *segs = nullptr;
+    FixRow *fix = nullptr;
+    int64_t n_segs = 0;
+    int64_t n_fix = 0;
+    int64_t n_slots = 0;
+};
+
+} // namespace slicegcn
+
+struct slicegcn_graph {
+    int64_t n = 0;
+    int64_t nnz = 0;
+    int symmetric = 0;
+    int device = 0;
+    int32_t *deg = nullptr;
+    float *dinv = nullptr;
+    slicegcn::Csr fwd;  // A^
+    slicegcn::Csr tr;   // A^^T (arrays alias fwd when the pattern is symmetric)
+    float *scratch = nullptr; // max(n_slots) x SCRATCH_COLS partial sums of cut rows
+};
+
+namespace slicegcn {
+
+// spmm.hip: Y[:, 0:width] = M X (+ Add), M given by `m`.  Add may alias Y.
+int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
+                float *Y, int64_t ldy, const float *Add, int64_t ldadd, hipStream_t stream);
+
+// dense.hip: out[j] = sum over rows of M[r, j] (fp32 per row block, fp64 across blocks)
+int launch_colsum(const float *M, int64_t ld, int64_t n, int32_t w, float *out, float *ws, hipStream_t stream);
+size_t colsum_workspace_bytes(int64_t n, int32_t w);
+
+// build_csr.hip
+int build_schedule(int64_t n, Csr &m, hipStream_t stream);
+void free_csr(Csr &m, bool owns_pattern);
+
+} // namespace slicegcn

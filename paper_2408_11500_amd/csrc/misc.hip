@@ -1,0 +1,179 @@
+// Host-side slice strategy, direct feature slicing, slice encoding + concatenation and the
+// error-text plumbing of the C ABI.
+#include "common.h"
+
+#include <cstdarg>
+
+namespace slicegcn {
+
+namespace {
+thread_local char g_err[512] = "";
+}
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+// dst[r, c] = src[r, c] (+ e[c]) for c < w, 0 for w <= c < w_pad.  One thread per element of
+// the padded destination row, rows strided over the grid.
+__global__ __launch_bounds__(256) void copy_cols_kernel(const float *__restrict__ src, int64_t lds_, float *__restrict__ dst,
+                                                        int64_t ldd, int64_t n, int32_t w, int32_t w_pad,
+                                                        const float *__restrict__ e)
+{
+    const int64_t total = n * (int64_t)w_pad;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t r = t / w_pad;
+        const int c = (int)(t - r * w_pad);
+        float v = 0.f;
+        if (c < w) {
+            v = src[r * lds_ + c];
+            if (e) v += e[c];
+        }
+        dst[r * ldd + c] = v;
+    }
+}
+
+inline unsigned grid_for(int64_t total)
+{
+    const int64_t b = (total + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : (b > 1048576 ? 1048576 : b));
+}
+
+} // namespace
+} // namespace slicegcn
+
+using namespace slicegcn;
+
+extern "C" int slicegcn_slice_strategy(int32_t in_d, int32_t p, double slice_size_scale,
+                                       int32_t *starts, int32_t *ends, int32_t *slice_size)
+{
+    SG_REQUIRE(starts && ends && slice_size, SLICEGCN_EINVAL, "slice_strategy: NULL output");
+    SG_REQUIRE(in_d >= 1 && p >= 1 && p <= in_d, SLICEGCN_EINVAL, "slice_strategy: need 1 <= p <= in_d (p=%d, in_d=%d)", p, in_d);
+    SG_REQUIRE(slice_size_scale > 0.0, SLICEGCN_EINVAL, "slice_strategy: slice_size_scale must be positive");
+    const int32_t size = in_d / p + (in_d % p != 0);
+    const double scaled = (double)size * slice_size_scale;
+    SG_REQUIRE(scaled >= 1.0 && scaled <= (double)in_d, SLICEGCN_EINVAL,
+               "slice_strategy: scaled slice width %.3f outside [1, in_d]", scaled);
+    const int64_t width = (int64_t)scaled; // truncation, as the algorithm's int() does
+    for (int32_t i = 0; i < p; ++i) {
+        int64_t s = (int64_t)i * size, e = s + width;
+        if (e > in_d) { // the slice that passes the end moves left to end at in_d
+            s -= e - in_d;
+            e = in_d;
+        }
+        SG_REQUIRE(s >= 0, SLICEGCN_EINVAL, "slice_strategy: slice %d would start before column 0", i);
+        starts[i] = (int32_t)s;
+        ends[i] = (int32_t)e;
+    }
+    *slice_size = size;
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, int32_t start, int32_t end,
+                                      float *Xs, int64_t ldxs, void *stream)
+{
+    SG_REQUIRE(X && Xs, SLICEGCN_EINVAL, "slice_feature: NULL pointer");
+    SG_REQUIRE(n >= 1, SLICEGCN_EINVAL, "slice_feature: n < 1");
+    SG_REQUIRE(start >= 0 && start < end && end <= ldx, SLICEGCN_EINVAL,
+               "slice_feature: need 0 <= start < end <= ldx (start=%d, end=%d, ldx=%lld)", start, end, (long long)ldx);
+    SG_REQUIRE(ldxs >= end - start, SLICEGCN_EINVAL, "slice_feature: ldxs smaller than the slice width");
+    SG_REQUIRE(ldxs <= INT32_MAX, SLICEGCN_EINVAL, "slice_feature: ldxs too large");
+    copy_cols_kernel<<<grid_for(n * ldxs), 256, 0, as_stream(stream)>>>(X + start, ldx, Xs, ldxs, n, end - start,
+                                                                        (int32_t)ldxs, nullptr);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t *lds, const int32_t *widths,
+                               const float *E, int64_t lde, int64_t n, float *H, int64_t ldh, void *stream)
+{
+    SG_REQUIRE(Hs && lds && widths && H, SLICEGCN_EINVAL, "concat: NULL pointer");
+    SG_REQUIRE(k >= 1 && n >= 1, SLICEGCN_EINVAL, "concat: k and n must be >= 1");
+    int64_t total = 0;
+    int32_t wmax = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        SG_REQUIRE(Hs[i] != nullptr, SLICEGCN_EINVAL, "concat: Hs[%d] is NULL", i);
+        SG_REQUIRE(widths[i] >= 1 && lds[i] >= widths[i], SLICEGCN_EINVAL, "concat: bad width or ld of slice %d", i);
+        total += widths[i];
+        wmax = widths[i] > wmax ? widths[i] : wmax;
+    }
+    SG_REQUIRE(total <= ldh, SLICEGCN_EINVAL, "concat: sum of widths %lld exceeds ldh %lld", (long long)total, (long long)ldh);
+    SG_REQUIRE(E == nullptr || lde >= wmax, SLICEGCN_EINVAL, "concat: lde smaller than the widest slice");
+    int64_t off = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        const bool in_place = Hs[i] == H + off && lds[i] == ldh;
+        if (!(in_place && E == nullptr)) {
+            copy_cols_kernel<<<grid_for(n * widths[i]), 256, 0, as_stream(stream)>>>(
+                Hs[i], lds[i], H + off, ldh, n, widths[i], widths[i], E ? E + (int64_t)i * lde : nullptr);
+            SG_LAUNCH_CHECK();
+        }
+        off += widths[i];
+    }
+    return SLICEGCN_OK;
+}
+
+extern "C" size_t slicegcn_concat_bwd_workspace_bytes(int64_t n, int32_t k, const int32_t *widths)
+{
+    if (n < 1 || k < 1 || !widths) return 0;
+    int32_t wmax = 0;
+    for (int32_t i = 0; i < k; ++i) wmax = widths[i] > wmax ? widths[i] : wmax;
+    return (size_t)round_up((int64_t)colsum_workspace_bytes(n, wmax), 256);
+}
+
+extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, const int32_t *widths,
+                                   float *const *dHs, const int64_t *lds, float *dE, int64_t lde,
+                                   void *ws, size_t ws_bytes, void *stream)
+{
+    SG_REQUIRE(dH && widths, SLICEGCN_EINVAL, "concat_bwd: NULL pointer");
+    SG_REQUIRE(k >= 1 && n >= 1, SLICEGCN_EINVAL, "concat_bwd: k and n must be >= 1");
+    int64_t total = 0;
+    int32_t wmax = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        SG_REQUIRE(widths[i] >= 1, SLICEGCN_EINVAL, "concat_bwd: width of slice %d < 1", i);
+        if (dHs && dHs[i]) SG_REQUIRE(lds && lds[i] >= widths[i], SLICEGCN_EINVAL, "concat_bwd: bad ld of slice %d", i);
+        total += widths[i];
+        wmax = widths[i] > wmax ? widths[i] : wmax;
+    }
+    SG_REQUIRE(total <= ldh, SLICEGCN_EINVAL, "concat_bwd: sum of widths exceeds ldh");
+    if (dE) {
+        SG_REQUIRE(lde >= wmax, SLICEGCN_EINVAL, "concat_bwd: lde smaller than the widest slice");
+        const size_t need = slicegcn_concat_bwd_workspace_bytes(n, k, widths);
+        SG_REQUIRE(ws && ws_bytes >= need, SLICEGCN_EWORKSPACE, "concat_bwd: workspace of %zu bytes, %zu needed", ws_bytes, need);
+    }
+    int64_t off = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        if (dHs && dHs[i] && !(dHs[i] == dH + off && lds[i] == ldh)) {
+            copy_cols_kernel<<<grid_for(n * widths[i]), 256, 0, as_stream(stream)>>>(dH + off, ldh, dHs[i], lds[i], n,
+                                                                                     widths[i], widths[i], nullptr);
+            SG_LAUNCH_CHECK();
+        }
+        if (dE)
+            if (int rc = launch_colsum(dH + off, ldh, n, widths[i], dE + (int64_t)i * lde, static_cast<float *>(ws),
+                                       as_stream(stream)))
+                return rc;
+        off += widths[i];
+    }
+    return SLICEGCN_OK;
+}
+
+extern "C" const char *slicegcn_strerror(int status)
+{
+    switch (status) {
+    case SLICEGCN_OK: return "ok";
+    case SLICEGCN_EINVAL: return "invalid argument";
+    case SLICEGCN_ERANGE: return "value out of range";
+    case SLICEGCN_ENOMEM: return "out of memory";
+    case SLICEGCN_EHIP: return "HIP runtime error";
+    case SLICEGCN_EUNSUPPORTED: return "unsupported request";
+    case SLICEGCN_EWORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+extern "C" const char *slicegcn_last_error(void) { return g_err; }

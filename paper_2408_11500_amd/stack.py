@@ -1,0 +1,100 @@
+"""Call sequence of one full-batch pass over k feature slices (the inner loops of the paper's
+training algorithm): for every slice, L layer evaluations, then slice encoding + CONCAT, and
+the same chain backwards.  This module only owns buffers (torch device tensors) and orders the
+library calls; every arithmetic step is a kernel of ``libslicegcn.so``.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+def padded_ld(width: int) -> int:
+    """Leading dimension for a slice operand: rows start on 128-byte boundaries when narrow
+    (one row of a <= 32-wide slice is one cache line), on 64-byte boundaries otherwise."""
+    q = 32 if width <= 32 else 16
+    return (width + q - 1) // q * q
+
+
+class SliceStack:
+    def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
+                 device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU):
+        self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
+        self.w0, self.hs = first_width, slice_hidden
+        self.dev = torch.device(device)
+        self.act_last = act_last
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.widths = [(first_width if l == 0 else slice_hidden, slice_hidden) for l in range(layers)]
+        # inputs
+        self.X = [torch.zeros((n_nodes, padded_ld(first_width)), **f32) for _ in range(k)]
+        # parameters and their gradients: [slice][layer] -> dict
+        self.params = [[None] * layers for _ in range(k)]
+        self.grads = [[None] * layers for _ in range(k)]
+        self.E = torch.zeros((k, slice_hidden), **f32) if slice_encoding else None
+        self.dE = torch.zeros((k, slice_hidden), **f32) if slice_encoding else None
+        # activations kept for the backward pass
+        self.H = [[torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(layers - 1)] for _ in range(k)]
+        self.Z = [[torch.empty((n_nodes, padded_ld(wi)), **f32) for (wi, _) in self.widths] for _ in range(k)]
+        mw = (slice_hidden + 31) // 32
+        self.mask = [[torch.zeros((n_nodes, mw), dtype=torch.int32, device=self.dev) for _ in range(layers)] for _ in range(k)]
+        self.Hcat = torch.empty((n_nodes, k * slice_hidden), **f32)
+        # backward scratch
+        self.dbuf = [torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
+        ws = 0
+        for l, (wi, wo) in enumerate(self.widths):
+            ws = max(ws, B.slicegcn_layer_bwd_workspace_bytes(n_nodes, wi, wo, l > 0))
+        ws = max(ws, B.slicegcn_concat_bwd_workspace_bytes(n_nodes, [slice_hidden] * k))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    # ---------------------------------------------------------------------------------
+    def set_params(self, i: int, l: int, W_agg, b, W_self, b_self):
+        wi, wo = self.widths[l]
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.params[i][l] = dict(W_agg=W_agg.to(**f32).contiguous(), b=b.to(**f32).contiguous(),
+                                 W_self=None if W_self is None else W_self.to(**f32).contiguous(),
+                                 b_self=None if b_self is None else b_self.to(**f32).contiguous())
+        self.grads[i][l] = dict(dW_agg=torch.empty((wi, wo), **f32), db=torch.empty(wo, **f32),
+                                dW_self=torch.empty((wi, wo), **f32) if W_self is not None else None,
+                                db_self=torch.empty(wo, **f32) if W_self is not None else None)
+
+    def hin(self, i: int, l: int) -> torch.Tensor:
+        wi = self.widths[l][0]
+        return (self.X[i] if l == 0 else self.H[i][l - 1])[:, :wi]
+
+    def hout(self, i: int, l: int) -> torch.Tensor:
+        if l == self.L - 1:
+            return self.Hcat[:, i * self.hs:(i + 1) * self.hs]
+        return self.H[i][l][:, :self.hs]
+
+    def act(self, l: int) -> int:
+        return self.act_last if l == self.L - 1 else B.ACT_RELU
+
+    # ---------------------------------------------------------------------------------
+    def forward_slice(self, i: int):
+        for l in range(self.L):
+            p = self.params[i][l]
+            wi = self.widths[l][0]
+            B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], p["b_self"], self.hout(i, l),
+                                 self.Z[i][l][:, :wi], self.mask[i][l], act=self.act(l))
+
+    def forward(self) -> torch.Tensor:
+        for i in range(self.k):
+            self.forward_slice(i)
+        # the last layer of every slice already stored into its column block: encode in place
+        B.slicegcn_concat([self.hout(i, self.L - 1) for i in range(self.k)], self.E, self.Hcat)
+        return self.Hcat
+
+    def backward(self, dH: torch.Tensor):
+        if self.E is not None:
+            B.slicegcn_concat_bwd(dH, [self.hs] * self.k, dE=self.dE, ws=self.ws)
+        for i in range(self.k):
+            g_out = dH[:, i * self.hs:(i + 1) * self.hs]  # CONCAT backward is a column view
+            for l in reversed(range(self.L)):
+                p, gr = self.params[i][l], self.grads[i][l]
+                wi = self.widths[l][0]
+                g_in = self.dbuf[l % 2][:, :wi] if l > 0 else None  # raw features need no gradient
+                B.slicegcn_layer_bwd(self.g, self.hin(i, l), p["W_agg"], p["W_self"], self.Z[i][l][:, :wi], self.mask[i][l],
+                                     g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws,
+                                     act=self.act(l))
+                g_out = g_in
