@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the SliceGCN hot path on one MI355X.
+
+A step is one full-batch forward + backward pass over all k feature slices at their real
+per-slice shapes: k x L layer evaluations (aggregation + dense transform), slice encoding +
+concatenation, and the same chain backwards, with a seeded synthetic upstream gradient (no
+optimiser step).  Inputs are resident in HBM before the timed region starts.
+
+The headline value is the slice aggregation (SpMM) rate 2*nnz*F_s / t at the slice width
+F_s, with t the average duration of that kernel measured with HIP events inside the timed
+steps; ``ms_per_step`` is the whole fwd+bwd pass.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg: str):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def spmm_bytes(n: int, nnz: int, w: int, with_add: bool = False) -> int:
+    """Algorithmic HBM bytes of one aggregation call: 4 B column index + 4 B value per stored
+    entry, 4 B per row pointer, each input row read once and each output row written once."""
+    return 8 * nnz + 4 * (n + 1) + 8 * n * w + (4 * n * w if with_add else 0)
+
+
+def cpu_baseline(w, edges_src, edges_dst, Xs_host, width: int, frac: int):
+    """The fp64 oracle's aggregation timed on the host, on the sub-workload made of every edge
+    incident to the first n/frac nodes (all N rows and the full N x width slice stay)."""
+    import numpy as np
+    import oracle
+    n_s = max(1, w.n_nodes // frac)
+    keep = (edges_src < n_s) | (edges_dst < n_s)
+    s = edges_src[keep].cpu().numpy()
+    d = edges_dst[keep].cpu().numpy()
+    t0 = time.perf_counter()
+    g = oracle.build_norm_csr(s, d, w.n_nodes)
+    t_build = time.perf_counter() - t0
+    X64 = np.ascontiguousarray(Xs_host, dtype=np.float64)
+    t0 = time.perf_counter()
+    oracle.spmm(g, X64)
+    t = time.perf_counter() - t0
+    return {"value": 2.0 * g.nnz * width / t / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle aggregation over the sub-graph of all edges incident to nodes [0, {n_s}) "
+                      f"(nnz {g.nnz} incl. self loops, all {w.n_nodes} rows, width {width}): {t:.2f} s; "
+                      f"oracle CSR build of the sample {t_build:.2f} s (not in the rate)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-frac", type=int, default=16, help="oracle leg uses edges incident to n/frac nodes")
+    ap.add_argument("--spmm-only", type=int, default=0, help="time only this many round-robin slice aggregations per step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all k slices execute sequentially on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from synth import configs, model
+    import paper_2408_11500_amd as sg
+    from paper_2408_11500_amd.stack import SliceStack
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.WORKLOADS[args.workload]
+
+    log(f"generating {w.name}: N={w.n_nodes} M_und={w.m_und}")
+    t0 = time.perf_counter()
+    src, dst = configs.edges(w, device=dev)
+    torch.cuda.synchronize()
+    log(f"edges in {time.perf_counter() - t0:.1f} s")
+    t0 = time.perf_counter()
+    g = sg.slicegcn_build_norm_csr(src, dst, w.n_nodes)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    view = g.view()
+    assert view.nnz == w.nnz, (view.nnz, w.nnz)
+    log(f"build_norm_csr {build_ms:.1f} ms, nnz={view.nnz}")
+
+    slices, width = sg.slicegcn_slice_strategy(w.feat, w.k)
+    hs, L, k, n = w.slice_hidden, w.layers, w.k, w.n_nodes
+    st = SliceStack(g, n, k, width, hs, L, device=dev)
+    X = configs.features(w, device=dev)
+    for i, (a, b) in enumerate(slices):
+        sg.slicegcn_slice_feature(X, a, b, st.X[i])
+        for l, (wi, wo) in enumerate(st.widths):
+            st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, device=dev))
+    del X
+    st.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, device=dev, std=0.1))
+    dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * hs, device=dev)
+    torch.cuda.synchronize()
+    log("inputs resident")
+
+    Yspmm = torch.empty_like(st.Z[0][0]) if args.spmm_only else None
+
+    def step():
+        if args.spmm_only:
+            for j in range(args.spmm_only):   # round-robin over the slices, as in the real pass
+                sg.slicegcn_spmm_slice(g, st.X[j % k][:, :width], Yspmm[:, :width])
+        else:
+            st.forward()
+            st.backward(dH)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sg.slicegcn_profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = sg.slicegcn_profile_end()
+    ms_per_step = elapsed * 1e3 / args.steps
+    log(f"{args.steps} steps, {ms_per_step:.2f} ms/step")
+
+    kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt} for kind, wd, cnt, tot in prof}
+    dom = next(((cnt, tot) for kind, wd, cnt, tot in prof if kind == "spmm" and wd == width), None)
+    if dom is None:
+        print("bench.py: no aggregation at the slice width was timed", file=sys.stderr)
+        sys.exit(1)
+    avg_s = dom[1] / dom[0] / 1e3
+    nbytes = spmm_bytes(n, view.nnz, width)
+    achieved = nbytes / avg_s / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_hbm_traffic.json")
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+    out = {
+        "metric": "slice_spmm_gflops", "value": 2.0 * view.nnz * width / avg_s / 1e9, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={n}, nnz={view.nnz} (R-MAT, symmetrised + self loops), F={w.feat} in k={k} "
+                               f"slices of {width}, {L} layers, per-slice hidden {hs}, full-batch fwd+bwd"
+                               + (" [aggregation only]" if args.spmm_only else ""),
+                   "n_nodes": n, "nnz": view.nnz, "k": k, "slice_width": width, "slice_hidden": hs, "layers": L},
+        "epoch_ms": None if args.spmm_only else ms_per_step,
+        "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,
+        "spmm_avg_ms": avg_s * 1e3, "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "spmm_kernel (slice aggregation)",
+                     "algorithmic_bytes_per_launch": nbytes},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample")
+        Xs_host = st.X[0][:, :width].cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(w, src, dst, Xs_host, width, args.cpu_sample_frac)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

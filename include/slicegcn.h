@@ -210,6 +210,29 @@ int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, cons
                         float *const *dHs, const int64_t *lds, float *dE, int64_t lde,
                         void *ws, size_t ws_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the
+ * stream each kernel is launched on.  Between slicegcn_profile_begin and slicegcn_profile_end
+ * every kernel group the library launches is bracketed by an event pair.  _end synchronises
+ * the device, adds the elapsed times up by (kind, width) and writes at most `capacity` entries
+ * to the HOST array `entries`; *count receives the number of distinct (kind, width) pairs.
+ * Process-wide state; not meant to be used from several threads at once.
+ * ------------------------------------------------------------------------------------- */
+#define SLICEGCN_PROF_SPMM 0        /* aggregation pass (main kernel + fix-up); width = operand width */
+#define SLICEGCN_PROF_DENSE_FWD 1   /* forward weight products + epilogue; width = w_out              */
+#define SLICEGCN_PROF_DENSE_BWD 2   /* backward dZ / self products; width = w_in                      */
+#define SLICEGCN_PROF_GRAD_REDUCE 3 /* weight-gradient reductions; width = w_out                      */
+#define SLICEGCN_PROF_CONCAT 4      /* slice encoding / concat / their backward; width = slice width  */
+#define SLICEGCN_PROF_SPMM_ADD 5    /* aggregation pass fused with an addend (backward); operand width */
+typedef struct {
+    int32_t kind;
+    int32_t width;
+    int64_t launches;
+    double total_ms;
+} slicegcn_profile_entry;
+int slicegcn_profile_begin(void);
+int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t capacity, int32_t *count);
+
 const char *slicegcn_strerror(int status);
 const char *slicegcn_last_error(void);
 

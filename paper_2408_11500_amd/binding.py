@@ -28,8 +28,10 @@ EXPORTS = [
     "slicegcn_slice_strategy", "slicegcn_build_norm_csr", "slicegcn_graph_view", "slicegcn_graph_destroy",
     "slicegcn_slice_feature", "slicegcn_spmm_slice", "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
-    "slicegcn_strerror", "slicegcn_last_error",
+    "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_begin", "slicegcn_profile_end",
 ]
+
+PROF_KINDS = {0: "spmm", 1: "dense_fwd", 2: "dense_bwd", 3: "grad_reduce", 4: "concat", 5: "spmm_add"}
 
 
 class SliceGCNError(RuntimeError):
@@ -54,6 +56,11 @@ class _LayerParams(ctypes.Structure):
 
 class _LayerSaved(ctypes.Structure):
     _fields_ = [("Z", ctypes.c_void_p), ("ldz", ctypes.c_int64), ("mask", ctypes.c_void_p), ("mask_words", ctypes.c_int64)]
+
+
+class _ProfileEntry(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("width", ctypes.c_int32), ("launches", ctypes.c_int64),
+                ("total_ms", ctypes.c_double)]
 
 
 class _LayerGrads(ctypes.Structure):
@@ -89,6 +96,7 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_concat_bwd_workspace_bytes.argtypes = [i64, i32, vp]
         L.slicegcn_concat_bwd_workspace_bytes.restype = sz
         L.slicegcn_concat_bwd.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, i64, vp, sz, vp]
+        L.slicegcn_profile_end.argtypes = [ctypes.POINTER(_ProfileEntry), i32, ctypes.POINTER(i32)]
         L.slicegcn_strerror.argtypes = [ctypes.c_int]
         L.slicegcn_strerror.restype = ctypes.c_char_p
         L.slicegcn_last_error.restype = ctypes.c_char_p
@@ -324,3 +332,16 @@ def slicegcn_concat_bwd(dH: torch.Tensor, widths, dHs=None, dE=None, ws=None):
                                      ctypes.addressof(lds) if lds is not None else None, pe, lde,
                                      ws.data_ptr() if ws is not None else None,
                                      ws.numel() * ws.element_size() if ws is not None else 0, _stream()))
+
+
+def slicegcn_profile_begin():
+    _check(lib().slicegcn_profile_begin())
+
+
+def slicegcn_profile_end(capacity: int = 64):
+    """[(kind name, width, launches, total_ms)] of the kernels launched since profile_begin."""
+    arr = (_ProfileEntry * capacity)()
+    count = ctypes.c_int32(0)
+    _check(lib().slicegcn_profile_end(arr, capacity, ctypes.byref(count)))
+    return [(PROF_KINDS.get(e.kind, str(e.kind)), int(e.width), int(e.launches), float(e.total_ms))
+            for e in arr[:min(count.value, capacity)]]

@@ -95,6 +95,16 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
 int launch_colsum(const float *M, int64_t ld, int64_t n, int32_t w, float *out, float *ws, hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t n, int32_t w);
 
+// misc.hip: brackets the launches of its scope with an event pair while profiling is on
+struct ProfScope {
+    ProfScope(int kind, int width, hipStream_t stream);
+    ~ProfScope();
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
+    int slot_;
+    hipStream_t stream_;
+};
+
 // build_csr.hip
 int build_schedule(int64_t n, Csr &m, hipStream_t stream);
 void free_csr(Csr &m, bool owns_pattern);

@@ -390,6 +390,7 @@ extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_
     a.O1 = Hout; a.ldo1 = ldo; a.O2 = nullptr; a.ldo2 = 0;
     a.mask = desc->act == SLICEGCN_ACT_RELU ? saved->mask : nullptr; a.mask_words = saved->mask_words;
     a.n = g->n; a.K = desc->w_in; a.Nout = desc->w_out; a.ldw = desc->w_out; a.act = desc->act;
+    ProfScope prof(SLICEGCN_PROF_DENSE_FWD, desc->w_out, stream);
     return launch_pair<false>(a, stream);
 }
 
@@ -426,6 +427,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
     const int64_t nb = red_blocks(g->n);
     const int32_t stride = 2 * w_in * w_out + 2 * w_out;
     {
+        ProfScope prof(SLICEGCN_PROF_GRAD_REDUCE, w_out, stream);
         ReduceArgs r;
         r.Z = saved->Z; r.ldz = saved->ldz;
         r.Hin = params->W_self ? Hin : nullptr; r.ldi = ldi;
@@ -460,7 +462,10 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         a.O2 = params->W_self ? dHin : nullptr; a.ldo2 = ldgi;
         a.mask = const_cast<uint32_t *>(mask); a.mask_words = saved->mask_words;
         a.n = g->n; a.K = w_out; a.Nout = w_in; a.ldw = w_out; a.act = desc->act;
-        if (int rc = launch_pair<true>(a, stream)) return rc;
+        {
+            ProfScope prof(SLICEGCN_PROF_DENSE_BWD, w_in, stream);
+            if (int rc = launch_pair<true>(a, stream)) return rc;
+        }
         // padding columns of dZ are never read as data: the aggregation masks them on store
         if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, stream)) return rc;
     }

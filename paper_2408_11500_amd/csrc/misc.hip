@@ -3,6 +3,10 @@
 #include "common.h"
 
 #include <cstdarg>
+#include <map>
+#include <mutex>
+#include <utility>
+#include <vector>
 
 namespace slicegcn {
 
@@ -16,6 +20,36 @@ void set_error(const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+// ---- per-kernel event timing --------------------------------------------------------------
+namespace {
+struct ProfRecord { int kind, width; hipEvent_t start, stop; bool closed; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+} // namespace
+
+ProfScope::ProfScope(int kind, int width, hipStream_t stream) : slot_(-1), stream_(stream)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof_on) return;
+    ProfRecord r{kind, width, nullptr, nullptr, false};
+    if (hipEventCreate(&r.start) != hipSuccess) return;
+    if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+    (void)hipEventRecord(r.start, stream);
+    g_prof.push_back(r);
+    slot_ = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (slot_ < (int)g_prof.size() && !g_prof[slot_].closed) {
+        (void)hipEventRecord(g_prof[slot_].stop, stream_);
+        g_prof[slot_].closed = true;
+    }
 }
 
 namespace {
@@ -106,6 +140,7 @@ extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t 
     SG_REQUIRE(total <= ldh, SLICEGCN_EINVAL, "concat: sum of widths %lld exceeds ldh %lld", (long long)total, (long long)ldh);
     SG_REQUIRE(E == nullptr || lde >= wmax, SLICEGCN_EINVAL, "concat: lde smaller than the widest slice");
     int64_t off = 0;
+    ProfScope prof(SLICEGCN_PROF_CONCAT, wmax, as_stream(stream));
     for (int32_t i = 0; i < k; ++i) {
         const bool in_place = Hs[i] == H + off && lds[i] == ldh;
         if (!(in_place && E == nullptr)) {
@@ -147,6 +182,7 @@ extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int6
         SG_REQUIRE(ws && ws_bytes >= need, SLICEGCN_EWORKSPACE, "concat_bwd: workspace of %zu bytes, %zu needed", ws_bytes, need);
     }
     int64_t off = 0;
+    ProfScope prof(SLICEGCN_PROF_CONCAT, wmax, as_stream(stream));
     for (int32_t i = 0; i < k; ++i) {
         if (dHs && dHs[i] && !(dHs[i] == dH + off && lds[i] == ldh)) {
             copy_cols_kernel<<<grid_for(n * widths[i]), 256, 0, as_stream(stream)>>>(dH + off, ldh, dHs[i], lds[i], n,
@@ -159,6 +195,47 @@ extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int6
                 return rc;
         off += widths[i];
     }
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_profile_begin(void)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    for (auto &r : g_prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    g_prof.clear();
+    g_prof_on = true;
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t capacity, int32_t *count)
+{
+    SG_REQUIRE(count != nullptr && (entries != nullptr || capacity == 0), SLICEGCN_EINVAL, "profile_end: NULL output");
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof_on = false;
+    SG_HIP(hipDeviceSynchronize());
+    std::map<std::pair<int, int>, std::pair<int64_t, double>> sum;
+    for (auto &r : g_prof) {
+        float ms = 0.f;
+        if (r.closed && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            auto &e = sum[{r.kind, r.width}];
+            e.first += 1;
+            e.second += (double)ms;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+    int32_t i = 0;
+    for (auto &kv : sum) {
+        if (i < capacity) {
+            entries[i].kind = kv.first.first;
+            entries[i].width = kv.first.second;
+            entries[i].launches = kv.second.first;
+            entries[i].total_ms = kv.second.second;
+        }
+        ++i;
+    }
+    *count = i;
     return SLICEGCN_OK;
 }
 

@@ -216,6 +216,7 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
     const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
     a.vec_store = aligned16(Y) && (ldy % 4 == 0) && (!Add || (aligned16(Add) && ldadd % 4 == 0));
+    ProfScope prof(Add ? SLICEGCN_PROF_SPMM_ADD : SLICEGCN_PROF_SPMM, width, stream);
     const int V = vec_load ? 4 : 1;
     const int pass_cols = vec_load ? SCRATCH_COLS : 64;
     for (int32_t c0 = 0; c0 < width; c0 += pass_cols) {
