@@ -63,7 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-frac", type=int, default=16, help="oracle leg uses edges incident to n/frac nodes")
+    ap.add_argument("--cpu-sample-frac", type=int, default=1, help="oracle leg uses edges incident to n/frac nodes")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 4 GiB device copy (reference for HBM byte counters) and exit")
     ap.add_argument("--spmm-only", type=int, default=0, help="time only this many round-robin slice aggregations per step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,6 +85,22 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = synth.WORKLOADS[args.workload]
+
+    if args.copy_calibration:
+        rows, ld = 1 << 22, 256   # 2^30 floats = 4 GiB read + 4 GiB written by one plain copy kernel
+        a = torch.ones((rows, ld), dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            sg.slicegcn_slice_feature(a, 0, ld, b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            sg.slicegcn_slice_feature(a, 0, ld, b)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"copy_bytes_read": rows * ld * 4, "copy_bytes_written": rows * ld * 4, "ms": dt * 1e3,
+                          "GBps": 2 * rows * ld * 4 / dt / 1e9}))
+        return
 
     log(f"generating {w.name}: N={w.n_nodes} M_und={w.m_und}")
     t0 = time.perf_counter()
@@ -144,9 +162,12 @@ def main():
     nbytes = spmm_bytes(n, view.nnz, width)
     achieved = nbytes / avg_s / 1e9
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_hbm_traffic.json")
+    # HBM-side bytes per aggregation call from the committed rocprofv3 counter summary of this workload
+    tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_rocprofv3.md")
     if os.path.exists(tfile):
-        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+        import re
+        m = re.search(r"^hbm_bytes_per_launch = (\d+)", open(tfile).read(), flags=re.M)
+        traffic = int(m.group(1)) if m else None
     out = {
         "metric": "slice_spmm_gflops", "value": 2.0 * view.nnz * width / avg_s / 1e9, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
