@@ -8,7 +8,9 @@
 #include <rocprim/rocprim.hpp>
 
 #include <cstdarg>
+#include <cstdlib>
 #include <new>
+#include <vector>
 
 namespace slicegcn {
 
@@ -104,45 +106,118 @@ __global__ void swap_keys_kernel(const uint64_t *__restrict__ in, int64_t nnz, u
 }
 
 // ---- schedule ---------------------------------------------------------------------------
-__device__ inline int segments_of(int32_t d) { return d > LONG_ROW ? (d + SEG_NNZ - 1) / SEG_NNZ : 0; }
+// Per long row: the entries of column class c are [lower_bound(c * cw), lower_bound((c+1) * cw)).
+// counts layout: cnt[(2*c + kind) * (n+1) + row], kind 0 = wavefront items, 1 = lane-group items.
+struct RowCut {
+    int32_t lo[MAX_CLASSES + 1];
+};
 
-__global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, int64_t n,
-                                   int32_t *__restrict__ c_seg, int32_t *__restrict__ c_slot,
-                                   int32_t *__restrict__ c_fix)
+__device__ inline RowCut cut_row(const int32_t *__restrict__ colidx, int32_t beg, int32_t end, int n_classes, int32_t cw)
+{
+    RowCut rc;
+    rc.lo[0] = beg;
+    for (int c = 1; c < n_classes; ++c) {
+        const int32_t target = c * cw; // first column of class c (cw * n_classes >= n, so no overflow past n + cw)
+        int32_t lo = rc.lo[c - 1], hi = end;
+        while (lo < hi) {
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            if (colidx[mid] < target) lo = mid + 1; else hi = mid;
+        }
+        rc.lo[c] = lo;
+    }
+    for (int c = n_classes; c <= MAX_CLASSES; ++c) rc.lo[c] = end;
+    return rc;
+}
+
+__device__ inline int pieces_of(int32_t len) { return (len + SEG_NNZ - 1) / SEG_NNZ; }
+
+// The items of one row, in (class, piece) order.  F is called as f(cls, kind, beg, end) with
+// kind 0 = wavefront item, 1 = lane-group item.
+template <class F>
+__device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t r, int32_t beg, int32_t end,
+                                    int n_classes, int32_t cw, int32_t part_row, F f)
+{
+    const int32_t d = end - beg;
+    int total = 0;
+    if (d <= TINY_ROW) return 0;
+    const int own = (int)(r % n_classes);
+    if (d <= LONG_ROW) {
+        f(own, 1, beg, end);
+        return 1;
+    }
+    if (n_classes == 1 || d <= part_row) {
+        const int s = pieces_of(d);
+        const int32_t piece = (d + s - 1) / s; // equal cuts, the last one takes the remainder
+        for (int j = 0; j < s; ++j) f(own, 0, beg + j * piece, min(end, beg + (j + 1) * piece));
+        return s;
+    }
+    const RowCut rc = cut_row(colidx, beg, end, n_classes, cw);
+    for (int c = 0; c < n_classes; ++c) {
+        const int32_t b = rc.lo[c], e = rc.lo[c + 1], len = e - b;
+        if (len <= 0) continue;
+        if (len <= SMALL_ITEM) {
+            f(c, 1, b, e);
+            ++total;
+        } else {
+            const int s = pieces_of(len);
+            const int32_t piece = (len + s - 1) / s;
+            for (int j = 0; j < s; ++j) f(c, 0, b + j * piece, min(e, b + (j + 1) * piece));
+            total += s;
+        }
+    }
+    return total;
+}
+
+// counts layout: cnt[(2*c + kind) * (n+1) + row]
+__global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
+                                   int n_classes, int32_t cw, int32_t part_row, int32_t *__restrict__ cnt,
+                                   int32_t *__restrict__ c_slot, int32_t *__restrict__ c_fix)
 {
     const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (r > n) return;
-    int s = 0;
-    if (r < n) s = segments_of(rowptr[r + 1] - rowptr[r]);
-    c_seg[r] = s;
-    c_slot[r] = s > 1 ? s : 0;
-    c_fix[r] = s > 1 ? 1 : 0;
+    const int64_t stride = n + 1;
+    int32_t per[2 * MAX_CLASSES];
+    for (int t = 0; t < 2 * MAX_CLASSES; ++t) per[t] = 0;
+    int total = 0;
+    if (r < n)
+        total = for_each_item(colidx, r, rowptr[r], rowptr[r + 1], n_classes, cw, part_row,
+                              [&](int c, int kind, int32_t, int32_t) { per[2 * c + kind] += 1; });
+    for (int t = 0; t < 2 * n_classes; ++t) cnt[t * stride + r] = per[t];
+    c_slot[r] = total > 1 ? total : 0;
+    c_fix[r] = total > 1 ? 1 : 0;
 }
 
-__global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, int64_t n,
-                                  const int32_t *__restrict__ o_seg, const int32_t *__restrict__ o_slot,
-                                  const int32_t *__restrict__ o_fix,
-                                  Segment *__restrict__ segs, FixRow *__restrict__ fix)
+__global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
+                                  int n_classes, int32_t cw, int32_t part_row, const int32_t *__restrict__ off,
+                                  const int32_t *__restrict__ o_slot, const int32_t *__restrict__ o_fix,
+                                  Segment *__restrict__ items, FixRow *__restrict__ fix)
 {
     const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (r >= n) return;
+    const int64_t stride = n + 1;
     const int32_t beg = rowptr[r], end = rowptr[r + 1];
-    const int s = segments_of(end - beg);
-    if (s == 0) return;
-    const int32_t len = (end - beg + s - 1) / s; // equal cuts, last one takes the remainder
-    for (int j = 0; j < s; ++j) {
+    if (end - beg <= TINY_ROW) return;
+    // first pass: how many items (decides whether they write the row or partial slots)
+    const int total = for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [](int, int, int32_t, int32_t) {});
+    int32_t used[2 * MAX_CLASSES];
+    for (int t = 0; t < 2 * MAX_CLASSES; ++t) used[t] = 0;
+    int slot = o_slot[r]; // slots are handed out in (class, piece) order
+    for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [&](int c, int kind, int32_t b, int32_t e) {
         Segment sg;
         sg.row = (int32_t)r;
-        sg.beg = beg + j * len;
-        sg.end = min(end, beg + (j + 1) * len);
-        sg.dst = s == 1 ? (int32_t)r : -(o_slot[r] + j + 1);
-        segs[o_seg[r] + j] = sg;
-    }
-    if (s > 1) {
+        sg.beg = b;
+        sg.end = e;
+        sg.dst = total == 1 ? (int32_t)r : -(slot + 1);
+        const int t = 2 * c + kind;
+        items[off[t * stride + r] + used[t]] = sg;
+        used[t] += 1;
+        ++slot;
+    });
+    if (total > 1) {
         FixRow f;
         f.row = (int32_t)r;
         f.slot_beg = o_slot[r];
-        f.slot_end = o_slot[r] + s;
+        f.slot_end = o_slot[r] + total;
         f.pad = 0;
         fix[o_fix[r]] = f;
     }
@@ -187,6 +262,13 @@ int pattern_from_keys(const uint64_t *keys, int64_t nnz, int64_t n, const float 
 
 } // namespace
 
+static void free_schedule(Schedule &sc)
+{
+    (void)hipFree(sc.items);
+    (void)hipFree(sc.fix);
+    sc = Schedule();
+}
+
 void free_csr(Csr &m, bool owns_pattern)
 {
     if (owns_pattern) {
@@ -194,38 +276,78 @@ void free_csr(Csr &m, bool owns_pattern)
         (void)hipFree(m.colidx);
         (void)hipFree(m.vals);
     }
-    (void)hipFree(m.segs);
-    (void)hipFree(m.fix);
+    free_schedule(m.wide);
+    free_schedule(m.xcd);
     m = Csr();
 }
 
-int build_schedule(int64_t n, Csr &m, hipStream_t stream)
+int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStream_t stream)
 {
-    DevBuf cnt, off;
+    out = Schedule();
+    out.n_classes = n_classes;
     const size_t stride = (size_t)(n + 1);
-    if (int rc = cnt.alloc(3 * stride * sizeof(int32_t))) return rc;
-    if (int rc = off.alloc(3 * stride * sizeof(int32_t))) return rc;
-    int32_t *c = cnt.as<int32_t>(), *o = off.as<int32_t>();
-    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, n, c, c + stride, c + 2 * stride);
+    const size_t n_cnt = 2 * (size_t)n_classes * stride;
+    SG_REQUIRE(n_cnt <= (size_t)INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: schedule tables exceed int32 indexing");
+    const int32_t cw = (int32_t)((n + n_classes - 1) / n_classes); // columns per class
+    DevBuf cnt, off, aux;
+    if (int rc = cnt.alloc(n_cnt * sizeof(int32_t))) return rc;
+    if (int rc = off.alloc(n_cnt * sizeof(int32_t))) return rc;
+    if (int rc = aux.alloc(4 * stride * sizeof(int32_t))) return rc; // slot counts, fix counts and their scans
+    int32_t *c = cnt.as<int32_t>(), *o = off.as<int32_t>(), *x = aux.as<int32_t>();
+    const int32_t part_row = getenv("SLICEGCN_PART_ROW") ? atoi(getenv("SLICEGCN_PART_ROW")) : PART_ROW;
+    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cw, part_row, c, x, x + stride);
     SG_LAUNCH_CHECK();
-    for (int a = 0; a < 3; ++a)
-        if (int rc = scan_i32(c + a * stride, o + a * stride, n + 1, stream)) return rc;
-    int32_t totals[3];
-    for (int a = 0; a < 3; ++a)
-        SG_HIP(hipMemcpy(&totals[a], o + a * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
-    m.n_segs = totals[0];
-    m.n_slots = totals[1];
-    m.n_fix = totals[2];
-    DevBuf segs, fix;
-    if (int rc = segs.alloc((size_t)m.n_segs * sizeof(Segment))) return rc;
-    if (int rc = fix.alloc((size_t)m.n_fix * sizeof(FixRow))) return rc;
-    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, n, o, o + stride, o + 2 * stride,
-                                                         segs.as<Segment>(), fix.as<FixRow>());
+    if (int rc = scan_i32(c, o, (int64_t)n_cnt, stream)) return rc;
+    if (int rc = scan_i32(x, x + 2 * stride, n + 1, stream)) return rc;
+    if (int rc = scan_i32(x + stride, x + 3 * stride, n + 1, stream)) return rc;
+    // the scan runs over all (class, kind) tables back to back: table t starts at o[t * stride]
+    std::vector<int32_t> starts(2 * n_classes + 1);
+    for (int t = 0; t < 2 * n_classes; ++t)
+        SG_HIP(hipMemcpy(&starts[t], o + (size_t)t * stride, sizeof(int32_t), hipMemcpyDeviceToHost));
+    int32_t last_off = 0, last_cnt = 0, n_slots = 0, n_fix = 0;
+    SG_HIP(hipMemcpy(&last_off, o + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
+    SG_HIP(hipMemcpy(&last_cnt, c + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
+    SG_HIP(hipMemcpy(&n_slots, x + 2 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
+    SG_HIP(hipMemcpy(&n_fix, x + 3 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
+    starts[2 * n_classes] = last_off + last_cnt;
+    for (int cl = 0; cl < n_classes; ++cl) {
+        out.big_off[cl] = starts[2 * cl];
+        out.big_cnt[cl] = starts[2 * cl + 1] - starts[2 * cl];
+        out.small_off[cl] = starts[2 * cl + 1];
+        out.small_cnt[cl] = starts[2 * cl + 2] - starts[2 * cl + 1];
+    }
+    out.n_items = starts[2 * n_classes];
+    out.n_slots = n_slots;
+    out.n_fix = n_fix;
+    DevBuf items, fix;
+    if (int rc = items.alloc((size_t)out.n_items * sizeof(Segment))) return rc;
+    if (int rc = fix.alloc((size_t)out.n_fix * sizeof(FixRow))) return rc;
+    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cw, part_row, o, x + 2 * stride,
+                                                         x + 3 * stride, items.as<Segment>(), fix.as<FixRow>());
     SG_LAUNCH_CHECK();
     SG_HIP(hipStreamSynchronize(stream));
-    m.segs = segs.release<Segment>();
-    m.fix = fix.release<FixRow>();
+    out.items = items.release<Segment>();
+    out.fix = fix.release<FixRow>();
+    if (getenv("SLICEGCN_VERBOSE")) {
+        int64_t big = 0, small = 0;
+        for (int cl = 0; cl < n_classes; ++cl) { big += out.big_cnt[cl]; small += out.small_cnt[cl]; }
+        fprintf(stderr, "[slicegcn] schedule with %d class(es): %lld wavefront items, %lld lane-group items, %lld rows with "
+                        "several items, %lld partial-sum slots\n", n_classes, (long long)big, (long long)small,
+                (long long)out.n_fix, (long long)out.n_slots);
+    }
     return SLICEGCN_OK;
+}
+
+static int build_schedules(int64_t n, Csr &m, hipStream_t stream)
+{
+    if (int rc = build_schedule(n, m, 1, m.wide, stream)) return rc;
+    return build_schedule(n, m, MAX_CLASSES, m.xcd, stream);
+}
+
+static int64_t scratch_need(const Csr &m)
+{
+    const int64_t a = m.wide.n_slots * WIDE_SLOT_COLS, b = m.xcd.n_slots * XCD_SLOT_COLS;
+    return a > b ? a : b;
 }
 
 } // namespace slicegcn
@@ -320,7 +442,7 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         g->dinv = dinv.release<float>();
     }
     if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
-    if (int rc = build_schedule(n_nodes, g->fwd, stream)) return rc;
+    if (int rc = build_schedules(n_nodes, g->fwd, stream)) return rc;
 
     if (sym) {
         g->tr = g->fwd; // A^ is symmetric: the same arrays serve the transposed product
@@ -342,14 +464,15 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         SG_LAUNCH_CHECK();
         g->tr.rowptr = rowptr.release<int32_t>();
         if (int rc = pattern_from_keys(keys_c.as<uint64_t>(), nnz, n_nodes, g->dinv, g->tr, stream)) return rc;
-        if (int rc = build_schedule(n_nodes, g->tr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, g->tr, stream)) return rc;
         SG_HIP(hipStreamSynchronize(stream));
     }
 
-    const int64_t slots = g->fwd.n_slots > g->tr.n_slots ? g->fwd.n_slots : g->tr.n_slots;
-    if (slots > 0) {
+    const int64_t need_f = scratch_need(g->fwd), need_t = scratch_need(g->tr);
+    g->scratch_floats = need_f > need_t ? need_f : need_t;
+    if (g->scratch_floats > 0) {
         DevBuf scratch;
-        if (int rc = scratch.alloc((size_t)slots * SCRATCH_COLS * sizeof(float))) return rc;
+        if (int rc = scratch.alloc((size_t)g->scratch_floats * sizeof(float))) return rc;
         g->scratch = scratch.release<float>();
     }
     SG_HIP(hipStreamSynchronize(stream));

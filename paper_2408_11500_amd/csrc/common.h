@@ -39,12 +39,27 @@ inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- aggregation schedule -------------------------------------------------------------
-// Rows with more than LONG_ROW stored entries are cut into segments of at most SEG_NNZ
-// entries, one wavefront each; a row cut into several segments gets one partial-sum slot per
-// segment and is finished by a fix-up pass that adds the slots in order.
+// Rows are split by their number of stored entries d:
+//   d <= TINY_ROW            : handled whole, 64 consecutive rows per wavefront, in natural order;
+//   TINY_ROW < d <= LONG_ROW : one lane-group item (the whole row);
+//   d > LONG_ROW             : wavefront items of at most SEG_NNZ entries;
+//   d > PART_ROW (schedules with 8 classes only): the row is first cut by column class
+//       (8 contiguous column ranges; a row's entries of one class are contiguous because columns
+//       ascend); a class piece of at most SMALL_ITEM entries is a lane-group item, a longer one is
+//       cut into wavefront items.
+// Items of class c are executed by workgroups whose index is c modulo n_classes; with 8 classes
+// and the round-robin placement of workgroups over the 8 XCDs, each XCD's L2 only ever sees its
+// own eighth of the columns of the gathered operand for the partitioned rows.  Whole-row items
+// take class (row mod n_classes).  A row with several items gets one partial-sum slot per item
+// and is finished by a fix-up pass that adds the slots in order.
+constexpr int TINY_ROW = 4;
 constexpr int LONG_ROW = 32;
+constexpr int PART_ROW = 256;
+constexpr int SMALL_ITEM = 32;   // class pieces up to this many entries: one lane group; longer: wavefronts
 constexpr int SEG_NNZ = 2048;
-constexpr int SCRATCH_COLS = 256; // columns one aggregation pass covers (= floats per slot)
+constexpr int MAX_CLASSES = 8;
+constexpr int WIDE_SLOT_COLS = 256; // floats per slot, single-class schedule (any width, 256 columns per pass)
+constexpr int XCD_SLOT_COLS = 64;   // floats per slot, 8-class schedule (used for operands up to 64 wide)
 
 struct Segment { // 16 bytes, read as one int4
     int32_t row;
@@ -53,22 +68,30 @@ struct Segment { // 16 bytes, read as one int4
     int32_t dst; // >= 0: final (write the row); < 0: partial slot index -(dst+1)
 };
 
-struct FixRow { // a row whose segments went to partial slots [slot_beg, slot_end)
+struct FixRow { // a row whose items went to partial slots [slot_beg, slot_end)
     int32_t row;
     int32_t slot_beg;
     int32_t slot_end;
     int32_t pad;
 };
 
+struct Schedule {
+    int32_t n_classes = 0;
+    Segment *items = nullptr; // all items, ordered by (class, wavefront items before lane-group items, row, piece)
+    FixRow *fix = nullptr;
+    int32_t big_off[MAX_CLASSES] = {0}, big_cnt[MAX_CLASSES] = {0};
+    int32_t small_off[MAX_CLASSES] = {0}, small_cnt[MAX_CLASSES] = {0};
+    int64_t n_items = 0;
+    int64_t n_fix = 0;
+    int64_t n_slots = 0;
+};
+
 struct Csr {
     int32_t *rowptr = nullptr;
     int32_t *colidx = nullptr;
     float *vals = nullptr;
-    Segment *segs = nullptr;
-    FixRow *fix = nullptr;
-    int64_t n_segs = 0;
-    int64_t n_fix = 0;
-    int64_t n_slots = 0;
+    Schedule wide; // one class: rows cut by length only
+    Schedule xcd;  // eight column classes
 };
 
 } // namespace slicegcn
@@ -82,7 +105,8 @@ struct slicegcn_graph {
     float *dinv = nullptr;
     slicegcn::Csr fwd;  // A^
     slicegcn::Csr tr;   // A^^T (arrays alias fwd when the pattern is symmetric)
-    float *scratch = nullptr; // max(n_slots) x SCRATCH_COLS partial sums of cut rows
+    float *scratch = nullptr; // partial sums of rows with several items (see Schedule)
+    int64_t scratch_floats = 0;
 };
 
 namespace slicegcn {
@@ -106,7 +130,7 @@ struct ProfScope {
 };
 
 // build_csr.hip
-int build_schedule(int64_t n, Csr &m, hipStream_t stream);
+int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStream_t stream);
 void free_csr(Csr &m, bool owns_pattern);
 
 } // namespace slicegcn

@@ -1,18 +1,34 @@
 // Slice aggregation Y = A^ X (+ Add): the neighbour sum of the SliceGCN layer equation.
 //
-// Work split (fixed per graph when it is built):
-//   * rows with at most LONG_ROW stored entries: a group of LPR lanes per row, rows in natural
-//     order, so index/value reads and the output stream stay contiguous;
-//   * longer rows: one wavefront per segment of at most SEG_NNZ entries; the 64/LPR lane groups
-//     stride over the segment (four gathers in flight per group) and are combined with
-//     cross-lane shuffles; a row cut into several segments stores per-segment partial sums that
-//     a small fix-up kernel adds in segment order.
+// Work split (fixed per graph when it is built, see the schedule notes in common.h):
+//   * rows of at most TINY_ROW stored entries: 64 consecutive rows per wavefront (8-lane groups,
+//     narrow slices).  Lane i loads the row pointers and entries of row i; the gather phase
+//     then hands row (t * GROUPS + grp) to lane group grp in sub-round t through cross-lane reads,
+//     so one wavefront keeps many independent row gathers in flight and the output stream stays
+//     contiguous;
+//   * lane-group items (whole rows of up to LONG_ROW entries, short class pieces of partitioned
+//     rows): the same batched path, four entries per item per round, the next round's indices
+//     requested before the current round's data is consumed;
+//   * wavefront items (everything longer, cut at SEG_NNZ entries): the 64/LPR lane groups stride
+//     over the entries with four gathers in flight per lane and are combined with cross-lane
+//     shuffles;
+//   * a row with several items stores per-item partial sums that a fix-up kernel adds in item order.
+// Workgroup b serves class b mod n_classes.  With 8 classes this pins each column class of the
+// gathered operand to one XCD's L2 (workgroups are placed round-robin over the XCDs), so the
+// eight L2s hold disjoint sets of hot rows instead of eight copies of the same set.  If the
+// placement were different the result would be the same, only slower.
 // No floating-point atomics anywhere: the summation order is a function of the graph only.
 //
 // Lanes map to columns: with vector width V (4 floats when the operand layout allows 16-byte
 // loads, else 1), lane `sub` of a group owns columns [V*sub, V*sub + V) of the current column
-// pass; a pass covers at most SCRATCH_COLS columns and wider operands take several passes.
+// pass; wider operands take several passes.
+//
+// Environment (diagnostics / tuning, read once): SLICEGCN_SPMM_SCHEDULE=rowsplit|xcd forces the
+// single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
+// are cut by column class when a graph is built; SLICEGCN_VERBOSE=1 prints schedule statistics.
 #include "common.h"
+
+#include <cstdlib>
 
 namespace slicegcn {
 
@@ -22,7 +38,7 @@ struct SpmmArgs {
     const int32_t *rowptr;
     const int32_t *colidx;
     const float *vals;
-    const Segment *segs;
+    const Segment *items;
     const FixRow *fix;
     const float *X;
     float *Y;
@@ -30,11 +46,15 @@ struct SpmmArgs {
     float *scratch;
     int64_t ldx, ldy, ldadd;
     int32_t n;
-    int32_t n_segs;
-    int32_t n_seg_blocks;
-    int32_t col0;    // first column of this pass
-    int32_t col_end; // one past the last column of this pass (<= width)
-    int32_t vec_store; // Y (and Add) allow 16-byte accesses
+    int32_t n_classes;
+    int32_t big_blocks;   // workgroups per class in the wavefront-item section
+    int32_t small_blocks; // workgroups per class in the lane-group-item section
+    int32_t slot_cols;    // floats per partial-sum slot
+    int32_t col0;         // first column of this pass
+    int32_t col_end;      // one past the last column of this pass (<= width)
+    int32_t vec_store;    // Y (and Add) allow 16-byte accesses
+    int32_t big_off[MAX_CLASSES], big_cnt[MAX_CLASSES];
+    int32_t small_off[MAX_CLASSES], small_cnt[MAX_CLASSES];
 };
 
 template <int V> struct Acc;
@@ -100,76 +120,218 @@ __device__ inline void store_cols(const Acc<V> &acc, float *y_row, const float *
     }
 }
 
-// Accumulate entries e = first, first + step, ... < end, four gathers in flight.
+// Accumulate entries e = first, first + step, ... < end in chunks of four: the four gathers of
+// a chunk are issued together, and the indices/values of the next chunk are requested before
+// the current chunk's data is consumed, so index latency hides behind the gathers.  A chunk
+// that runs past `end` re-reads the row's first entry with weight 0 and is not accumulated.
 template <int V>
 __device__ inline void gather_accumulate(Acc<V> &acc, const SpmmArgs &a, int first, int end, int step, int col)
 {
     using L = Ld<V>;
+    if (first >= end) return;
+    int c[4];
+    float v[4];
+    bool ok[4];
     int e = first;
-    for (; e + 3 * step < end; e += 4 * step) {
-        const int c0 = a.colidx[e], c1 = a.colidx[e + step], c2 = a.colidx[e + 2 * step], c3 = a.colidx[e + 3 * step];
-        const float v0 = a.vals[e], v1 = a.vals[e + step], v2 = a.vals[e + 2 * step], v3 = a.vals[e + 3 * step];
-        const typename L::T x0 = L::load(a.X + (int64_t)c0 * a.ldx + col);
-        const typename L::T x1 = L::load(a.X + (int64_t)c1 * a.ldx + col);
-        const typename L::T x2 = L::load(a.X + (int64_t)c2 * a.ldx + col);
-        const typename L::T x3 = L::load(a.X + (int64_t)c3 * a.ldx + col);
-        acc.fma(v0, x0);
-        acc.fma(v1, x1);
-        acc.fma(v2, x2);
-        acc.fma(v3, x3);
-    }
-    for (; e < end; e += step) {
-        const int c = a.colidx[e];
-        const float v = a.vals[e];
-        acc.fma(v, L::load(a.X + (int64_t)c * a.ldx + col));
-    }
-}
-
-template <int LPR, int V>
-__global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a)
-{
-    constexpr int GROUPS = 64 / LPR;       // lane groups per wavefront
-    constexpr int ROWS_PER_BLOCK = 256 / LPR;
-    const int blk = blockIdx.x;
-    if (blk < a.n_seg_blocks) {
-        // ---- long rows: one wavefront per segment ----
-        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        const int seg = blk * 4 + wave;
-        if (seg >= a.n_segs) return; // uniform per wavefront
-        const int4 s = *reinterpret_cast<const int4 *>(a.segs + seg);
-        const int row = s.x, beg = s.y, end = s.z, dst = s.w;
-        const int grp = lane / LPR, sub = lane % LPR;
-        const int col = a.col0 + sub * V;
-        const bool active = col < a.col_end;
-        Acc<V> acc;
-        if (active) gather_accumulate<V>(acc, a, beg + grp, end, GROUPS, col);
 #pragma unroll
-        for (int m = LPR; m < 64; m <<= 1) acc.add(shfl_xor_acc<V>(acc, m));
-        if (grp == 0 && active) {
-            if (dst >= 0) {
-                store_cols<V>(acc, a.Y + (int64_t)row * a.ldy, a.Add ? a.Add + (int64_t)row * a.ldadd : nullptr, col,
-                              a.col_end, a.vec_store != 0);
-            } else {
-                float *p = a.scratch + (int64_t)(-(dst + 1)) * SCRATCH_COLS - a.col0; // slot row, pass-relative columns
-                store_cols<V>(acc, p, nullptr, col, a.col_end, true);
+    for (int i = 0; i < 4; ++i) {
+        const int idx = e + i * step;
+        ok[i] = idx < end;
+        const int idc = ok[i] ? idx : first;
+        c[i] = a.colidx[idc];
+        v[i] = a.vals[idc];
+    }
+    while (true) {
+        typename L::T x[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = L::load(a.X + (int64_t)c[i] * a.ldx + col);
+        const int e_next = e + 4 * step;
+        const bool more = e_next < end;
+        int c2[4];
+        float v2[4];
+        bool ok2[4];
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = e_next + i * step;
+                ok2[i] = idx < end;
+                const int idc = ok2[i] ? idx : first;
+                c2[i] = a.colidx[idc];
+                v2[i] = a.vals[idc];
             }
         }
-    } else {
-        // ---- short rows: one lane group per row, natural order ----
-        const int row = (blk - a.n_seg_blocks) * ROWS_PER_BLOCK + threadIdx.x / LPR;
-        const int sub = threadIdx.x % LPR;
-        const int col = a.col0 + sub * V;
-        if (row >= a.n || col >= a.col_end) return;
-        const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-        if (end - beg > LONG_ROW) return; // a long row: written by the branch above
-        Acc<V> acc;
-        gather_accumulate<V>(acc, a, beg, end, 1, col);
-        store_cols<V>(acc, a.Y + (int64_t)row * a.ldy, a.Add ? a.Add + (int64_t)row * a.ldadd : nullptr, col,
-                      a.col_end, a.vec_store != 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (ok[i]) acc.fma(v[i], x[i]);
+        if (!more) break;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { c[i] = c2[i]; v[i] = v2[i]; ok[i] = ok2[i]; }
+        e = e_next;
     }
 }
 
-// Rows that were cut: add the partial slots in order.  One thread per (row, column).
+// Write an item's (or a row's) sum: to the output row, or to its partial-sum slot.
+template <int V>
+__device__ inline void store_result(const Acc<V> &acc, const SpmmArgs &a, int row, int dst, int col)
+{
+    if (dst >= 0) {
+        store_cols<V>(acc, a.Y + (int64_t)row * a.ldy, a.Add ? a.Add + (int64_t)row * a.ldadd : nullptr, col, a.col_end,
+                      a.vec_store != 0);
+    } else {
+        float *p = a.scratch + (int64_t)(-(dst + 1)) * a.slot_cols - a.col0; // slot row, pass-relative columns
+        store_cols<V>(acc, p, nullptr, col, a.col_end, true);
+    }
+}
+
+constexpr int NO_UNIT = INT32_MIN;
+
+// One gather phase of the batched path: sub-round t hands unit (t * GROUPS + grp) of the wavefront
+// to lane group grp.  c_l / v_l hold, per lane, four (column, value) pairs of the unit that lane
+// owns (column -1 = no entry).  Two sub-rounds (eight gathers per lane) are in flight at a time.
+// SKIP_EMPTY adds a wavefront-uniform test that skips sub-round pairs with no entry at all.
+template <int LPR, int V, bool SKIP_EMPTY>
+__device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const int (&c_l)[4], const float (&v_l)[4],
+                                    int grp, int colc)
+{
+    constexpr int G = 64 / LPR;
+    using L = Ld<V>;
+#pragma unroll
+    for (int t0 = 0; t0 < 8; t0 += 2) {
+        int cc[2][4];
+        float vv[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cc[u][i] = __shfl(c_l[i], (t0 + u) * G + grp, 64);
+                vv[u][i] = __shfl(v_l[i], (t0 + u) * G + grp, 64);
+            }
+        if (SKIP_EMPTY && !__any(cc[0][0] >= 0 || cc[1][0] >= 0)) continue; // entries fill from slot 0
+        typename L::T x[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = cc[u][i] >= 0 ? cc[u][i] : 0; // an absent entry re-reads row 0 and is not accumulated
+                x[u][i] = L::load(a.X + (int64_t)c * a.ldx + colc);
+            }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (cc[u][i] >= 0) acc[t0 + u].fma(vv[u][i], x[u][i]);
+    }
+}
+
+// Batched path: up to 8 * GROUPS work units (rows or lane-group items) per wavefront.  Index
+// phase: lane i owns unit i (entries [beg_l, end_l), destination dst_l, NO_UNIT = nothing) and
+// loads its entries four at a time, the next four being requested while the current four are
+// gathered.  Every lane of the wavefront must call this.
+template <int LPR, int V, bool SINGLE_ROUND>
+__device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int row_l, int dst_l, int lane)
+{
+    constexpr int G = 64 / LPR;
+    const int grp = lane / LPR, sub = lane % LPR;
+    const int col = a.col0 + sub * V;
+    const bool col_ok = col < a.col_end;
+    const int colc = col_ok ? col : a.col0;
+    Acc<V> acc[8];
+    int c_l[4];
+    float v_l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = beg_l + i;
+        const bool ok = idx < end_l;
+        c_l[i] = ok ? a.colidx[idx] : -1;
+        v_l[i] = ok ? a.vals[idx] : 0.f;
+    }
+    if (SINGLE_ROUND) {
+        batch_gather<LPR, V, false>(acc, a, c_l, v_l, grp, colc);
+    } else {
+        int k = 0;
+        bool first = true;
+        while (true) {
+            const bool more = beg_l + k + 4 < end_l;
+            int cn[4];
+            float vn[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { // request the next four entries before consuming the current ones
+                const int idx = beg_l + k + 4 + i;
+                const bool ok = idx < end_l;
+                cn[i] = ok ? a.colidx[idx] : -1;
+                vn[i] = ok ? a.vals[idx] : 0.f;
+            }
+            if (first) batch_gather<LPR, V, false>(acc, a, c_l, v_l, grp, colc);
+            else batch_gather<LPR, V, true>(acc, a, c_l, v_l, grp, colc);
+            first = false;
+            if (!__any(more)) break;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { c_l[i] = cn[i]; v_l[i] = vn[i]; }
+            k += 4;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int d = __shfl(dst_l, t * G + grp, 64);
+        const int r = __shfl(row_l, t * G + grp, 64);
+        if (d != NO_UNIT && col_ok) store_result<V>(acc[t], a, r, d, col);
+    }
+}
+
+// Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup.
+template <int LPR, int V>
+__global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
+{
+    constexpr int GROUPS = 64 / LPR; // lane groups per wavefront
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cls = blockIdx.x % a.n_classes, j = blockIdx.x / a.n_classes;
+    const int idx = j * 4 + wave;
+    if (idx >= a.big_cnt[cls]) return; // uniform per wavefront
+    const int4 s = *reinterpret_cast<const int4 *>(a.items + a.big_off[cls] + idx);
+    const int grp = lane / LPR, sub = lane % LPR;
+    const int col = a.col0 + sub * V;
+    const bool active = col < a.col_end;
+    Acc<V> acc;
+    if (active) gather_accumulate<V>(acc, a, s.y + grp, s.z, GROUPS, col);
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) acc.add(shfl_xor_acc<V>(acc, m));
+    if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
+}
+
+// Batched paths.  Workgroups [0, n_classes * small_blocks): lane-group items of class b mod
+// n_classes; the rest: rows of at most TINY_ROW entries in natural order.
+template <int LPR, int V>
+__global__ __launch_bounds__(256) void spmm_batched_kernel(const SpmmArgs a)
+{
+    constexpr int UNITS = 8 * (64 / LPR); // rows / lane-group items per wavefront
+    const int blk = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int small_section = a.n_classes * a.small_blocks;
+    if (blk < small_section) {
+        const int cls = blk % a.n_classes, j = blk / a.n_classes;
+        const int first = (j * 4 + wave) * UNITS;
+        if (first >= a.small_cnt[cls]) return; // uniform per wavefront
+        int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
+        if (lane < UNITS && first + lane < a.small_cnt[cls]) {
+            const int4 s = *reinterpret_cast<const int4 *>(a.items + a.small_off[cls] + first + lane);
+            row_l = s.x; beg_l = s.y; end_l = s.z; dst_l = s.w;
+        }
+        batch_units<LPR, V, false>(a, beg_l, end_l, row_l, dst_l, lane);
+    } else {
+        const int first = ((blk - small_section) * 4 + wave) * UNITS;
+        if (first >= a.n) return; // uniform per wavefront
+        int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
+        if (lane < UNITS && first + lane < a.n) {
+            const int row = first + lane;
+            const int b = a.rowptr[row], e = a.rowptr[row + 1];
+            if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
+        }
+        batch_units<LPR, V, true>(a, beg_l, end_l, row_l, dst_l, lane);
+    }
+}
+
+// Rows with several items: add the partial slots in order.  One thread per (row, column); eight
+// independent slot reads are in flight at a time, the additions stay in slot order.
 __global__ __launch_bounds__(256) void spmm_fix_kernel(const SpmmArgs a, int32_t n_fix)
 {
     const int w = a.col_end - a.col0;
@@ -178,26 +340,60 @@ __global__ __launch_bounds__(256) void spmm_fix_kernel(const SpmmArgs a, int32_t
     if (r >= n_fix) return;
     const int j = (int)(t - r * w);
     const int4 f = *reinterpret_cast<const int4 *>(a.fix + r);
+    const float *p = a.scratch + j;
     float acc = 0.f;
-    for (int s = f.y; s < f.z; ++s) acc += a.scratch[(int64_t)s * SCRATCH_COLS + j];
+    int s = f.y;
+    for (; s + 8 <= f.z; s += 8) {
+        float q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = p[(int64_t)(s + i) * a.slot_cols];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += q[i];
+    }
+    for (; s < f.z; ++s) acc += p[(int64_t)s * a.slot_cols];
     const int col = a.col0 + j;
     if (a.Add) acc += a.Add[(int64_t)f.x * a.ldadd + col];
     a.Y[(int64_t)f.x * a.ldy + col] = acc;
 }
 
+template <int LPR, int V>
+int launch_kernels(const SpmmArgs &a, hipStream_t stream)
+{
+    constexpr int units_per_block = 4 * 8 * (64 / LPR);
+    const int64_t g1 = (int64_t)a.n_classes * a.big_blocks;
+    const int64_t g2 = (int64_t)a.n_classes * a.small_blocks + (a.n + units_per_block - 1) / units_per_block;
+    SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+    if (g1 > 0) {
+        spmm_wave_items_kernel<LPR, V><<<(unsigned)g1, 256, 0, stream>>>(a);
+        SG_LAUNCH_CHECK();
+    }
+    spmm_batched_kernel<LPR, V><<<(unsigned)g2, 256, 0, stream>>>(a);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
 template <int V>
 int launch_pass(const SpmmArgs &a, int lpr, hipStream_t stream)
 {
-    const int rows_per_block = 256 / lpr;
-    const unsigned grid = (unsigned)a.n_seg_blocks + (unsigned)((a.n + rows_per_block - 1) / rows_per_block);
     switch (lpr) {
-    case 8: spmm_kernel<8, V><<<grid, 256, 0, stream>>>(a); break;
-    case 16: spmm_kernel<16, V><<<grid, 256, 0, stream>>>(a); break;
-    case 32: spmm_kernel<32, V><<<grid, 256, 0, stream>>>(a); break;
-    default: spmm_kernel<64, V><<<grid, 256, 0, stream>>>(a); break;
+    case 8: return launch_kernels<8, V>(a, stream);
+    case 16: return launch_kernels<16, V>(a, stream);
+    case 32: return launch_kernels<32, V>(a, stream);
+    default: return launch_kernels<64, V>(a, stream);
     }
-    SG_LAUNCH_CHECK();
-    return SLICEGCN_OK;
+}
+
+// SLICEGCN_SPMM_SCHEDULE=rowsplit | xcd forces one schedule (for A/B measurements); default: by width.
+int forced_schedule()
+{
+    static const int v = [] {
+        const char *e = getenv("SLICEGCN_SPMM_SCHEDULE");
+        if (!e) return 0;
+        if (strcmp(e, "rowsplit") == 0) return 1;
+        if (strcmp(e, "xcd") == 0) return 2;
+        return 0;
+    }();
+    return v;
 }
 
 } // namespace
@@ -205,30 +401,48 @@ int launch_pass(const SpmmArgs &a, int lpr, hipStream_t stream)
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
                 float *Y, int64_t ldy, const float *Add, int64_t ldadd, hipStream_t stream)
 {
-    SG_REQUIRE(m.n_slots == 0 || g->scratch != nullptr, SLICEGCN_EINVAL, "spmm: graph handle has no scratch buffer");
+    // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
+    const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
+    const int V = vec_load ? 4 : 1;
+    // narrow operands (one or two cache lines per row) use the 8-class schedule
+    const int forced = forced_schedule();
+    const bool use_xcd = forced ? forced == 2 : (vec_load && width <= XCD_SLOT_COLS);
+    const Schedule &sc = use_xcd ? m.xcd : m.wide;
+    const int slot_cols = use_xcd ? XCD_SLOT_COLS : WIDE_SLOT_COLS;
+    SG_REQUIRE(sc.n_slots == 0 || (g->scratch != nullptr && sc.n_slots * slot_cols <= g->scratch_floats), SLICEGCN_EINVAL,
+               "spmm: graph handle has no scratch buffer for this schedule");
     SpmmArgs a;
-    a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.segs = m.segs; a.fix = m.fix;
+    a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.items = sc.items; a.fix = sc.fix;
     a.X = X; a.Y = Y; a.Add = Add; a.scratch = g->scratch;
     a.ldx = ldx; a.ldy = ldy; a.ldadd = Add ? ldadd : 0;
     a.n = (int32_t)g->n;
-    a.n_segs = (int32_t)m.n_segs;
-    a.n_seg_blocks = (int32_t)((m.n_segs + 3) / 4);
-    // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
-    const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
+    a.n_classes = sc.n_classes;
+    a.slot_cols = slot_cols; // narrowed below to the pass width
     a.vec_store = aligned16(Y) && (ldy % 4 == 0) && (!Add || (aligned16(Add) && ldadd % 4 == 0));
+    int max_big = 0, max_small = 0;
+    for (int c = 0; c < MAX_CLASSES; ++c) {
+        a.big_off[c] = sc.big_off[c]; a.big_cnt[c] = sc.big_cnt[c];
+        a.small_off[c] = sc.small_off[c]; a.small_cnt[c] = sc.small_cnt[c];
+        max_big = sc.big_cnt[c] > max_big ? sc.big_cnt[c] : max_big;
+        max_small = sc.small_cnt[c] > max_small ? sc.small_cnt[c] : max_small;
+    }
+    a.big_blocks = (max_big + 3) / 4;
     ProfScope prof(Add ? SLICEGCN_PROF_SPMM_ADD : SLICEGCN_PROF_SPMM, width, stream);
-    const int V = vec_load ? 4 : 1;
-    const int pass_cols = vec_load ? SCRATCH_COLS : 64;
+    int pass_cols = vec_load ? slot_cols : 64;
+    if (pass_cols > 256) pass_cols = 256;
+    if (width < pass_cols) a.slot_cols = (int32_t)round_up(width, 4); // one pass: pack the slots densely
     for (int32_t c0 = 0; c0 < width; c0 += pass_cols) {
         a.col0 = c0;
         a.col_end = width < c0 + pass_cols ? width : c0 + pass_cols;
         const int lanes_needed = (a.col_end - c0 + V - 1) / V;
         int lpr = 8;
         while (lpr < lanes_needed) lpr <<= 1; // 8, 16, 32 or 64
+        const int units_per_block = 4 * 8 * (64 / lpr);
+        a.small_blocks = (max_small + units_per_block - 1) / units_per_block;
         if (int rc = vec_load ? launch_pass<4>(a, lpr, stream) : launch_pass<1>(a, lpr, stream)) return rc;
-        if (m.n_fix > 0) {
-            const int64_t threads = m.n_fix * (int64_t)(a.col_end - c0);
-            spmm_fix_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, stream>>>(a, (int32_t)m.n_fix);
+        if (sc.n_fix > 0) {
+            const int64_t threads = sc.n_fix * (int64_t)(a.col_end - c0);
+            spmm_fix_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, stream>>>(a, (int32_t)sc.n_fix);
             SG_LAUNCH_CHECK();
         }
     }
