@@ -36,7 +36,7 @@ void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
-inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+__host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- aggregation schedule -------------------------------------------------------------
 // Rows are split by their number of stored entries d:
@@ -115,8 +115,10 @@ namespace slicegcn {
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
                 float *Y, int64_t ldy, const float *Add, int64_t ldadd, hipStream_t stream);
 
-// dense.hip: out[j] = sum over rows of M[r, j] (fp32 per row block, fp64 across blocks)
-int launch_colsum(const float *M, int64_t ld, int64_t n, int32_t w, float *out, float *ws, hipStream_t stream);
+// dense.hip: column sums of an n x w matrix: fp32 per block of rows into ws[blocks][w], then
+// out[j] = sum over blocks of ws[b][first + j] in fp64 (ws_row = floats per ws row)
+int launch_colsum_partial(const float *M, int64_t ld, int64_t n, int32_t w, float *ws, hipStream_t stream);
+int launch_colsum_final(const float *ws_first, int64_t n, int32_t ws_row, int32_t count, float *out, hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t n, int32_t w);
 
 // misc.hip: brackets the launches of its scope with an event pair while profiling is on

@@ -6,9 +6,15 @@
 //   backward:  dZ = (dHout * mask) W_agg^T,  T = dHout W_self^T            (pair kernel, transposed)
 //              dW_agg = Z^T (dHout * mask), dW_self = Hin^T dHout, db, db_self   (reduce kernels)
 //
-// This file holds the portable fp32 FMA version of the pair kernel: register-blocked 4x4
-// micro-tiles, operands staged through LDS in K-steps of 16.
+// Two implementations of the pair kernel and of the weight-gradient reduction live here:
+//   * MFMA (default): v_mfma_f32_32x32x2_f32 tiles, one 32-row strip per wavefront, operands staged
+//     through LDS with coalesced 16-byte loads; fp32 in, fp32 accumulate.
+//   * plain fp32 FMA with 4x4 register micro-tiles (SLICEGCN_DENSE=fma), kept as a cross-check.
+// Lane layout of the 32x32x2 fp32 MFMA (64 lanes, l = lane): A operand = A[m = l % 32][k = l / 32],
+// B operand = B[k = l / 32][n = l % 32], accumulator register r (0..15) = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
 #include "common.h"
+
+#include <cstdlib>
 
 namespace slicegcn {
 
@@ -161,9 +167,172 @@ __global__ __launch_bounds__(256) void pair_gemm_kernel(const PairArgs a)
     }
 }
 
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Four floats of row `row` starting at column k (k % 4 == 0), zero beyond column K.
+__device__ inline float4 load_k4(const float *__restrict__ base, int64_t ld, int64_t row, int k, int K, bool vec_ok)
+{
+    const float *p = base + row * ld + k;
+    if (vec_ok && k + 4 <= K) return *reinterpret_cast<const float4 *>(p);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < K) v.x = p[0];
+    if (k + 1 < K) v.y = p[1];
+    if (k + 2 < K) v.z = p[2];
+    if (k + 3 < K) v.w = p[3];
+    return v;
+}
+
+__device__ inline float pick(const float4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+// MFMA pair kernel.  Workgroup = 4 wavefronts = 128 rows (32 per wavefront) x NT*32 output
+// columns.  The reduction axis is walked in chunks of 32: both A tiles (128 x 32) and both B
+// tiles (32 x NT*32) are staged in LDS; a lane then reads 4 consecutive k of its row with one
+// 16-byte LDS read and feeds them to four MFMA steps (the k pairing of a step is (k, k+4), the B
+// tile is read with the same pairing).
+template <int NT, bool BWD>
+__global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
+{
+    constexpr int BM = 128, KC = 32, AS = KC + 4, BN = NT * 32;
+    __shared__ __attribute__((aligned(16))) float As1[BM][AS];
+    __shared__ __attribute__((aligned(16))) float As2[BM][AS];
+    __shared__ float Bs1[KC][BN];
+    __shared__ float Bs2[KC][BN];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int64_t row0 = (int64_t)blockIdx.x * BM;
+    const int col0 = blockIdx.y * BN;
+    const bool two = a.A2 != nullptr && a.B2 != nullptr;
+    const bool vec1 = aligned16(a.A1) && (a.lda1 % 4 == 0);
+    const bool vec2 = two && aligned16(a.A2) && (a.lda2 % 4 == 0);
+
+    floatx16 acc1[NT], acc2[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; acc2[t][r] = 0.f; }
+
+    for (int k0 = 0; k0 < a.K; k0 += KC) {
+        // ---- stage the A tiles: 128 rows x 32 k, one float4 per thread and iteration ----
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = tid + it * 256;
+            const int r = idx >> 3, c4 = (idx & 7) * 4;
+            const int64_t row = row0 + r;
+            const int kk = k0 + c4;
+            float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
+            if (row < a.n && kk < a.K) {
+                if (!BWD) {
+                    v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
+                    if (two) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                } else {
+                    const float4 g = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
+                    v1 = g;
+                    if (a.mask) { // four mask bits of this row; kk % 4 == 0 keeps them inside one word
+                        const uint32_t bits = a.mask[row * a.mask_words + (kk >> 5)] >> (kk & 31);
+                        if (!(bits & 1u)) v1.x = 0.f;
+                        if (!(bits & 2u)) v1.y = 0.f;
+                        if (!(bits & 4u)) v1.z = 0.f;
+                        if (!(bits & 8u)) v1.w = 0.f;
+                    }
+                    if (two) v2 = g;
+                }
+            }
+            *reinterpret_cast<float4 *>(&As1[r][c4]) = v1;
+            *reinterpret_cast<float4 *>(&As2[r][c4]) = v2;
+        }
+        // ---- stage the B tiles: 32 k x BN columns ----
+        for (int idx = tid; idx < KC * BN; idx += 256) {
+            const int kk = idx / BN, j = idx % BN;
+            const int gk = k0 + kk, col = col0 + j;
+            float w1 = 0.f, w2 = 0.f;
+            if (gk < a.K && col < a.Nout) {
+                const int64_t id = BWD ? (int64_t)col * a.ldw + gk : (int64_t)gk * a.ldw + col;
+                w1 = a.B1[id];
+                if (two) w2 = a.B2[id];
+            }
+            Bs1[kk][j] = w1;
+            Bs2[kk][j] = w2;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j8 = 0; j8 < 4; ++j8) {
+            const float4 a1 = *reinterpret_cast<const float4 *>(&As1[wave * 32 + m][8 * j8 + 4 * h]);
+            const float4 a2 = *reinterpret_cast<const float4 *>(&As2[wave * 32 + m][8 * j8 + 4 * h]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int kk = 8 * j8 + 4 * h + i;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1, i), Bs1[kk][t * 32 + m], acc1[t], 0, 0, 0);
+                    if (two) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2, i), Bs2[kk][t * 32 + m], acc2[t], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: register r of a lane is row 8*(r/4) + 4*h + r%4 of the strip, column m of tile t ----
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int col = col0 + t * 32 + m;
+        const bool col_ok = col < a.Nout;
+        const float bias1 = (!BWD && a.bias1 && col_ok) ? a.bias1[col] : 0.f;
+        const float bias2 = (!BWD && two && a.bias2 && col_ok) ? a.bias2[col] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = row0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (!BWD) {
+                const float p = acc1[t][r] + bias1;
+                const bool pos = p > 0.f && col_ok;
+                if (a.act == SLICEGCN_ACT_RELU) {
+                    // lanes 0..31 hold one row of this tile, lanes 32..63 the row four below it
+                    const unsigned long long bal = __ballot(pos);
+                    if (m == 0 && row < a.n && col0 + t * 32 < a.Nout)
+                        a.mask[row * a.mask_words + ((col0 + t * 32) >> 5)] = h ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+                }
+                const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
+                const float o = rl + (two ? acc2[t][r] + bias2 : 0.f);
+                if (row < a.n && col_ok) a.O1[row * a.ldo1 + col] = o;
+            } else {
+                if (row < a.n && col_ok) {
+                    a.O1[row * a.ldo1 + col] = acc1[t][r];
+                    if (a.O2) a.O2[row * a.ldo2 + col] = acc2[t][r];
+                }
+            }
+        }
+    }
+}
+
+bool use_mfma()
+{
+    static const bool v = [] {
+        const char *e = getenv("SLICEGCN_DENSE");
+        return !(e && strcmp(e, "fma") == 0);
+    }();
+    return v;
+}
+
+template <bool BWD>
+int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
+{
+    const int nt = a.Nout <= 32 ? 1 : a.Nout <= 64 ? 2 : a.Nout <= 96 ? 3 : 4;
+    dim3 grid((unsigned)((a.n + 127) / 128), (unsigned)((a.Nout + nt * 32 - 1) / (nt * 32)));
+    switch (nt) {
+    case 1: pair_mfma_kernel<1, BWD><<<grid, 256, 0, stream>>>(a); break;
+    case 2: pair_mfma_kernel<2, BWD><<<grid, 256, 0, stream>>>(a); break;
+    case 3: pair_mfma_kernel<3, BWD><<<grid, 256, 0, stream>>>(a); break;
+    default: pair_mfma_kernel<4, BWD><<<grid, 256, 0, stream>>>(a); break;
+    }
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
 template <bool BWD>
 int launch_pair(const PairArgs &a, hipStream_t stream)
 {
+    if (use_mfma()) return launch_pair_mfma<BWD>(a, stream);
     int cgp = 8;
     while (cgp < 32 && cgp * 4 < a.Nout) cgp <<= 1;
     const int bm = (256 / cgp) * 4, bn = cgp * 4;
@@ -271,6 +440,106 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
     }
 }
 
+// MFMA version of the partial weight gradients.  Same grid and output layout as
+// grad_partial_kernel.  Per step the workgroup stages 32 rows of the four operand tiles in LDS;
+// wavefront w multiplies rows 8w..8w+7 (the node axis is the MFMA's k axis: A[m][k] = Z[k][m]),
+// and the four wavefronts' accumulators are added in wavefront order at the end.
+__global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float Zs[RED_RK][RED_TILE];
+    __shared__ __attribute__((aligned(16))) float Hs[RED_RK][RED_TILE];
+    __shared__ __attribute__((aligned(16))) float Ps[RED_RK][RED_TILE];
+    __shared__ __attribute__((aligned(16))) float Gs[RED_RK][RED_TILE];
+    __shared__ float red[3][2][RED_TILE * RED_TILE]; // accumulators of wavefronts 1..3
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int i_base = blockIdx.y * RED_TILE, j_base = blockIdx.z * RED_TILE;
+    const int64_t r_begin = (int64_t)blockIdx.x * RED_ROWS;
+    const int64_t r_end = r_begin + RED_ROWS < a.n ? r_begin + RED_ROWS : a.n;
+    const bool self = a.Hin != nullptr;
+    const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
+    const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
+
+    floatx16 accA, accS;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { accA[r] = 0.f; accS[r] = 0.f; }
+    float accb = 0.f, accbs = 0.f; // threads 0..31: column sums of column j_base + tid
+
+    const int lr = tid >> 3, lc = (tid & 7) * 4; // this thread's float4 of each 32 x 32 tile
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
+        const int64_t row = r0 + lr;
+        float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z, p = z, g = z;
+        if (row < r_end) {
+            if (i_base + lc < a.w_in) {
+                z = load_k4(a.Z, a.ldz, row, i_base + lc, a.w_in, vz);
+                if (self) hh = load_k4(a.Hin, a.ldi, row, i_base + lc, a.w_in, vh);
+            }
+            if (j_base + lc < a.w_out) {
+                g = load_k4(a.dHout, a.ldo, row, j_base + lc, a.w_out, vg);
+                p = g;
+                if (a.mask) {
+                    const int j = j_base + lc;
+                    const uint32_t bits = a.mask[row * a.mask_words + (j >> 5)] >> (j & 31);
+                    if (!(bits & 1u)) p.x = 0.f;
+                    if (!(bits & 2u)) p.y = 0.f;
+                    if (!(bits & 4u)) p.z = 0.f;
+                    if (!(bits & 8u)) p.w = 0.f;
+                }
+            }
+        }
+        *reinterpret_cast<float4 *>(&Zs[lr][lc]) = z;
+        *reinterpret_cast<float4 *>(&Hs[lr][lc]) = hh;
+        *reinterpret_cast<float4 *>(&Ps[lr][lc]) = p;
+        *reinterpret_cast<float4 *>(&Gs[lr][lc]) = g;
+        __syncthreads();
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int k = wave * 8 + s4 * 2 + h;
+            accA = __builtin_amdgcn_mfma_f32_32x32x2f32(Zs[k][m], Ps[k][m], accA, 0, 0, 0);
+            if (self) accS = __builtin_amdgcn_mfma_f32_32x32x2f32(Hs[k][m], Gs[k][m], accS, 0, 0, 0);
+        }
+        if (blockIdx.y == 0 && tid < 32) {
+#pragma unroll 8
+            for (int r = 0; r < RED_RK; ++r) { accb += Ps[r][tid]; accbs += Gs[r][tid]; }
+        }
+        __syncthreads();
+    }
+
+    // ---- add the four wavefronts' tiles in order, then store ----
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = 8 * (r / 4) + 4 * h + (r % 4);
+            red[wave - 1][0][i * RED_TILE + m] = accA[r];
+            red[wave - 1][1][i * RED_TILE + m] = accS[r];
+        }
+    }
+    __syncthreads();
+    float *out = a.partial + (int64_t)blockIdx.x * a.stride;
+    const int ww = a.w_in * a.w_out;
+    if (wave == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int il = 8 * (r / 4) + 4 * h + (r % 4);
+            float va = accA[r], vs = accS[r];
+            for (int q = 0; q < 3; ++q) { va += red[q][0][il * RED_TILE + m]; vs += red[q][1][il * RED_TILE + m]; }
+            const int i = i_base + il, j = j_base + m;
+            if (i < a.w_in && j < a.w_out) {
+                out[i * a.w_out + j] = va;
+                out[ww + i * a.w_out + j] = vs;
+            }
+        }
+        if (blockIdx.y == 0 && tid < 32) {
+            const int j = j_base + tid;
+            if (j < a.w_out) {
+                out[2 * ww + j] = accb;
+                out[2 * ww + a.w_out + j] = accbs;
+            }
+        }
+    }
+}
+
 // Column sums of an n x w matrix (slice-encoding gradient): partial[block][w].
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const float *__restrict__ M, int64_t ld, int64_t n, int32_t w,
                                                              float *__restrict__ partial)
@@ -299,12 +568,59 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const float *__rest
     }
 }
 
+// Same sums with 16-byte loads (aligned base, ld % 4 == 0, w % 4 == 0): thread t owns four
+// columns of every (256 / q)-th row, q = float4 per row rounded up to a power of two.
+__global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const float *__restrict__ M, int64_t ld, int64_t n, int32_t w,
+                                                                 float *__restrict__ partial)
+{
+    const int64_t r_begin = (int64_t)blockIdx.x * RED_ROWS;
+    const int64_t r_end = r_begin + RED_ROWS < n ? r_begin + RED_ROWS : n;
+    __shared__ float4 red[256];
+    for (int c0 = 0; c0 < w; c0 += 1024) {
+        const int cols4 = (w - c0 < 1024 ? w - c0 : 1024) >> 2;
+        int q = 1;
+        while (q < cols4) q <<= 1;
+        const int lanes_r = 256 / q;
+        const int c = threadIdx.x % q, rr = threadIdx.x / q;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < cols4) {
+            const float *p = M + c0 + c * 4;
+            int64_t r = r_begin + rr;
+            for (; r + 3 * lanes_r < r_end; r += 4 * lanes_r) {
+                const float4 v0 = *reinterpret_cast<const float4 *>(p + r * ld);
+                const float4 v1 = *reinterpret_cast<const float4 *>(p + (r + lanes_r) * ld);
+                const float4 v2 = *reinterpret_cast<const float4 *>(p + (r + 2 * lanes_r) * ld);
+                const float4 v3 = *reinterpret_cast<const float4 *>(p + (r + 3 * lanes_r) * ld);
+                acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+                acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+                acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+                acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+            }
+            for (; r < r_end; r += lanes_r) {
+                const float4 v = *reinterpret_cast<const float4 *>(p + r * ld);
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+        }
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        if (rr == 0 && c < cols4) {
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < lanes_r; ++k) {
+                const float4 v = red[k * q + c];
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+            *reinterpret_cast<float4 *>(partial + (int64_t)blockIdx.x * w + c0 + c * 4) = s;
+        }
+        __syncthreads();
+    }
+}
+
 // Final stage: out[e] = sum over row blocks of partial[b][e], in fp64, fixed order.
 // 32 elements x 32 parts per block of 1024 threads.
 struct FinalDst { float *ptr[4]; int32_t begin[5]; }; // element ranges [begin[q], begin[q+1]) go to ptr[q]
 
 __global__ __launch_bounds__(1024) void reduce_final_kernel(const float *__restrict__ partial, int64_t n_blocks,
-                                                            int32_t stride, const FinalDst dst)
+                                                            int32_t row_stride, int32_t stride, const FinalDst dst)
 {
     __shared__ double red[32][33];
     const int el = threadIdx.x % 32, part = threadIdx.x / 32;
@@ -313,7 +629,7 @@ __global__ __launch_bounds__(1024) void reduce_final_kernel(const float *__restr
     const int64_t b0 = part * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
     double acc = 0.0;
     if (e < stride)
-        for (int64_t b = b0; b < b1; ++b) acc += (double)partial[b * stride + e];
+        for (int64_t b = b0; b < b1; ++b) acc += (double)partial[b * row_stride + e];
     red[part][el] = acc;
     __syncthreads();
     if (part == 0 && e < stride) {
@@ -350,16 +666,24 @@ int check_saved(const slicegcn_layer_desc *d, const slicegcn_layer_saved *s, con
 
 } // namespace
 
-// shared with concat.hip
-int launch_colsum(const float *M, int64_t ld, int64_t n, int32_t w, float *out, float *ws, hipStream_t stream)
+// shared with misc.hip
+int launch_colsum_partial(const float *M, int64_t ld, int64_t n, int32_t w, float *ws, hipStream_t stream)
 {
     const int64_t nb = red_blocks(n);
-    colsum_partial_kernel<<<(unsigned)nb, 256, 0, stream>>>(M, ld, n, w, ws);
+    if (aligned16(M) && ld % 4 == 0 && w % 4 == 0)
+        colsum_partial_vec_kernel<<<(unsigned)nb, 256, 0, stream>>>(M, ld, n, w, ws);
+    else
+        colsum_partial_kernel<<<(unsigned)nb, 256, 0, stream>>>(M, ld, n, w, ws);
     SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
+int launch_colsum_final(const float *ws_first, int64_t n, int32_t ws_row, int32_t count, float *out, hipStream_t stream)
+{
     FinalDst dst;
     dst.ptr[0] = out; dst.ptr[1] = dst.ptr[2] = dst.ptr[3] = nullptr;
-    dst.begin[0] = 0; dst.begin[1] = dst.begin[2] = dst.begin[3] = dst.begin[4] = w;
-    reduce_final_kernel<<<(unsigned)((w + 31) / 32), 1024, 0, stream>>>(ws, nb, w, dst);
+    dst.begin[0] = 0; dst.begin[1] = dst.begin[2] = dst.begin[3] = dst.begin[4] = count;
+    reduce_final_kernel<<<(unsigned)((count + 31) / 32), 1024, 0, stream>>>(ws_first, red_blocks(n), ws_row, count, dst);
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
 }
@@ -435,7 +759,8 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.mask = mask; r.mask_words = saved->mask_words;
         r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride;
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
-        grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        if (use_mfma()) grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
+        else grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
         SG_LAUNCH_CHECK();
         FinalDst dst;
         const int ww = w_in * w_out;
@@ -444,7 +769,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         dst.ptr[2] = grads->db;
         dst.ptr[3] = params->W_self ? grads->db_self : nullptr;
         dst.begin[0] = 0; dst.begin[1] = ww; dst.begin[2] = 2 * ww; dst.begin[3] = 2 * ww + w_out; dst.begin[4] = stride;
-        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(partial, nb, stride, dst);
+        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(partial, nb, stride, stride, dst);
         SG_LAUNCH_CHECK();
     }
 

@@ -73,10 +73,45 @@ __global__ __launch_bounds__(256) void copy_cols_kernel(const float *__restrict_
     }
 }
 
+// Same copy, 16 bytes per thread: needs aligned bases, leading dimensions, w and w_pad all multiples of 4.
+__global__ __launch_bounds__(256) void copy_cols_vec_kernel(const float *__restrict__ src, int64_t lds_, float *__restrict__ dst,
+                                                            int64_t ldd, int64_t n, int32_t w, int32_t w_pad,
+                                                            const float *__restrict__ e)
+{
+    const int q = w_pad >> 2; // float4 per destination row
+    const int64_t total = n * (int64_t)q;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t r = t / q;
+        const int c = (int)(t - r * q) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < w) {
+            v = *reinterpret_cast<const float4 *>(src + r * lds_ + c);
+            if (e) {
+                const float4 b = *reinterpret_cast<const float4 *>(e + c);
+                v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+            }
+        }
+        *reinterpret_cast<float4 *>(dst + r * ldd + c) = v;
+    }
+}
+
 inline unsigned grid_for(int64_t total)
 {
     const int64_t b = (total + 255) / 256;
     return (unsigned)(b < 1 ? 1 : (b > 1048576 ? 1048576 : b));
+}
+
+int launch_copy_cols(const float *src, int64_t lds_, float *dst, int64_t ldd, int64_t n, int32_t w, int32_t w_pad,
+                     const float *e, hipStream_t stream)
+{
+    const bool vec = aligned16(src) && aligned16(dst) && (!e || aligned16(e)) && lds_ % 4 == 0 && ldd % 4 == 0 &&
+                     w % 4 == 0 && w_pad % 4 == 0;
+    if (vec)
+        copy_cols_vec_kernel<<<grid_for(n * (w_pad / 4)), 256, 0, stream>>>(src, lds_, dst, ldd, n, w, w_pad, e);
+    else
+        copy_cols_kernel<<<grid_for(n * w_pad), 256, 0, stream>>>(src, lds_, dst, ldd, n, w, w_pad, e);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
 }
 
 } // namespace
@@ -118,10 +153,7 @@ extern "C" int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, in
                "slice_feature: need 0 <= start < end <= ldx (start=%d, end=%d, ldx=%lld)", start, end, (long long)ldx);
     SG_REQUIRE(ldxs >= end - start, SLICEGCN_EINVAL, "slice_feature: ldxs smaller than the slice width");
     SG_REQUIRE(ldxs <= INT32_MAX, SLICEGCN_EINVAL, "slice_feature: ldxs too large");
-    copy_cols_kernel<<<grid_for(n * ldxs), 256, 0, as_stream(stream)>>>(X + start, ldx, Xs, ldxs, n, end - start,
-                                                                        (int32_t)ldxs, nullptr);
-    SG_LAUNCH_CHECK();
-    return SLICEGCN_OK;
+    return launch_copy_cols(X + start, ldx, Xs, ldxs, n, end - start, (int32_t)ldxs, nullptr, as_stream(stream));
 }
 
 extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t *lds, const int32_t *widths,
@@ -144,9 +176,9 @@ extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t 
     for (int32_t i = 0; i < k; ++i) {
         const bool in_place = Hs[i] == H + off && lds[i] == ldh;
         if (!(in_place && E == nullptr)) {
-            copy_cols_kernel<<<grid_for(n * widths[i]), 256, 0, as_stream(stream)>>>(
-                Hs[i], lds[i], H + off, ldh, n, widths[i], widths[i], E ? E + (int64_t)i * lde : nullptr);
-            SG_LAUNCH_CHECK();
+            if (int rc = launch_copy_cols(Hs[i], lds[i], H + off, ldh, n, widths[i], widths[i],
+                                          E ? E + (int64_t)i * lde : nullptr, as_stream(stream)))
+                return rc;
         }
         off += widths[i];
     }
@@ -156,9 +188,10 @@ extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t 
 extern "C" size_t slicegcn_concat_bwd_workspace_bytes(int64_t n, int32_t k, const int32_t *widths)
 {
     if (n < 1 || k < 1 || !widths) return 0;
-    int32_t wmax = 0;
-    for (int32_t i = 0; i < k; ++i) wmax = widths[i] > wmax ? widths[i] : wmax;
-    return (size_t)round_up((int64_t)colsum_workspace_bytes(n, wmax), 256);
+    int64_t total = 0;
+    for (int32_t i = 0; i < k; ++i) total += widths[i] > 0 ? widths[i] : 0;
+    if (total < 1 || total > INT32_MAX) return 0;
+    return (size_t)round_up((int64_t)colsum_workspace_bytes(n, (int32_t)total), 256);
 }
 
 extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, const int32_t *widths,
@@ -185,15 +218,20 @@ extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int6
     ProfScope prof(SLICEGCN_PROF_CONCAT, wmax, as_stream(stream));
     for (int32_t i = 0; i < k; ++i) {
         if (dHs && dHs[i] && !(dHs[i] == dH + off && lds[i] == ldh)) {
-            copy_cols_kernel<<<grid_for(n * widths[i]), 256, 0, as_stream(stream)>>>(dH + off, ldh, dHs[i], lds[i], n,
-                                                                                     widths[i], widths[i], nullptr);
-            SG_LAUNCH_CHECK();
-        }
-        if (dE)
-            if (int rc = launch_colsum(dH + off, ldh, n, widths[i], dE + (int64_t)i * lde, static_cast<float *>(ws),
-                                       as_stream(stream)))
+            if (int rc = launch_copy_cols(dH + off, ldh, dHs[i], lds[i], n, widths[i], widths[i], nullptr, as_stream(stream)))
                 return rc;
+        }
         off += widths[i];
+    }
+    if (dE) { // one pass over dH gives the column sums of every slice; each slice then takes its block
+        if (int rc = launch_colsum_partial(dH, ldh, n, (int32_t)total, static_cast<float *>(ws), as_stream(stream))) return rc;
+        off = 0;
+        for (int32_t i = 0; i < k; ++i) {
+            if (int rc = launch_colsum_final(static_cast<float *>(ws) + off, n, (int32_t)total, widths[i],
+                                             dE + (int64_t)i * lde, as_stream(stream)))
+                return rc;
+            off += widths[i];
+        }
     }
     return SLICEGCN_OK;
 }
