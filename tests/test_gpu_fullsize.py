@@ -71,9 +71,60 @@ def _run(name: str, n_samples: int):
     g.destroy()
 
 
+def test_cfg3_full_size_sampled():
+    _run("cfg3", 500)      # slices of 301 columns: two column passes, rows of up to 10^5 entries
+
+
 def test_cfg4_full_size_sampled():
     _run("cfg4", 2000)
 
 
 def test_cfg5_full_size_sampled():
     _run("cfg5", 2000)
+
+
+def test_cfg5_full_size_layer_fwd_bwd():
+    """One whole layer of one slice at the benchmark's size (10M x 32 -> 32), forward and backward,
+    every output element against the oracle."""
+    from synth import model
+    from gpu_util import assert_close, pack_mask, unpack_mask
+    w = synth.WORKLOADS["cfg5"]
+    dev = torch.device("cuda")
+    n, hs = w.n_nodes, w.slice_hidden
+    print("[fullsize-layer] generating", flush=True)
+    src, dst = configs.edges(w, device=dev)
+    g = sg.slicegcn_build_norm_csr(src, dst, n)
+    o = oracle.build_norm_csr(src.cpu().numpy(), dst.cpu().numpy(), n)
+    del src, dst
+    slices, width = sg.slicegcn_slice_strategy(w.feat, w.k)
+    a, b = slices[1]
+    Xs = configs.features(w, device=dev, col_start=a, col_count=b - a)
+    W_agg, bias, W_self, b_self = model.slice_layer_params(w, 1, 0, width, hs, bias_std=0.05)
+    f32 = dict(dtype=torch.float32, device=dev)
+    Hout = torch.empty((n, hs), **f32); Z = torch.empty((n, width), **f32)
+    mask = torch.zeros((n, 1), dtype=torch.int32, device=dev)
+    sg.slicegcn_layer_fwd(g, Xs, W_agg.cuda(), bias.cuda(), W_self.cuda(), b_self.cuda(), Hout, Z, mask)
+    print("[fullsize-layer] oracle forward", flush=True)
+    X64 = Xs.cpu().numpy().astype(np.float64)
+    want, Zo, Po = oracle.layer_fwd(o, X64, W_agg.numpy(), bias.numpy(), W_self.numpy(), b_self.numpy(), act=1)
+    assert_close(Z.cpu().numpy(), Zo, "Z")
+    assert_close(Hout.cpu().numpy(), want, "Hout")
+    ref_mask = (Po > 0)
+    differ = unpack_mask(mask.cpu().numpy(), hs) != ref_mask
+    assert np.all(np.abs(Po[differ]) <= 1e-5 * np.sqrt(np.mean(Po * Po)))
+    print(f"[fullsize-layer] forward ok, {int(differ.sum())} activation decisions inside the rounding band", flush=True)
+    del want, Po
+    # backward on the oracle's activation pattern
+    mask.copy_(torch.as_tensor(pack_mask(ref_mask.astype(np.uint8))))
+    dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, hs, device=dev)
+    dHin = torch.empty((n, width), **f32)
+    dW_agg = torch.empty((width, hs), **f32); db = torch.empty(hs, **f32)
+    dW_self = torch.empty((width, hs), **f32); db_self = torch.empty(hs, **f32)
+    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(n, width, hs, True), dtype=torch.uint8, device=dev)
+    sg.slicegcn_layer_bwd(g, Xs, W_agg.cuda(), W_self.cuda(), Z, mask, dH, dHin, dW_agg, db, dW_self, db_self, ws)
+    print("[fullsize-layer] oracle backward", flush=True)
+    ref = oracle.layer_bwd(o, X64, Zo, ref_mask, W_agg.numpy(), W_self.numpy(), dH.cpu().numpy())
+    for name, t in (("dW_agg", dW_agg), ("db", db), ("dW_self", dW_self), ("db_self", db_self), ("dHin", dHin)):
+        e = assert_close(t.cpu().numpy(), ref[name], name)
+        print(f"[fullsize-layer] {name}: max rel err {e:.2e}", flush=True)
+    g.destroy()
