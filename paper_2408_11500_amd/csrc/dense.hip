@@ -305,6 +305,120 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
     }
 }
 
+// Variant for reduction lengths K <= 64 (every layer of the narrow-slice workloads): the weight
+// tiles are staged in LDS once per workgroup, which then walks over row tiles; each lane loads the
+// k values it feeds to the MFMA straight from global memory (16-byte loads, 32 contiguous bytes
+// per row and instruction), so there is no LDS round trip or barrier per row tile and all loads of
+// a tile are in flight at once.
+template <int NT, int KCH, bool BWD> // KCH: number of 32-wide K chunks (1 or 2)
+__global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
+{
+    constexpr int BN = NT * 32, KK = KCH * 32;
+    __shared__ float Bs1[KK][BN];
+    __shared__ float Bs2[KK][BN];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int col0 = blockIdx.y * BN;
+    const bool two = a.A2 != nullptr && a.B2 != nullptr;
+    const bool vec1 = aligned16(a.A1) && (a.lda1 % 4 == 0);
+    const bool vec2 = two && aligned16(a.A2) && (a.lda2 % 4 == 0);
+
+    for (int idx = tid; idx < KK * BN; idx += 256) {
+        const int kk = idx / BN, j = idx % BN;
+        const int col = col0 + j;
+        float w1 = 0.f, w2 = 0.f;
+        if (kk < a.K && col < a.Nout) {
+            const int64_t id = BWD ? (int64_t)col * a.ldw + kk : (int64_t)kk * a.ldw + col;
+            w1 = a.B1[id];
+            if (two) w2 = a.B2[id];
+        }
+        Bs1[kk][j] = w1;
+        Bs2[kk][j] = w2;
+    }
+    __syncthreads();
+
+    const int64_t n_tiles = (a.n + 127) / 128;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row = tile * 128 + wave * 32 + m; // the row this lane feeds as A operand
+        float4 a1[KCH * 4], a2[KCH * 4];
+#pragma unroll
+        for (int q = 0; q < KCH * 4; ++q) {
+            const int kk = 8 * q + 4 * h;
+            float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
+            if (row < a.n && kk < a.K) {
+                v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
+                if (!BWD) {
+                    if (two) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                } else {
+                    if (two) v2 = v1;
+                    if (a.mask) {
+                        const uint32_t bits = a.mask[row * a.mask_words + (kk >> 5)] >> (kk & 31);
+                        if (!(bits & 1u)) v1.x = 0.f;
+                        if (!(bits & 2u)) v1.y = 0.f;
+                        if (!(bits & 4u)) v1.z = 0.f;
+                        if (!(bits & 8u)) v1.w = 0.f;
+                    }
+                }
+            }
+            a1[q] = v1;
+            a2[q] = v2;
+        }
+        floatx16 acc1[NT], acc2[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; acc2[t][r] = 0.f; }
+#pragma unroll
+        for (int q = 0; q < KCH * 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int kk = 8 * q + 4 * h + i;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1[q], i), Bs1[kk][t * 32 + m], acc1[t], 0, 0, 0);
+                    if (two) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2[q], i), Bs2[kk][t * 32 + m], acc2[t], 0, 0, 0);
+                }
+            }
+        const int64_t row0 = tile * 128;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int col = col0 + t * 32 + m;
+            const bool col_ok = col < a.Nout;
+            const float bias1 = (!BWD && a.bias1 && col_ok) ? a.bias1[col] : 0.f;
+            const float bias2 = (!BWD && two && a.bias2 && col_ok) ? a.bias2[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t orow = row0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (!BWD) {
+                    const float p = acc1[t][r] + bias1;
+                    const bool pos = p > 0.f && col_ok;
+                    if (a.act == SLICEGCN_ACT_RELU) {
+                        const unsigned long long bal = __ballot(pos);
+                        if (m == 0 && orow < a.n && col0 + t * 32 < a.Nout)
+                            a.mask[orow * a.mask_words + ((col0 + t * 32) >> 5)] = h ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+                    }
+                    const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
+                    const float o = rl + (two ? acc2[t][r] + bias2 : 0.f);
+                    if (orow < a.n && col_ok) a.O1[orow * a.ldo1 + col] = o;
+                } else {
+                    if (orow < a.n && col_ok) {
+                        a.O1[orow * a.ldo1 + col] = acc1[t][r];
+                        if (a.O2) a.O2[orow * a.ldo2 + col] = acc2[t][r];
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int NT, bool BWD>
+void launch_direct(const PairArgs &a, dim3 grid, hipStream_t stream)
+{
+    if (a.K <= 32) pair_mfma_direct_kernel<NT, 1, BWD><<<grid, 256, 0, stream>>>(a);
+    else pair_mfma_direct_kernel<NT, 2, BWD><<<grid, 256, 0, stream>>>(a);
+}
+
 bool use_mfma()
 {
     static const bool v = [] {
@@ -319,6 +433,19 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
 {
     const int nt = a.Nout <= 32 ? 1 : a.Nout <= 64 ? 2 : a.Nout <= 96 ? 3 : 4;
     dim3 grid((unsigned)((a.n + 127) / 128), (unsigned)((a.Nout + nt * 32 - 1) / (nt * 32)));
+    static const bool no_direct = getenv("SLICEGCN_DENSE_STAGED") != nullptr;
+    if (a.K <= 64 && nt == 1 && !no_direct) { // short reduction, one output tile: weights resident in LDS, workgroups walk over row tiles
+        const unsigned tiles = grid.x;
+        grid.x = tiles < 2048u ? tiles : 2048u;
+        switch (nt) {
+        case 1: launch_direct<1, BWD>(a, grid, stream); break;
+        case 2: launch_direct<2, BWD>(a, grid, stream); break;
+        case 3: launch_direct<3, BWD>(a, grid, stream); break;
+        default: launch_direct<4, BWD>(a, grid, stream); break;
+        }
+        SG_LAUNCH_CHECK();
+        return SLICEGCN_OK;
+    }
     switch (nt) {
     case 1: pair_mfma_kernel<1, BWD><<<grid, 256, 0, stream>>>(a); break;
     case 2: pair_mfma_kernel<2, BWD><<<grid, 256, 0, stream>>>(a); break;
@@ -446,11 +573,14 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
 // and the four wavefronts' accumulators are added in wavefront order at the end.
 __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float Zs[RED_RK][RED_TILE];
-    __shared__ __attribute__((aligned(16))) float Hs[RED_RK][RED_TILE];
-    __shared__ __attribute__((aligned(16))) float Ps[RED_RK][RED_TILE];
-    __shared__ __attribute__((aligned(16))) float Gs[RED_RK][RED_TILE];
-    __shared__ float red[3][2][RED_TILE * RED_TILE]; // accumulators of wavefronts 1..3
+    // one LDS block: the four operand tiles during the row loop, the accumulators of wavefronts 1..3 after it
+    constexpr int TILE_FLOATS = RED_RK * RED_TILE;
+    __shared__ __attribute__((aligned(16))) float lds[3 * 2 * RED_TILE * RED_TILE];
+    float (*Zs)[RED_TILE] = reinterpret_cast<float (*)[RED_TILE]>(lds);
+    float (*Hs)[RED_TILE] = reinterpret_cast<float (*)[RED_TILE]>(lds + TILE_FLOATS);
+    float (*Ps)[RED_TILE] = reinterpret_cast<float (*)[RED_TILE]>(lds + 2 * TILE_FLOATS);
+    float (*Gs)[RED_TILE] = reinterpret_cast<float (*)[RED_TILE]>(lds + 3 * TILE_FLOATS);
+    float (*red)[2][RED_TILE * RED_TILE] = reinterpret_cast<float (*)[2][RED_TILE * RED_TILE]>(lds);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int m = lane & 31, h = lane >> 5;
@@ -464,12 +594,13 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
     floatx16 accA, accS;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { accA[r] = 0.f; accS[r] = 0.f; }
-    float accb = 0.f, accbs = 0.f; // threads 0..31: column sums of column j_base + tid
+    float accb = 0.f; // lanes 0..31: column (j_base + m) of dP, lanes 32..63: of dH_out; rows of this wavefront only
 
     const int lr = tid >> 3, lc = (tid & 7) * 4; // this thread's float4 of each 32 x 32 tile
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
+    float4 z, hh, p, g;
+    auto fetch = [&](int64_t r0) { // this thread's share of the four tiles of rows [r0, r0 + 32)
         const int64_t row = r0 + lr;
-        float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z, p = z, g = z;
+        z = make_float4(0.f, 0.f, 0.f, 0.f); hh = z; p = z; g = z;
         if (row < r_end) {
             if (i_base + lc < a.w_in) {
                 z = load_k4(a.Z, a.ldz, row, i_base + lc, a.w_in, vz);
@@ -488,25 +619,32 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
                 }
             }
         }
+    };
+    fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
         *reinterpret_cast<float4 *>(&Zs[lr][lc]) = z;
         *reinterpret_cast<float4 *>(&Hs[lr][lc]) = hh;
         *reinterpret_cast<float4 *>(&Ps[lr][lc]) = p;
         *reinterpret_cast<float4 *>(&Gs[lr][lc]) = g;
         __syncthreads();
+        if (r0 + RED_RK < r_end) fetch(r0 + RED_RK); // next step's loads fly during this step's MFMAs
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
             const int k = wave * 8 + s4 * 2 + h;
             accA = __builtin_amdgcn_mfma_f32_32x32x2f32(Zs[k][m], Ps[k][m], accA, 0, 0, 0);
             if (self) accS = __builtin_amdgcn_mfma_f32_32x32x2f32(Hs[k][m], Gs[k][m], accS, 0, 0, 0);
         }
-        if (blockIdx.y == 0 && tid < 32) {
-#pragma unroll 8
-            for (int r = 0; r < RED_RK; ++r) { accb += Ps[r][tid]; accbs += Gs[r][tid]; }
+        if (blockIdx.y == 0) {
+            float (*T)[RED_TILE] = h ? Gs : Ps;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) accb += T[wave * 8 + r][m];
         }
         __syncthreads();
     }
 
-    // ---- add the four wavefronts' tiles in order, then store ----
+    // ---- add the four wavefronts' tiles in order, then store (the tile memory is free now) ----
+    __shared__ float bsum[4][64];
+    bsum[wave][lane] = accb;
     if (wave > 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -530,12 +668,10 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
                 out[ww + i * a.w_out + j] = vs;
             }
         }
-        if (blockIdx.y == 0 && tid < 32) {
-            const int j = j_base + tid;
-            if (j < a.w_out) {
-                out[2 * ww + j] = accb;
-                out[2 * ww + a.w_out + j] = accbs;
-            }
+        if (blockIdx.y == 0) {
+            const int j = j_base + m;
+            const float sum = ((bsum[0][lane] + bsum[1][lane]) + bsum[2][lane]) + bsum[3][lane];
+            if (j < a.w_out) out[2 * ww + (h ? a.w_out : 0) + j] = sum;
         }
     }
 }
