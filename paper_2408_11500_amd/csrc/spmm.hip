@@ -404,9 +404,11 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
     const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
     const int V = vec_load ? 4 : 1;
-    // narrow operands (one or two cache lines per row) use the 8-class schedule
+    // 16-byte gathers use the 8-class schedule in passes of at most 64 columns: a narrow pass keeps
+    // the set of hot rows of the operand small enough for the L2s (a wider operand costs more index
+    // reads, which are small next to the gathers); the scalar path keeps the single-class schedule
     const int forced = forced_schedule();
-    const bool use_xcd = forced ? forced == 2 : (vec_load && width <= XCD_SLOT_COLS);
+    const bool use_xcd = forced ? forced == 2 : vec_load;
     const Schedule &sc = use_xcd ? m.xcd : m.wide;
     const int slot_cols = use_xcd ? XCD_SLOT_COLS : WIDE_SLOT_COLS;
     SG_REQUIRE(sc.n_slots == 0 || (g->scratch != nullptr && sc.n_slots * slot_cols <= g->scratch_floats), SLICEGCN_EINVAL,
