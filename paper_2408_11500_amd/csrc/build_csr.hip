@@ -107,7 +107,12 @@ __global__ void swap_keys_kernel(const uint64_t *__restrict__ in, int64_t nnz, u
 
 // ---- schedule ---------------------------------------------------------------------------
 // Per long row: the entries of column class c are [lower_bound(c * cw), lower_bound((c+1) * cw)).
-// counts layout: cnt[(2*c + kind) * (n+1) + row], kind 0 = wavefront items, 1 = lane-group items.
+// counts layout: cnt[(KINDS*c + kind) * (n+1) + row]; kind 0 = wavefront items of rows cut by column
+// class, 1 = wavefront items of rows kept whole, 2 = lane-group items.  A class's wavefront list is
+// its kind-0 items followed by its kind-1 items, so the class-cut pieces (whose gathers stay inside
+// the class's column range) run before the whole rows (whose gathers span every column and would
+// otherwise keep evicting the class's hot rows from the XCD's L2).
+constexpr int KINDS = 3;
 struct RowCut {
     int32_t lo[MAX_CLASSES + 1];
 };
@@ -131,8 +136,7 @@ __device__ inline RowCut cut_row(const int32_t *__restrict__ colidx, int32_t beg
 
 __device__ inline int pieces_of(int32_t len) { return (len + SEG_NNZ - 1) / SEG_NNZ; }
 
-// The items of one row, in (class, piece) order.  F is called as f(cls, kind, beg, end) with
-// kind 0 = wavefront item, 1 = lane-group item.
+// The items of one row, in (class, piece) order.  F is called as f(cls, kind, beg, end).
 template <class F>
 __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t r, int32_t beg, int32_t end,
                                     int n_classes, int32_t cw, int32_t part_row, F f)
@@ -142,13 +146,13 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t 
     if (d <= TINY_ROW) return 0;
     const int own = (int)(r % n_classes);
     if (d <= LONG_ROW) {
-        f(own, 1, beg, end);
+        f(own, 2, beg, end);
         return 1;
     }
     if (n_classes == 1 || d <= part_row) {
         const int s = pieces_of(d);
         const int32_t piece = (d + s - 1) / s; // equal cuts, the last one takes the remainder
-        for (int j = 0; j < s; ++j) f(own, 0, beg + j * piece, min(end, beg + (j + 1) * piece));
+        for (int j = 0; j < s; ++j) f(own, 1, beg + j * piece, min(end, beg + (j + 1) * piece));
         return s;
     }
     const RowCut rc = cut_row(colidx, beg, end, n_classes, cw);
@@ -156,7 +160,7 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t 
         const int32_t b = rc.lo[c], e = rc.lo[c + 1], len = e - b;
         if (len <= 0) continue;
         if (len <= SMALL_ITEM) {
-            f(c, 1, b, e);
+            f(c, 2, b, e);
             ++total;
         } else {
             const int s = pieces_of(len);
@@ -168,7 +172,6 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t 
     return total;
 }
 
-// counts layout: cnt[(2*c + kind) * (n+1) + row]
 __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
                                    int n_classes, int32_t cw, int32_t part_row, int32_t *__restrict__ cnt,
                                    int32_t *__restrict__ c_slot, int32_t *__restrict__ c_fix)
@@ -176,13 +179,13 @@ __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int
     const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (r > n) return;
     const int64_t stride = n + 1;
-    int32_t per[2 * MAX_CLASSES];
-    for (int t = 0; t < 2 * MAX_CLASSES; ++t) per[t] = 0;
+    int32_t per[KINDS * MAX_CLASSES];
+    for (int t = 0; t < KINDS * MAX_CLASSES; ++t) per[t] = 0;
     int total = 0;
     if (r < n)
         total = for_each_item(colidx, r, rowptr[r], rowptr[r + 1], n_classes, cw, part_row,
-                              [&](int c, int kind, int32_t, int32_t) { per[2 * c + kind] += 1; });
-    for (int t = 0; t < 2 * n_classes; ++t) cnt[t * stride + r] = per[t];
+                              [&](int c, int kind, int32_t, int32_t) { per[KINDS * c + kind] += 1; });
+    for (int t = 0; t < KINDS * n_classes; ++t) cnt[t * stride + r] = per[t];
     c_slot[r] = total > 1 ? total : 0;
     c_fix[r] = total > 1 ? 1 : 0;
 }
@@ -199,8 +202,8 @@ __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int3
     if (end - beg <= TINY_ROW) return;
     // first pass: how many items (decides whether they write the row or partial slots)
     const int total = for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [](int, int, int32_t, int32_t) {});
-    int32_t used[2 * MAX_CLASSES];
-    for (int t = 0; t < 2 * MAX_CLASSES; ++t) used[t] = 0;
+    int32_t used[KINDS * MAX_CLASSES];
+    for (int t = 0; t < KINDS * MAX_CLASSES; ++t) used[t] = 0;
     int slot = o_slot[r]; // slots are handed out in (class, piece) order
     for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [&](int c, int kind, int32_t b, int32_t e) {
         Segment sg;
@@ -208,7 +211,7 @@ __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int3
         sg.beg = b;
         sg.end = e;
         sg.dst = total == 1 ? (int32_t)r : -(slot + 1);
-        const int t = 2 * c + kind;
+        const int t = KINDS * c + kind;
         items[off[t * stride + r] + used[t]] = sg;
         used[t] += 1;
         ++slot;
@@ -286,7 +289,7 @@ int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStr
     out = Schedule();
     out.n_classes = n_classes;
     const size_t stride = (size_t)(n + 1);
-    const size_t n_cnt = 2 * (size_t)n_classes * stride;
+    const size_t n_cnt = KINDS * (size_t)n_classes * stride;
     SG_REQUIRE(n_cnt <= (size_t)INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: schedule tables exceed int32 indexing");
     const int32_t cw = (int32_t)((n + n_classes - 1) / n_classes); // columns per class
     DevBuf cnt, off, aux;
@@ -301,22 +304,22 @@ int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStr
     if (int rc = scan_i32(x, x + 2 * stride, n + 1, stream)) return rc;
     if (int rc = scan_i32(x + stride, x + 3 * stride, n + 1, stream)) return rc;
     // the scan runs over all (class, kind) tables back to back: table t starts at o[t * stride]
-    std::vector<int32_t> starts(2 * n_classes + 1);
-    for (int t = 0; t < 2 * n_classes; ++t)
+    std::vector<int32_t> starts(KINDS * n_classes + 1);
+    for (int t = 0; t < KINDS * n_classes; ++t)
         SG_HIP(hipMemcpy(&starts[t], o + (size_t)t * stride, sizeof(int32_t), hipMemcpyDeviceToHost));
     int32_t last_off = 0, last_cnt = 0, n_slots = 0, n_fix = 0;
     SG_HIP(hipMemcpy(&last_off, o + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&last_cnt, c + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&n_slots, x + 2 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&n_fix, x + 3 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
-    starts[2 * n_classes] = last_off + last_cnt;
+    starts[KINDS * n_classes] = last_off + last_cnt;
     for (int cl = 0; cl < n_classes; ++cl) {
-        out.big_off[cl] = starts[2 * cl];
-        out.big_cnt[cl] = starts[2 * cl + 1] - starts[2 * cl];
-        out.small_off[cl] = starts[2 * cl + 1];
-        out.small_cnt[cl] = starts[2 * cl + 2] - starts[2 * cl + 1];
+        out.big_off[cl] = starts[KINDS * cl];
+        out.big_cnt[cl] = starts[KINDS * cl + 2] - starts[KINDS * cl];
+        out.small_off[cl] = starts[KINDS * cl + 2];
+        out.small_cnt[cl] = starts[KINDS * cl + 3] - starts[KINDS * cl + 2];
     }
-    out.n_items = starts[2 * n_classes];
+    out.n_items = starts[KINDS * n_classes];
     out.n_slots = n_slots;
     out.n_fix = n_fix;
     DevBuf items, fix;

@@ -9,9 +9,10 @@
 //   * lane-group items (whole rows of up to LONG_ROW entries, short class pieces of partitioned
 //     rows): the same batched path, four entries per item per round, the next round's indices
 //     requested before the current round's data is consumed;
-//   * wavefront items (everything longer, cut at SEG_NNZ entries): the 64/LPR lane groups stride
-//     over the entries with four gathers in flight per lane and are combined with cross-lane
-//     shuffles;
+//   * wavefront items (everything longer, cut at SEG_NNZ entries): the wavefront loads 64
+//     (column, value) pairs per coalesced read, the 64/LPR lane groups take them in turn through
+//     cross-lane reads with eight gathers in flight per lane, and the groups' sums are combined
+//     with cross-lane shuffles;
 //   * a row with several items stores per-item partial sums that a fix-up kernel adds in item order.
 // Workgroup b serves class b mod n_classes.  With 8 classes this pins each column class of the
 // gathered operand to one XCD's L2 (workgroups are placed round-robin over the XCDs), so the
@@ -45,6 +46,7 @@ struct SpmmArgs {
     const float *Add;
     float *scratch;
     int64_t ldx, ldy, ldadd;
+    uint32_t ldx_bytes;   // S32 kernels: byte stride of X rows (n * ldx * 4 < 2^32, n and ldx * 4 < 2^24)
     int32_t n;
     int32_t n_classes;
     int32_t big_blocks;   // workgroups per class in the wavefront-item section
@@ -85,6 +87,19 @@ template <> struct Ld<1> {
     static __device__ T load(const float *p) { return *p; }
 };
 
+// Address of columns [col, col + V) of row c of the gathered operand.  S32: the whole operand lies
+// within 4 GiB of its base and both factors fit 24 bits, so one 24-bit multiply-add gives an
+// unsigned 32-bit byte offset from the (wavefront-uniform) base pointer.
+template <int V, bool S32>
+__device__ inline typename Ld<V>::T load_x(const SpmmArgs &a, int c, int col)
+{
+    if (S32) {
+        const uint32_t off = __umul24((uint32_t)c, a.ldx_bytes) + (uint32_t)col * 4u;
+        return Ld<V>::load(reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.X) + off));
+    }
+    return Ld<V>::load(a.X + (int64_t)c * a.ldx + col);
+}
+
 template <int V> __device__ inline Acc<V> shfl_xor_acc(const Acc<V> &a, int mask);
 template <> __device__ inline Acc<4> shfl_xor_acc<4>(const Acc<4> &a, int mask)
 {
@@ -120,53 +135,68 @@ __device__ inline void store_cols(const Acc<V> &acc, float *y_row, const float *
     }
 }
 
-// Accumulate entries e = first, first + step, ... < end in chunks of four: the four gathers of
-// a chunk are issued together, and the indices/values of the next chunk are requested before
-// the current chunk's data is consumed, so index latency hides behind the gathers.  A chunk
-// that runs past `end` re-reads the row's first entry with weight 0 and is not accumulated.
-template <int V>
-__device__ inline void gather_accumulate(Acc<V> &acc, const SpmmArgs &a, int first, int end, int step, int col)
+// Accumulate the entries [beg, end) of one wavefront item.  The wavefront reads 64 consecutive
+// (column, value) pairs with one coalesced load each, lane i holding entry base + i, and requests
+// the next 64 before it consumes the current ones; sub-step t then hands entry t * G + grp to lane
+// group grp through cross-lane reads, eight sub-steps (eight gathers per lane) at a time.  Full
+// chunks run without any per-entry test; only the last, partial chunk checks entry indices.
+// Every lane of the wavefront must call this (lanes past the last column pass a valid `col` and
+// drop their result).
+template <int LPR, int V, bool S32>
+__device__ inline void wave_gather(Acc<V> &acc, const SpmmArgs &a, int beg, int end, int lane, int grp, int col)
 {
+    constexpr int G = 64 / LPR; // lane groups = entries per sub-step
+    constexpr int U = 8;        // gathers in flight per lane
     using L = Ld<V>;
-    if (first >= end) return;
-    int c[4];
-    float v[4];
-    bool ok[4];
-    int e = first;
+    if (beg >= end) return;
+    int idx = beg + lane;
+    int c_l = a.colidx[idx < end ? idx : beg];
+    float v_l = a.vals[idx < end ? idx : beg];
+    for (int base = beg; base < end; base += 64) {
+        int c_n = 0;
+        float v_n = 0.f;
+        if (base + 64 < end) { // wavefront-uniform
+            idx = base + 64 + lane;
+            c_n = a.colidx[idx < end ? idx : beg];
+            v_n = a.vals[idx < end ? idx : beg];
+        }
+        const int cnt = end - base; // entries of this chunk (>= 64: a full chunk)
+        if (cnt >= 64) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = e + i * step;
-        ok[i] = idx < end;
-        const int idc = ok[i] ? idx : first;
-        c[i] = a.colidx[idc];
-        v[i] = a.vals[idc];
-    }
-    while (true) {
-        typename L::T x[4];
+            for (int t = 0; t < LPR; t += U) {
+                int c[U];
+                float v[U];
+                typename L::T x[U];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = L::load(a.X + (int64_t)c[i] * a.ldx + col);
-        const int e_next = e + 4 * step;
-        const bool more = e_next < end;
-        int c2[4];
-        float v2[4];
-        bool ok2[4];
-        if (more) {
+                for (int u = 0; u < U; ++u) {
+                    c[u] = __shfl(c_l, (t + u) * G + grp, 64);
+                    v[u] = __shfl(v_l, (t + u) * G + grp, 64);
+                }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = e_next + i * step;
-                ok2[i] = idx < end;
-                const int idc = ok2[i] ? idx : first;
-                c2[i] = a.colidx[idc];
-                v2[i] = a.vals[idc];
+                for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc.fma(v[u], x[u]);
+            }
+        } else {
+            for (int t = 0; t * G < cnt; t += U) { // uniform trip count
+                int c[U];
+                float v[U];
+                typename L::T x[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int src = ((t + u) * G + grp) & 63; // lanes past cnt hold the item's first entry (in bounds)
+                    c[u] = __shfl(c_l, src, 64);
+                    v[u] = __shfl(v_l, src, 64);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if ((t + u) * G + grp < cnt) acc.fma(v[u], x[u]);
             }
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (ok[i]) acc.fma(v[i], x[i]);
-        if (!more) break;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { c[i] = c2[i]; v[i] = v2[i]; ok[i] = ok2[i]; }
-        e = e_next;
+        c_l = c_n;
+        v_l = v_n;
     }
 }
 
@@ -189,7 +219,7 @@ constexpr int NO_UNIT = INT32_MIN;
 // to lane group grp.  c_l / v_l hold, per lane, four (column, value) pairs of the unit that lane
 // owns (column -1 = no entry).  Two sub-rounds (eight gathers per lane) are in flight at a time.
 // SKIP_EMPTY adds a wavefront-uniform test that skips sub-round pairs with no entry at all.
-template <int LPR, int V, bool SKIP_EMPTY>
+template <int LPR, int V, bool S32, bool SKIP_EMPTY>
 __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const int (&c_l)[4], const float (&v_l)[4],
                                     int grp, int colc)
 {
@@ -213,7 +243,7 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int c = cc[u][i] >= 0 ? cc[u][i] : 0; // an absent entry re-reads row 0 and is not accumulated
-                x[u][i] = L::load(a.X + (int64_t)c * a.ldx + colc);
+                x[u][i] = load_x<V, S32>(a, c, colc);
             }
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -227,7 +257,7 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
 // phase: lane i owns unit i (entries [beg_l, end_l), destination dst_l, NO_UNIT = nothing) and
 // loads its entries four at a time, the next four being requested while the current four are
 // gathered.  Every lane of the wavefront must call this.
-template <int LPR, int V, bool SINGLE_ROUND>
+template <int LPR, int V, bool S32, bool SINGLE_ROUND>
 __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int row_l, int dst_l, int lane)
 {
     constexpr int G = 64 / LPR;
@@ -246,7 +276,7 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
         v_l[i] = ok ? a.vals[idx] : 0.f;
     }
     if (SINGLE_ROUND) {
-        batch_gather<LPR, V, false>(acc, a, c_l, v_l, grp, colc);
+        batch_gather<LPR, V, S32, false>(acc, a, c_l, v_l, grp, colc);
     } else {
         int k = 0;
         bool first = true;
@@ -261,8 +291,8 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
                 cn[i] = ok ? a.colidx[idx] : -1;
                 vn[i] = ok ? a.vals[idx] : 0.f;
             }
-            if (first) batch_gather<LPR, V, false>(acc, a, c_l, v_l, grp, colc);
-            else batch_gather<LPR, V, true>(acc, a, c_l, v_l, grp, colc);
+            if (first) batch_gather<LPR, V, S32, false>(acc, a, c_l, v_l, grp, colc);
+            else batch_gather<LPR, V, S32, true>(acc, a, c_l, v_l, grp, colc);
             first = false;
             if (!__any(more)) break;
 #pragma unroll
@@ -279,10 +309,9 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
 }
 
 // Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup.
-template <int LPR, int V>
+template <int LPR, int V, bool S32>
 __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
 {
-    constexpr int GROUPS = 64 / LPR; // lane groups per wavefront
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cls = blockIdx.x % a.n_classes, j = blockIdx.x / a.n_classes;
     const int idx = j * 4 + wave;
@@ -292,7 +321,7 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
     const int col = a.col0 + sub * V;
     const bool active = col < a.col_end;
     Acc<V> acc;
-    if (active) gather_accumulate<V>(acc, a, s.y + grp, s.z, GROUPS, col);
+    wave_gather<LPR, V, S32>(acc, a, s.y, s.z, lane, grp, active ? col : a.col0);
 #pragma unroll
     for (int m = LPR; m < 64; m <<= 1) acc.add(shfl_xor_acc<V>(acc, m));
     if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
@@ -300,7 +329,7 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
 
 // Batched paths.  Workgroups [0, n_classes * small_blocks): lane-group items of class b mod
 // n_classes; the rest: rows of at most TINY_ROW entries in natural order.
-template <int LPR, int V>
+template <int LPR, int V, bool S32>
 __global__ __launch_bounds__(256) void spmm_batched_kernel(const SpmmArgs a)
 {
     constexpr int UNITS = 8 * (64 / LPR); // rows / lane-group items per wavefront
@@ -316,7 +345,7 @@ __global__ __launch_bounds__(256) void spmm_batched_kernel(const SpmmArgs a)
             const int4 s = *reinterpret_cast<const int4 *>(a.items + a.small_off[cls] + first + lane);
             row_l = s.x; beg_l = s.y; end_l = s.z; dst_l = s.w;
         }
-        batch_units<LPR, V, false>(a, beg_l, end_l, row_l, dst_l, lane);
+        batch_units<LPR, V, S32, false>(a, beg_l, end_l, row_l, dst_l, lane);
     } else {
         const int first = ((blk - small_section) * 4 + wave) * UNITS;
         if (first >= a.n) return; // uniform per wavefront
@@ -326,7 +355,7 @@ __global__ __launch_bounds__(256) void spmm_batched_kernel(const SpmmArgs a)
             const int b = a.rowptr[row], e = a.rowptr[row + 1];
             if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
         }
-        batch_units<LPR, V, true>(a, beg_l, end_l, row_l, dst_l, lane);
+        batch_units<LPR, V, S32, true>(a, beg_l, end_l, row_l, dst_l, lane);
     }
 }
 
@@ -356,20 +385,27 @@ __global__ __launch_bounds__(256) void spmm_fix_kernel(const SpmmArgs a, int32_t
     a.Y[(int64_t)f.x * a.ldy + col] = acc;
 }
 
-template <int LPR, int V>
-int launch_kernels(const SpmmArgs &a, hipStream_t stream)
+template <int LPR, int V, bool S32>
+int launch_variant(const SpmmArgs &a, hipStream_t stream)
 {
     constexpr int units_per_block = 4 * 8 * (64 / LPR);
     const int64_t g1 = (int64_t)a.n_classes * a.big_blocks;
     const int64_t g2 = (int64_t)a.n_classes * a.small_blocks + (a.n + units_per_block - 1) / units_per_block;
     SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
     if (g1 > 0) {
-        spmm_wave_items_kernel<LPR, V><<<(unsigned)g1, 256, 0, stream>>>(a);
+        spmm_wave_items_kernel<LPR, V, S32><<<(unsigned)g1, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
-    spmm_batched_kernel<LPR, V><<<(unsigned)g2, 256, 0, stream>>>(a);
+    spmm_batched_kernel<LPR, V, S32><<<(unsigned)g2, 256, 0, stream>>>(a);
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
+}
+
+template <int LPR, int V>
+int launch_kernels(const SpmmArgs &a, hipStream_t stream)
+{
+    if (V == 4 && a.ldx_bytes != 0) return launch_variant<LPR, V, V == 4>(a, stream);
+    return launch_variant<LPR, V, false>(a, stream);
 }
 
 template <int V>
@@ -417,6 +453,8 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.items = sc.items; a.fix = sc.fix;
     a.X = X; a.Y = Y; a.Add = Add; a.scratch = g->scratch;
     a.ldx = ldx; a.ldy = ldy; a.ldadd = Add ? ldadd : 0;
+    const bool s32 = g->n < (1 << 24) && ldx * 4 < (1 << 24) && (int64_t)g->n * ldx * 4 < ((int64_t)1 << 32);
+    a.ldx_bytes = s32 ? (uint32_t)(ldx * 4) : 0u;
     a.n = (int32_t)g->n;
     a.n_classes = sc.n_classes;
     a.slot_cols = slot_cols; // narrowed below to the pass width
@@ -432,6 +470,7 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     ProfScope prof(Add ? SLICEGCN_PROF_SPMM_ADD : SLICEGCN_PROF_SPMM, width, stream);
     int pass_cols = vec_load ? slot_cols : 64;
     if (pass_cols > 256) pass_cols = 256;
+    if (const char *e = getenv("SLICEGCN_PASS_COLS")) { const int v = atoi(e); if (v >= 4 && v <= pass_cols && v % 4 == 0) pass_cols = v; }
     if (width < pass_cols) a.slot_cols = (int32_t)round_up(width, 4); // one pass: pack the slots densely
     for (int32_t c0 = 0; c0 < width; c0 += pass_cols) {
         a.col0 = c0;
