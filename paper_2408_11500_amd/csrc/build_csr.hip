@@ -108,11 +108,12 @@ __global__ void swap_keys_kernel(const uint64_t *__restrict__ in, int64_t nnz, u
 // ---- schedule ---------------------------------------------------------------------------
 // Per long row: the entries of column class c are [lower_bound(c * cw), lower_bound((c+1) * cw)).
 // counts layout: cnt[(KINDS*c + kind) * (n+1) + row]; kind 0 = wavefront items of rows cut by column
-// class, 1 = wavefront items of rows kept whole, 2 = lane-group items.  A class's wavefront list is
-// its kind-0 items followed by its kind-1 items, so the class-cut pieces (whose gathers stay inside
-// the class's column range) run before the whole rows (whose gathers span every column and would
-// otherwise keep evicting the class's hot rows from the XCD's L2).
-constexpr int KINDS = 3;
+// class, 1 = wavefront items of rows kept whole, 2 = lane-group items of rows cut by column class,
+// 3 = lane-group items that are whole rows.  A class's wavefront list is its kind-0 items followed
+// by its kind-1 items (and likewise kinds 2, 3 for the lane-group list), so the class-cut pieces
+// (whose gathers stay inside the class's column range) run before the whole rows (whose gathers
+// span every column and would otherwise keep evicting the class's hot rows from the XCD's L2).
+constexpr int KINDS = 4;
 struct RowCut {
     int32_t lo[MAX_CLASSES + 1];
 };
@@ -146,7 +147,7 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t 
     if (d <= TINY_ROW) return 0;
     const int own = (int)(r % n_classes);
     if (d <= LONG_ROW) {
-        f(own, 2, beg, end);
+        f(own, 3, beg, end);
         return 1;
     }
     if (n_classes == 1 || d <= part_row) {
@@ -317,7 +318,7 @@ int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStr
         out.big_off[cl] = starts[KINDS * cl];
         out.big_cnt[cl] = starts[KINDS * cl + 2] - starts[KINDS * cl];
         out.small_off[cl] = starts[KINDS * cl + 2];
-        out.small_cnt[cl] = starts[KINDS * cl + 3] - starts[KINDS * cl + 2];
+        out.small_cnt[cl] = starts[KINDS * cl + 4] - starts[KINDS * cl + 2];
     }
     out.n_items = starts[KINDS * n_classes];
     out.n_slots = n_slots;

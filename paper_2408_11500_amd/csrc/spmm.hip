@@ -7,8 +7,9 @@
 //     so one wavefront keeps many independent row gathers in flight and the output stream stays
 //     contiguous;
 //   * lane-group items (whole rows of up to LONG_ROW entries, short class pieces of partitioned
-//     rows): the same batched path, four entries per item per round, the next round's indices
-//     requested before the current round's data is consumed;
+//     rows): one item per lane group at a time, its (column, value) pairs read LPR at a time by the
+//     group's lanes and handed out by cross-lane reads, the next item's pairs requested before the
+//     current item's gathers;
 //   * wavefront items (everything longer, cut at SEG_NNZ entries): the wavefront loads 64
 //     (column, value) pairs per coalesced read, the 64/LPR lane groups take them in turn through
 //     cross-lane reads with eight gathers in flight per lane, and the groups' sums are combined
@@ -135,68 +136,50 @@ __device__ inline void store_cols(const Acc<V> &acc, float *y_row, const float *
     }
 }
 
-// Accumulate the entries [beg, end) of one wavefront item.  The wavefront reads 64 consecutive
-// (column, value) pairs with one coalesced load each, lane i holding entry base + i, and requests
-// the next 64 before it consumes the current ones; sub-step t then hands entry t * G + grp to lane
-// group grp through cross-lane reads, eight sub-steps (eight gathers per lane) at a time.  Full
-// chunks run without any per-entry test; only the last, partial chunk checks entry indices.
-// Every lane of the wavefront must call this (lanes past the last column pass a valid `col` and
-// drop their result).
+// Accumulate one chunk of a wavefront item: lane i holds the (column, value) pair of the chunk's
+// entry i (lanes past the chunk hold a valid column).  Sub-step t hands entry t * G + grp to lane
+// group grp through cross-lane reads, eight sub-steps (eight gathers per lane) at a time.  A
+// full chunk (cnt >= 64) runs without any per-entry test.  Every lane of the wavefront must call
+// this (lanes past the last column pass a valid `col` and drop their result).
 template <int LPR, int V, bool S32>
-__device__ inline void wave_gather(Acc<V> &acc, const SpmmArgs &a, int beg, int end, int lane, int grp, int col)
+__device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, float v_l, int cnt, int grp, int col)
 {
     constexpr int G = 64 / LPR; // lane groups = entries per sub-step
     constexpr int U = 8;        // gathers in flight per lane
     using L = Ld<V>;
-    if (beg >= end) return;
-    int idx = beg + lane;
-    int c_l = a.colidx[idx < end ? idx : beg];
-    float v_l = a.vals[idx < end ? idx : beg];
-    for (int base = beg; base < end; base += 64) {
-        int c_n = 0;
-        float v_n = 0.f;
-        if (base + 64 < end) { // wavefront-uniform
-            idx = base + 64 + lane;
-            c_n = a.colidx[idx < end ? idx : beg];
-            v_n = a.vals[idx < end ? idx : beg];
-        }
-        const int cnt = end - base; // entries of this chunk (>= 64: a full chunk)
-        if (cnt >= 64) {
+    if (cnt >= 64) {
 #pragma unroll
-            for (int t = 0; t < LPR; t += U) {
-                int c[U];
-                float v[U];
-                typename L::T x[U];
+        for (int t = 0; t < LPR; t += U) {
+            int c[U];
+            float v[U];
+            typename L::T x[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    c[u] = __shfl(c_l, (t + u) * G + grp, 64);
-                    v[u] = __shfl(v_l, (t + u) * G + grp, 64);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc.fma(v[u], x[u]);
+            for (int u = 0; u < U; ++u) {
+                c[u] = __shfl(c_l, (t + u) * G + grp, 64);
+                v[u] = __shfl(v_l, (t + u) * G + grp, 64);
             }
-        } else {
-            for (int t = 0; t * G < cnt; t += U) { // uniform trip count
-                int c[U];
-                float v[U];
-                typename L::T x[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int src = ((t + u) * G + grp) & 63; // lanes past cnt hold the item's first entry (in bounds)
-                    c[u] = __shfl(c_l, src, 64);
-                    v[u] = __shfl(v_l, src, 64);
-                }
+            for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
 #pragma unroll
-                for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if ((t + u) * G + grp < cnt) acc.fma(v[u], x[u]);
-            }
+            for (int u = 0; u < U; ++u) acc.fma(v[u], x[u]);
         }
-        c_l = c_n;
-        v_l = v_n;
+    } else {
+        for (int t = 0; t * G < cnt; t += U) { // uniform trip count
+            int c[U];
+            float v[U];
+            typename L::T x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int src = ((t + u) * G + grp) & 63;
+                c[u] = __shfl(c_l, src, 64);
+                v[u] = __shfl(v_l, src, 64);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if ((t + u) * G + grp < cnt) acc.fma(v[u], x[u]);
+        }
     }
 }
 
@@ -218,8 +201,7 @@ constexpr int NO_UNIT = INT32_MIN;
 // One gather phase of the batched path: sub-round t hands unit (t * GROUPS + grp) of the wavefront
 // to lane group grp.  c_l / v_l hold, per lane, four (column, value) pairs of the unit that lane
 // owns (column -1 = no entry).  Two sub-rounds (eight gathers per lane) are in flight at a time.
-// SKIP_EMPTY adds a wavefront-uniform test that skips sub-round pairs with no entry at all.
-template <int LPR, int V, bool S32, bool SKIP_EMPTY>
+template <int LPR, int V, bool S32>
 __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const int (&c_l)[4], const float (&v_l)[4],
                                     int grp, int colc)
 {
@@ -236,7 +218,6 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
                 cc[u][i] = __shfl(c_l[i], (t0 + u) * G + grp, 64);
                 vv[u][i] = __shfl(v_l[i], (t0 + u) * G + grp, 64);
             }
-        if (SKIP_EMPTY && !__any(cc[0][0] >= 0 || cc[1][0] >= 0)) continue; // entries fill from slot 0
         typename L::T x[2][4];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -253,11 +234,10 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
     }
 }
 
-// Batched path: up to 8 * GROUPS work units (rows or lane-group items) per wavefront.  Index
-// phase: lane i owns unit i (entries [beg_l, end_l), destination dst_l, NO_UNIT = nothing) and
-// loads its entries four at a time, the next four being requested while the current four are
-// gathered.  Every lane of the wavefront must call this.
-template <int LPR, int V, bool S32, bool SINGLE_ROUND>
+// Rows of at most TINY_ROW (= 4) entries: 8 * GROUPS rows per wavefront.  Lane i owns row i
+// (entries [beg_l, end_l), destination dst_l, NO_UNIT = nothing) and loads its entries; the gather
+// phase hands them to the lane groups.  Every lane of the wavefront must call this.
+template <int LPR, int V, bool S32>
 __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int row_l, int dst_l, int lane)
 {
     constexpr int G = 64 / LPR;
@@ -275,31 +255,7 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
         c_l[i] = ok ? a.colidx[idx] : -1;
         v_l[i] = ok ? a.vals[idx] : 0.f;
     }
-    if (SINGLE_ROUND) {
-        batch_gather<LPR, V, S32, false>(acc, a, c_l, v_l, grp, colc);
-    } else {
-        int k = 0;
-        bool first = true;
-        while (true) {
-            const bool more = beg_l + k + 4 < end_l;
-            int cn[4];
-            float vn[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { // request the next four entries before consuming the current ones
-                const int idx = beg_l + k + 4 + i;
-                const bool ok = idx < end_l;
-                cn[i] = ok ? a.colidx[idx] : -1;
-                vn[i] = ok ? a.vals[idx] : 0.f;
-            }
-            if (first) batch_gather<LPR, V, S32, false>(acc, a, c_l, v_l, grp, colc);
-            else batch_gather<LPR, V, S32, true>(acc, a, c_l, v_l, grp, colc);
-            first = false;
-            if (!__any(more)) break;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { c_l[i] = cn[i]; v_l[i] = vn[i]; }
-            k += 4;
-        }
-    }
+    batch_gather<LPR, V, S32>(acc, a, c_l, v_l, grp, colc);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const int d = __shfl(dst_l, t * G + grp, 64);
@@ -308,55 +264,138 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
     }
 }
 
-// Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup.
+// Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup.  An item's
+// entries are read 64 (column, value) pairs at a time with one coalesced load each, lane i holding
+// entry base + i, and the next 64 are requested before the current ones are consumed.  (Giving a
+// wavefront several items and prefetching across them was measured and changes nothing: the
+// kernel is bound by the traffic of the gathers, not by the latency of its index loads.)
 template <int LPR, int V, bool S32>
 __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cls = blockIdx.x % a.n_classes, j = blockIdx.x / a.n_classes;
-    const int idx = j * 4 + wave;
-    if (idx >= a.big_cnt[cls]) return; // uniform per wavefront
-    const int4 s = *reinterpret_cast<const int4 *>(a.items + a.big_off[cls] + idx);
+    const int item = j * 4 + wave;
+    if (item >= a.big_cnt[cls]) return; // uniform per wavefront
+    const int4 s = *reinterpret_cast<const int4 *>(a.items + a.big_off[cls] + item);
     const int grp = lane / LPR, sub = lane % LPR;
     const int col = a.col0 + sub * V;
     const bool active = col < a.col_end;
+    const int colc = active ? col : a.col0;
+    const int beg = s.y, end = s.z;
     Acc<V> acc;
-    wave_gather<LPR, V, S32>(acc, a, s.y, s.z, lane, grp, active ? col : a.col0);
+    int idx = beg + lane;
+    int c_l = a.colidx[idx < end ? idx : beg];
+    float v_l = a.vals[idx < end ? idx : beg];
+    for (int base = beg; base < end; base += 64) {
+        int c_n = 0;
+        float v_n = 0.f;
+        if (base + 64 < end) { // wavefront-uniform
+            idx = base + 64 + lane;
+            c_n = a.colidx[idx < end ? idx : beg];
+            v_n = a.vals[idx < end ? idx : beg];
+        }
+        gather_chunk<LPR, V, S32>(acc, a, c_l, v_l, end - base, grp, colc);
+        c_l = c_n;
+        v_l = v_n;
+    }
 #pragma unroll
     for (int m = LPR; m < 64; m <<= 1) acc.add(shfl_xor_acc<V>(acc, m));
     if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
 }
 
-// Batched paths.  Workgroups [0, n_classes * small_blocks): lane-group items of class b mod
-// n_classes; the rest: rows of at most TINY_ROW entries in natural order.
+// Lane-group items (whole rows of 5..LONG_ROW entries, class pieces of at most SMALL_ITEM entries;
+// never more than 32 entries): workgroup b serves class b mod n_classes.  Lane i of a wavefront
+// reads the descriptor of item i; round r hands item r * G + grp to lane group grp.  The group
+// reads the item's (column, value) pairs with one read per LPR entries (lane `sub` holds entries
+// sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
+// gather takes its pair from the holding lane by a cross-lane read, eight gathers in flight.
 template <int LPR, int V, bool S32>
-__global__ __launch_bounds__(256) void spmm_batched_kernel(const SpmmArgs a)
+__global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
 {
-    constexpr int UNITS = 8 * (64 / LPR); // rows / lane-group items per wavefront
-    const int blk = blockIdx.x;
+    constexpr int G = 64 / LPR;                 // items in flight per wavefront
+    constexpr int UNITS = 8 * G;                // items per wavefront
+    constexpr int K = LPR >= 32 ? 1 : 32 / LPR; // index registers per lane (K * LPR >= 32 entries)
+    constexpr int U = 8;
+    using L = Ld<V>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int small_section = a.n_classes * a.small_blocks;
-    if (blk < small_section) {
-        const int cls = blk % a.n_classes, j = blk / a.n_classes;
-        const int first = (j * 4 + wave) * UNITS;
-        if (first >= a.small_cnt[cls]) return; // uniform per wavefront
-        int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
-        if (lane < UNITS && first + lane < a.small_cnt[cls]) {
-            const int4 s = *reinterpret_cast<const int4 *>(a.items + a.small_off[cls] + first + lane);
-            row_l = s.x; beg_l = s.y; end_l = s.z; dst_l = s.w;
-        }
-        batch_units<LPR, V, S32, false>(a, beg_l, end_l, row_l, dst_l, lane);
-    } else {
-        const int first = ((blk - small_section) * 4 + wave) * UNITS;
-        if (first >= a.n) return; // uniform per wavefront
-        int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
-        if (lane < UNITS && first + lane < a.n) {
-            const int row = first + lane;
-            const int b = a.rowptr[row], e = a.rowptr[row + 1];
-            if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
-        }
-        batch_units<LPR, V, S32, true>(a, beg_l, end_l, row_l, dst_l, lane);
+    const int cls = blockIdx.x % a.n_classes, blk = blockIdx.x / a.n_classes;
+    const int first = (blk * 4 + wave) * UNITS;
+    const int count = a.small_cnt[cls] - first;
+    if (count <= 0) return; // uniform per wavefront
+    int4 d = make_int4(0, 0, 0, NO_UNIT);
+    if (lane < UNITS && lane < count) d = *reinterpret_cast<const int4 *>(a.items + a.small_off[cls] + first + lane);
+    const int grp = lane / LPR, sub = lane % LPR, gbase = lane - sub;
+    const int col = a.col0 + sub * V;
+    const bool col_ok = col < a.col_end;
+    const int colc = col_ok ? col : a.col0;
+    const int rounds = ((count < UNITS ? count : UNITS) + G - 1) / G;
+    int beg = __shfl(d.y, grp, 64), end = __shfl(d.z, grp, 64);
+    int c_k[K];
+    float v_k[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int e = beg + sub + LPR * k;
+        const bool ok = e < end;
+        c_k[k] = ok ? a.colidx[e] : 0;
+        v_k[k] = ok ? a.vals[e] : 0.f;
     }
+    for (int r = 0; r < rounds; ++r) {
+        const int row = __shfl(d.x, r * G + grp, 64), dst = __shfl(d.w, r * G + grp, 64);
+        const int len = end - beg;
+        const int nsrc = (r + 1 < rounds ? (r + 1) * G : 0) + grp;
+        const int nbeg = __shfl(d.y, nsrc, 64), nend = r + 1 < rounds ? __shfl(d.z, nsrc, 64) : nbeg;
+        int c_n[K];
+        float v_n[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) { // the next round's pairs (none after the last round: nend == nbeg)
+            const int e = nbeg + sub + LPR * k;
+            const bool ok = e < nend;
+            c_n[k] = ok ? a.colidx[e] : 0;
+            v_n[k] = ok ? a.vals[e] : 0.f;
+        }
+        Acc<V> acc;
+#pragma unroll
+        for (int j0 = 0; j0 < 32; j0 += U) {
+            if (!__any(j0 < len)) break; // wavefront-uniform
+            int c[U];
+            float v[U];
+            typename L::T x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = j0 + u;
+                const int cc = __shfl(c_k[jj / LPR < K ? jj / LPR : 0], gbase + jj % LPR, 64);
+                v[u] = __shfl(v_k[jj / LPR < K ? jj / LPR : 0], gbase + jj % LPR, 64);
+                c[u] = jj < len ? cc : 0; // an absent entry re-reads row 0 and is not accumulated
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], colc);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (j0 + u < len) acc.fma(v[u], x[u]);
+        }
+        if (dst != NO_UNIT && col_ok) store_result<V>(acc, a, row, dst, col);
+        beg = nbeg;
+        end = nend;
+#pragma unroll
+        for (int k = 0; k < K; ++k) { c_k[k] = c_n[k]; v_k[k] = v_n[k]; }
+    }
+}
+
+// Rows of at most TINY_ROW entries, 64 consecutive rows per wavefront in natural order.
+template <int LPR, int V, bool S32>
+__global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a)
+{
+    constexpr int UNITS = 8 * (64 / LPR); // rows per wavefront
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int first = (blockIdx.x * 4 + wave) * UNITS;
+    if (first >= a.n) return; // uniform per wavefront
+    int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
+    if (lane < UNITS && first + lane < a.n) {
+        const int row = first + lane;
+        const int b = a.rowptr[row], e = a.rowptr[row + 1];
+        if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
+    }
+    batch_units<LPR, V, S32>(a, beg_l, end_l, row_l, dst_l, lane);
 }
 
 // Rows with several items: add the partial slots in order.  One thread per (row, column); eight
@@ -390,13 +429,18 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
 {
     constexpr int units_per_block = 4 * 8 * (64 / LPR);
     const int64_t g1 = (int64_t)a.n_classes * a.big_blocks;
-    const int64_t g2 = (int64_t)a.n_classes * a.small_blocks + (a.n + units_per_block - 1) / units_per_block;
-    SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+    const int64_t g2 = (int64_t)a.n_classes * a.small_blocks;
+    const int64_t g3 = (a.n + units_per_block - 1) / units_per_block;
+    SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX && g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
     if (g1 > 0) {
         spmm_wave_items_kernel<LPR, V, S32><<<(unsigned)g1, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
-    spmm_batched_kernel<LPR, V, S32><<<(unsigned)g2, 256, 0, stream>>>(a);
+    if (g2 > 0) {
+        spmm_group_items_kernel<LPR, V, S32><<<(unsigned)g2, 256, 0, stream>>>(a);
+        SG_LAUNCH_CHECK();
+    }
+    spmm_tiny_rows_kernel<LPR, V, S32><<<(unsigned)g3, 256, 0, stream>>>(a);
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
 }
