@@ -50,8 +50,9 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 // Items of class c are executed by workgroups whose index is c modulo n_classes; with 8 classes
 // and the round-robin placement of workgroups over the 8 XCDs, each XCD's L2 only ever sees its
 // own eighth of the columns of the gathered operand for the partitioned rows.  Whole-row items
-// take class (row mod n_classes).  A row with several items gets one partial-sum slot per item
-// and is finished by a fix-up pass that adds the slots in order.
+// take class (row mod n_classes) and sit behind the class pieces in their class's list.  A row
+// with several items gets one partial-sum slot per item and is finished by a fix-up pass that adds
+// the slots in order.
 constexpr int TINY_ROW = 4;
 constexpr int LONG_ROW = 32;
 constexpr int PART_ROW = 256;
@@ -77,7 +78,7 @@ struct FixRow { // a row whose items went to partial slots [slot_beg, slot_end)
 
 struct Schedule {
     int32_t n_classes = 0;
-    Segment *items = nullptr; // all items, ordered by (class, wavefront items before lane-group items, row, piece)
+    Segment *items = nullptr; // all items, ordered by (class, wavefront before lane-group items, class pieces before whole rows, row, piece)
     FixRow *fix = nullptr;
     int32_t big_off[MAX_CLASSES] = {0}, big_cnt[MAX_CLASSES] = {0};
     int32_t small_off[MAX_CLASSES] = {0}, small_cnt[MAX_CLASSES] = {0};
