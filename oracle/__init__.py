@@ -213,3 +213,51 @@ def encode_concat_bwd(dH, widths, want_dE: bool = True):
                                         _p(dE, ctypes.c_double), ctypes.c_int64(lde))
     _check(rc, "encode_concat_bwd")
     return outs, dE
+
+
+def linear_fwd(X, W, b=None, act: int = 0):
+    """Dense layer Y = act(X W + b).  Returns (Y, P) with P the pre-activation."""
+    X, W, b = map(_f64, (X, W, b))
+    n, w_in = X.shape
+    if W.shape[0] != w_in:
+        raise ValueError("weight shape does not match the input width")
+    w_out = W.shape[1]
+    P = np.empty((n, w_out)); Y = np.empty((n, w_out))
+    d = ctypes.c_double
+    rc = lib().oracle_linear_fwd(ctypes.c_int64(n), ctypes.c_int32(w_in), ctypes.c_int32(w_out), ctypes.c_int(act),
+                                 _p(X, d), ctypes.c_int64(w_in), _p(W, d), _p(b, d), _p(P, d), _p(Y, d), ctypes.c_int64(w_out))
+    _check(rc, "linear_fwd")
+    return Y, P
+
+
+def linear_bwd(X, W, mask, dY, need_dX: bool = True):
+    """Backward of the dense layer for the given 0/1 activation pattern.  Returns dict(dX, dW, db)."""
+    X, W, dY = map(_f64, (X, W, dY))
+    n, w_in = X.shape
+    w_out = W.shape[1]
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.shape != (n, w_out) or dY.shape != (n, w_out):
+        raise ValueError("shape mismatch")
+    d = ctypes.c_double
+    dX = np.empty((n, w_in)) if need_dX else None
+    dW = np.empty((w_in, w_out)); db = np.empty(w_out)
+    rc = lib().oracle_linear_bwd(ctypes.c_int64(n), ctypes.c_int32(w_in), ctypes.c_int32(w_out), _p(X, d), ctypes.c_int64(w_in),
+                                 _p(W, d), _p(mask, ctypes.c_uint8), _p(dY, d), ctypes.c_int64(w_out),
+                                 _p(dX, d), ctypes.c_int64(w_in), _p(dW, d), _p(db, d))
+    _check(rc, "linear_bwd")
+    return dict(dX=dX, dW=dW, db=db)
+
+
+def softmax_ce(logits, labels, want_grad: bool = True):
+    """Mean softmax cross-entropy over all rows.  Returns (loss, dlogits or None)."""
+    logits = _f64(logits)
+    n, c = logits.shape
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    if labels.shape != (n,):
+        raise ValueError("one label per row expected")
+    loss = ctypes.c_double(0.0)
+    dl = np.empty((n, c)) if want_grad else None
+    rc = lib().oracle_softmax_ce(ctypes.c_int64(n), ctypes.c_int32(c), _p(logits, ctypes.c_double), ctypes.c_int64(c),
+                                 _p(labels, ctypes.c_int32), ctypes.byref(loss), _p(dl, ctypes.c_double), ctypes.c_int64(c))
+    _check(rc, "softmax_ce")
+    return loss.value, dl

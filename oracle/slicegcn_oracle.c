@@ -15,7 +15,8 @@
  * Pins (see tests/test_oracle_*.py): dense brute force on tiny graphs, closed-form graphs
  * (empty, complete, ring, star), the fixed-point invariant of the normalised adjacency,
  * the slice/concat identity, adjoint identities, finite differences, and library
- * cross-checks.  No function here is "parity unpinned".
+ * cross-checks (tests/test_oracle_classifier.py for the dense layer and the loss).  No function
+ * here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -377,6 +378,97 @@ int oracle_encode_concat_bwd(int32_t k, const double *dH, int64_t ldh, int64_t n
             }
         off += widths[i];
     }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Dense layer Y = act(X W + b): the unit the paper's classifier MLP_CLS (classifier equation)
+ * and its feature-fusion MLP_FF (feature-fusion equation) are stacked from.
+ * X: n x w_in (ldx), W: w_in x w_out row-major, b: w_out or NULL, act: 0 identity / 1 ReLU.
+ * P (n x w_out, ld w_out) receives the pre-activation X W + b, Y (ldy) the output.
+ * ---------------------------------------------------------------------------------- */
+int oracle_linear_fwd(int64_t n, int32_t w_in, int32_t w_out, int act, const double *X, int64_t ldx,
+                      const double *W, const double *b, double *P, double *Y, int64_t ldy)
+{
+    if (!X || !W || !P || !Y || n < 1 || w_in < 1 || w_out < 1 || ldx < w_in || ldy < w_out) return ORACLE_EINVAL;
+    if (act != 0 && act != 1) return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; ++v)
+        for (int32_t j = 0; j < w_out; ++j) {
+            double acc = 0.0;
+            for (int32_t t = 0; t < w_in; ++t) acc += X[v * ldx + t] * W[(int64_t)t * w_out + j];
+            if (b) acc += b[j];
+            P[v * w_out + j] = acc;
+            Y[v * ldy + j] = (act == 1 && !(acc > 0.0)) ? 0.0 : acc;
+        }
+    return ORACLE_OK;
+}
+
+/* Backward of the dense layer (chain rule; ReLU'(0) = 0):
+ *   dP = dY * mask;  db = column sums of dP;  dW = X^T dP;  dX = dP W^T.
+ * mask: n x w_out bytes (1 where the activation passed the value; all ones for identity).
+ * Any output pointer may be NULL. */
+int oracle_linear_bwd(int64_t n, int32_t w_in, int32_t w_out, const double *X, int64_t ldx,
+                      const double *W, const uint8_t *mask, const double *dY, int64_t lddy,
+                      double *dX, int64_t lddx, double *dW, double *db)
+{
+    if (!X || !W || !mask || !dY || n < 1 || w_in < 1 || w_out < 1 || ldx < w_in || lddy < w_out) return ORACLE_EINVAL;
+    if (dX && lddx < w_in) return ORACLE_EINVAL;
+    if (db)
+        for (int32_t j = 0; j < w_out; ++j) {
+            double acc = 0.0;
+            for (int64_t v = 0; v < n; ++v) acc += mask[v * w_out + j] ? dY[v * lddy + j] : 0.0;
+            db[j] = acc;
+        }
+    if (dW) {
+#pragma omp parallel for schedule(static)
+        for (int32_t t = 0; t < w_in; ++t)
+            for (int32_t j = 0; j < w_out; ++j) {
+                double acc = 0.0;
+                for (int64_t v = 0; v < n; ++v)
+                    acc += X[v * ldx + t] * (mask[v * w_out + j] ? dY[v * lddy + j] : 0.0);
+                dW[(int64_t)t * w_out + j] = acc;
+            }
+    }
+    if (dX) {
+#pragma omp parallel for schedule(static)
+        for (int64_t v = 0; v < n; ++v)
+            for (int32_t t = 0; t < w_in; ++t) {
+                double acc = 0.0;
+                for (int32_t j = 0; j < w_out; ++j)
+                    acc += (mask[v * w_out + j] ? dY[v * lddy + j] : 0.0) * W[(int64_t)t * w_out + j];
+                dX[v * lddx + t] = acc;
+            }
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Mean softmax cross-entropy over all nodes (the paper's loss equation with every node
+ * labelled):  loss = -(1/n) sum_v log softmax(logits[v, :])[label_v].
+ * log softmax(x)[y] = x_y - log sum_j exp(x_j); the row maximum is subtracted before
+ * exponentiating, which changes nothing mathematically and keeps exp() in range.
+ * dlogits (n x c, ldd; may be NULL) receives the gradient (softmax - onehot) / n.
+ * ---------------------------------------------------------------------------------- */
+int oracle_softmax_ce(int64_t n, int32_t c, const double *logits, int64_t ld, const int32_t *labels,
+                      double *loss, double *dlogits, int64_t ldd)
+{
+    if (!logits || !labels || !loss || n < 1 || c < 1 || ld < c || (dlogits && ldd < c)) return ORACLE_EINVAL;
+    double total = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        const double *x = logits + v * ld;
+        const int32_t y = labels[v];
+        if (y < 0 || y >= c) return ORACLE_ERANGE;
+        double m = x[0];
+        for (int32_t j = 1; j < c; ++j) if (x[j] > m) m = x[j];
+        double sum = 0.0;
+        for (int32_t j = 0; j < c; ++j) sum += exp(x[j] - m);
+        total += (m + log(sum)) - x[y];
+        if (dlogits)
+            for (int32_t j = 0; j < c; ++j)
+                dlogits[v * ldd + j] = (exp(x[j] - m) / sum - (j == y ? 1.0 : 0.0)) / (double)n;
+    }
+    *loss = total / (double)n;
     return ORACLE_OK;
 }
 
