@@ -211,6 +211,51 @@ int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, cons
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Dense layer Y = act(X W + b): the unit the paper's classifier MLP_CLS (its classifier equation:
+ * the concatenated representation goes through an MLP) and its feature-fusion network MLP_FF
+ * (feature-fusion equation) are stacked from.
+ * X: n x w_in (ldx); W: w_in x w_out row-major, contiguous; b: [w_out] or NULL; Y: n x w_out (ldy).
+ * For ACT_RELU the pattern [X W + b > 0] is written to mask (n x mask_words uint32, bit layout as
+ * in slicegcn_layer_saved); for ACT_NONE mask is ignored and may be NULL.  X and Y must not overlap.
+ * EINVAL: NULL X/W/Y, sizes < 1, ld too small, unknown act, mask missing for ACT_RELU.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_linear_fwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out,
+                        const float *W, const float *b, int32_t act, float *Y, int64_t ldy,
+                        uint32_t *mask, int64_t mask_words, void *stream);
+
+/* Bytes of workspace slicegcn_linear_bwd needs when dW or db is wanted (0 on bad input). */
+size_t slicegcn_linear_bwd_workspace_bytes(int64_t n, int32_t w_in, int32_t w_out);
+
+/* Backward of the dense layer (chain rule; ReLU'(0) = 0), with dP = dY * mask:
+ *   dX = dP W^T (n x w_in, lddx);  dW = X^T dP (w_in x w_out);  db = colsum dP.
+ * NULL outputs are skipped (dX = NULL for a first layer over constant inputs).  mask is what
+ * slicegcn_linear_fwd wrote (read only; ignored for ACT_NONE).  The node-axis reductions run in
+ * fp32 over blocks of 1024 rows and are combined in fp64 in a fixed order.  ws: 256-byte aligned,
+ * at least slicegcn_linear_bwd_workspace_bytes bytes when dW or db is non-NULL, else unused.
+ * EINVAL as for the forward; EWORKSPACE when ws is NULL or too small. */
+int slicegcn_linear_bwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out,
+                        const float *W, int32_t act, const uint32_t *mask, int64_t mask_words,
+                        const float *dY, int64_t lddy, float *dX, int64_t lddx, float *dW, float *db,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Mean softmax cross-entropy over all n nodes and its gradient (the paper's loss equation with
+ * every node labelled):
+ *   *loss = -(1/n) sum_v log softmax(logits[v, :])[labels[v]]           (DEVICE float scalar)
+ *   dlogits[v, j] = (softmax(logits[v, :])[j] - [j == labels[v]]) / n   (skipped when NULL)
+ * logits: n x n_classes (ld); labels: DEVICE int32 [n] in [0, n_classes); dlogits may alias
+ * logits only if ldd == ld (each row is fully read before it is written).  Row losses are added
+ * in fp64 in a fixed order.  ws: 256-byte aligned, slicegcn_softmax_ce_workspace_bytes(n) bytes.
+ * Synchronises `stream` (the label check comes back to the host).
+ * EINVAL: NULL pointer, sizes < 1, ld < n_classes; ERANGE: a label outside [0, n_classes)
+ * (outputs are then unspecified); EWORKSPACE: ws NULL or too small.
+ * ------------------------------------------------------------------------------------- */
+size_t slicegcn_softmax_ce_workspace_bytes(int64_t n);
+int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, int32_t n_classes,
+                        const int32_t *labels, float *loss, float *dlogits, int64_t ldd,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the
  * stream each kernel is launched on.  Between slicegcn_profile_begin and slicegcn_profile_end
  * every kernel group the library launches is bracketed by an event pair.  _end synchronises
@@ -224,6 +269,10 @@ int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int64_t n, cons
 #define SLICEGCN_PROF_GRAD_REDUCE 3 /* weight-gradient reductions; width = w_out                      */
 #define SLICEGCN_PROF_CONCAT 4      /* slice encoding / concat / their backward; width = slice width  */
 #define SLICEGCN_PROF_SPMM_ADD 5    /* aggregation pass fused with an addend (backward); operand width */
+#define SLICEGCN_PROF_LINEAR_FWD 6  /* dense layer forward; width = w_out                             */
+#define SLICEGCN_PROF_LINEAR_BWD 7  /* dense layer input gradient; width = w_in                       */
+#define SLICEGCN_PROF_LINEAR_GRAD 8 /* dense layer weight/bias gradients; width = w_out               */
+#define SLICEGCN_PROF_LOSS 9        /* softmax cross-entropy; width = classes                         */
 typedef struct {
     int32_t kind;
     int32_t width;

@@ -29,9 +29,12 @@ EXPORTS = [
     "slicegcn_slice_feature", "slicegcn_spmm_slice", "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
     "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_begin", "slicegcn_profile_end",
+    "slicegcn_linear_fwd", "slicegcn_linear_bwd_workspace_bytes", "slicegcn_linear_bwd",
+    "slicegcn_softmax_ce_workspace_bytes", "slicegcn_softmax_ce",
 ]
 
-PROF_KINDS = {0: "spmm", 1: "dense_fwd", 2: "dense_bwd", 3: "grad_reduce", 4: "concat", 5: "spmm_add"}
+PROF_KINDS = {0: "spmm", 1: "dense_fwd", 2: "dense_bwd", 3: "grad_reduce", 4: "concat", 5: "spmm_add",
+              6: "linear_fwd", 7: "linear_bwd", 8: "linear_grad", 9: "loss"}
 
 
 class SliceGCNError(RuntimeError):
@@ -97,6 +100,13 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_concat_bwd_workspace_bytes.restype = sz
         L.slicegcn_concat_bwd.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, i64, vp, sz, vp]
         L.slicegcn_profile_end.argtypes = [ctypes.POINTER(_ProfileEntry), i32, ctypes.POINTER(i32)]
+        L.slicegcn_linear_fwd.argtypes = [vp, i64, i64, i32, i32, vp, vp, i32, vp, i64, vp, i64, vp]
+        L.slicegcn_linear_bwd_workspace_bytes.argtypes = [i64, i32, i32]
+        L.slicegcn_linear_bwd_workspace_bytes.restype = sz
+        L.slicegcn_linear_bwd.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+        L.slicegcn_softmax_ce_workspace_bytes.argtypes = [i64]
+        L.slicegcn_softmax_ce_workspace_bytes.restype = sz
+        L.slicegcn_softmax_ce.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, sz, vp]
         L.slicegcn_strerror.argtypes = [ctypes.c_int]
         L.slicegcn_strerror.restype = ctypes.c_char_p
         L.slicegcn_last_error.restype = ctypes.c_char_p
@@ -332,6 +342,57 @@ def slicegcn_concat_bwd(dH: torch.Tensor, widths, dHs=None, dE=None, ws=None):
                                      ctypes.addressof(lds) if lds is not None else None, pe, lde,
                                      ws.data_ptr() if ws is not None else None,
                                      ws.numel() * ws.element_size() if ws is not None else 0, _stream()))
+
+
+def _ws(ws):
+    return (ws.data_ptr(), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
+def slicegcn_linear_fwd(X, W, b, Y, mask=None, act: int = ACT_NONE):
+    """Y = act(X W + b); fills mask (n x ceil(w_out/32) int32) for ReLU."""
+    w_in, w_out = int(W.shape[0]), int(W.shape[1])
+    px, ldx = _mat(X, "X")
+    py, ldy = _mat(Y, "Y")
+    if X.shape[1] != w_in or Y.shape[1] != w_out or X.shape[0] != Y.shape[0]:
+        raise ValueError("X, W, Y shapes do not match")
+    pm, ldm = _mat(mask, "mask", torch.int32) if mask is not None else (None, 0)
+    _check(lib().slicegcn_linear_fwd(px, ldx, X.shape[0], w_in, w_out, _vec(W, "W"), _vec(b, "b"), act, py, ldy, pm, ldm,
+                                     _stream()))
+    return Y
+
+
+def slicegcn_linear_bwd_workspace_bytes(n: int, w_in: int, w_out: int) -> int:
+    return int(lib().slicegcn_linear_bwd_workspace_bytes(n, w_in, w_out))
+
+
+def slicegcn_linear_bwd(X, W, mask, dY, dX, dW, db, ws, act: int = ACT_NONE):
+    """dX = (dY * mask) W^T, dW = X^T (dY * mask), db = colsum(dY * mask); None outputs are skipped."""
+    w_in, w_out = int(W.shape[0]), int(W.shape[1])
+    px, ldx = _mat(X, "X")
+    pg, ldg = _mat(dY, "dY")
+    pdx, lddx = _mat(dX, "dX") if dX is not None else (None, 0)
+    pm, ldm = _mat(mask, "mask", torch.int32) if mask is not None else (None, 0)
+    if dW is not None and tuple(dW.shape) != (w_in, w_out):
+        raise ValueError("dW must be w_in x w_out")
+    pws, nws = _ws(ws)
+    _check(lib().slicegcn_linear_bwd(px, ldx, X.shape[0], w_in, w_out, _vec(W, "W"), act, pm, ldm, pg, ldg, pdx, lddx,
+                                     _vec(dW, "dW"), _vec(db, "db"), pws, nws, _stream()))
+
+
+def slicegcn_softmax_ce_workspace_bytes(n: int) -> int:
+    return int(lib().slicegcn_softmax_ce_workspace_bytes(n))
+
+
+def slicegcn_softmax_ce(logits, labels, loss, dlogits, ws):
+    """loss[0] = mean softmax cross-entropy over the rows; dlogits (or None) its gradient."""
+    pl, ld = _mat(logits, "logits")
+    pd, ldd = _mat(dlogits, "dlogits") if dlogits is not None else (None, 0)
+    if labels.shape != (logits.shape[0],):
+        raise ValueError("one label per row expected")
+    pws, nws = _ws(ws)
+    _check(lib().slicegcn_softmax_ce(pl, ld, logits.shape[0], logits.shape[1], _vec(labels, "labels", torch.int32),
+                                     _vec(loss, "loss"), pd, ldd, pws, nws, _stream()))
+    return loss
 
 
 def slicegcn_profile_begin():

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libslicegcn.so")
-SOURCES = ["build_csr.hip", "spmm.hip", "dense.hip", "misc.hip"]
+SOURCES = ["build_csr.hip", "spmm.hip", "dense.hip", "misc.hip", "loss.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions stay off for every kernel in this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -486,7 +486,8 @@ struct ReduceArgs {
     float *partial;                     // [n_row_blocks][stride]
     int64_t n;
     int32_t w_in, w_out;
-    int32_t stride;                     // 2*w_in*w_out + 2*w_out
+    int32_t stride;                     // 2*w_in*w_out + 2*w_out; compact: w_in*w_out + w_out
+    int32_t compact;                    // 1: no self term and no slot for it: [Z^T dP | colsum dP]
 };
 
 __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
@@ -552,7 +553,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
             const int i = i_base + ty * 2 + di, j = j_base + tx * 2 + dj;
             if (i < a.w_in && j < a.w_out) {
                 out[i * a.w_out + j] = accA[di][dj];
-                out[ww + i * a.w_out + j] = accS[di][dj];
+                if (!a.compact) out[ww + i * a.w_out + j] = accS[di][dj];
             }
         }
     if (blockIdx.y == 0 && ty == 0) {
@@ -560,8 +561,8 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
         for (int dj = 0; dj < 2; ++dj) {
             const int j = j_base + tx * 2 + dj;
             if (j < a.w_out) {
-                out[2 * ww + j] = accb[dj];
-                out[2 * ww + a.w_out + j] = accbs[dj];
+                out[(a.compact ? ww : 2 * ww) + j] = accb[dj];
+                if (!a.compact) out[2 * ww + a.w_out + j] = accbs[dj];
             }
         }
     }
@@ -665,13 +666,13 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
             const int i = i_base + il, j = j_base + m;
             if (i < a.w_in && j < a.w_out) {
                 out[i * a.w_out + j] = va;
-                out[ww + i * a.w_out + j] = vs;
+                if (!a.compact) out[ww + i * a.w_out + j] = vs;
             }
         }
         if (blockIdx.y == 0) {
             const int j = j_base + m;
             const float sum = ((bsum[0][lane] + bsum[1][lane]) + bsum[2][lane]) + bsum[3][lane];
-            if (j < a.w_out) out[2 * ww + (h ? a.w_out : 0) + j] = sum;
+            if (j < a.w_out && !(a.compact && h)) out[(a.compact ? ww : 2 * ww) + (h ? a.w_out : 0) + j] = sum;
         }
     }
 }
@@ -893,7 +894,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.Hin = params->W_self ? Hin : nullptr; r.ldi = ldi;
         r.dHout = dHout; r.ldo = ldo;
         r.mask = mask; r.mask_words = saved->mask_words;
-        r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride;
+        r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 0;
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
         if (use_mfma()) grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
         else grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
@@ -929,6 +930,91 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         }
         // padding columns of dZ are never read as data: the aggregation masks them on store
         if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, stream)) return rc;
+    }
+    return SLICEGCN_OK;
+}
+
+// ---- dense layer Y = act(X W + b): the unit of the paper's classifier MLP_CLS and of MLP_FF ----
+static size_t linear_partial_bytes(int64_t n, int32_t w_in, int32_t w_out)
+{
+    const size_t stride = (size_t)w_in * w_out + (size_t)w_out;
+    return (size_t)round_up((int64_t)(red_blocks(n) * stride * sizeof(float)), 256);
+}
+
+extern "C" int slicegcn_linear_fwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out, const float *W,
+                                   const float *b, int32_t act, float *Y, int64_t ldy, uint32_t *mask, int64_t mask_words,
+                                   void *stream_)
+{
+    SG_REQUIRE(X && W && Y, SLICEGCN_EINVAL, "linear_fwd: NULL X, W or Y");
+    SG_REQUIRE(n >= 1 && w_in >= 1 && w_out >= 1, SLICEGCN_EINVAL, "linear_fwd: sizes must be >= 1");
+    SG_REQUIRE(ldx >= w_in && ldy >= w_out, SLICEGCN_EINVAL, "linear_fwd: leading dimension too small");
+    SG_REQUIRE(act == SLICEGCN_ACT_NONE || act == SLICEGCN_ACT_RELU, SLICEGCN_EINVAL, "linear_fwd: unknown act %d", act);
+    if (act == SLICEGCN_ACT_RELU)
+        SG_REQUIRE(mask && mask_words >= (w_out + 31) / 32, SLICEGCN_EINVAL,
+                   "linear_fwd: mask is NULL or mask_words < ceil(w_out / 32)");
+    hipStream_t stream = as_stream(stream_);
+    PairArgs a;
+    a.A1 = X; a.lda1 = ldx; a.A2 = nullptr; a.lda2 = 0;
+    a.B1 = W; a.B2 = nullptr; a.bias1 = b; a.bias2 = nullptr;
+    a.O1 = Y; a.ldo1 = ldy; a.O2 = nullptr; a.ldo2 = 0;
+    a.mask = act == SLICEGCN_ACT_RELU ? mask : nullptr; a.mask_words = mask_words;
+    a.n = n; a.K = w_in; a.Nout = w_out; a.ldw = w_out; a.act = act;
+    ProfScope prof(SLICEGCN_PROF_LINEAR_FWD, w_out, stream);
+    return launch_pair<false>(a, stream);
+}
+
+extern "C" size_t slicegcn_linear_bwd_workspace_bytes(int64_t n, int32_t w_in, int32_t w_out)
+{
+    if (n < 1 || w_in < 1 || w_out < 1) return 0;
+    return linear_partial_bytes(n, w_in, w_out);
+}
+
+extern "C" int slicegcn_linear_bwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out, const float *W,
+                                   int32_t act, const uint32_t *mask, int64_t mask_words, const float *dY, int64_t lddy,
+                                   float *dX, int64_t lddx, float *dW, float *db, void *ws, size_t ws_bytes, void *stream_)
+{
+    SG_REQUIRE(X && W && dY, SLICEGCN_EINVAL, "linear_bwd: NULL X, W or dY");
+    SG_REQUIRE(n >= 1 && w_in >= 1 && w_out >= 1, SLICEGCN_EINVAL, "linear_bwd: sizes must be >= 1");
+    SG_REQUIRE(ldx >= w_in && lddy >= w_out && (dX == nullptr || lddx >= w_in), SLICEGCN_EINVAL,
+               "linear_bwd: leading dimension too small");
+    SG_REQUIRE(act == SLICEGCN_ACT_NONE || act == SLICEGCN_ACT_RELU, SLICEGCN_EINVAL, "linear_bwd: unknown act %d", act);
+    if (act == SLICEGCN_ACT_RELU)
+        SG_REQUIRE(mask && mask_words >= (w_out + 31) / 32, SLICEGCN_EINVAL,
+                   "linear_bwd: mask is NULL or mask_words < ceil(w_out / 32)");
+    hipStream_t stream = as_stream(stream_);
+    const uint32_t *m = act == SLICEGCN_ACT_RELU ? mask : nullptr;
+    if (dW || db) {
+        const size_t need = linear_partial_bytes(n, w_in, w_out);
+        SG_REQUIRE(ws != nullptr && ws_bytes >= need, SLICEGCN_EWORKSPACE, "linear_bwd: workspace of %zu bytes, %zu needed",
+                   ws_bytes, need);
+        SG_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255u) == 0, SLICEGCN_EINVAL, "linear_bwd: workspace not 256-byte aligned");
+        ProfScope prof(SLICEGCN_PROF_LINEAR_GRAD, w_out, stream);
+        const int64_t nb = red_blocks(n);
+        const int ww = w_in * w_out;
+        const int32_t stride = ww + w_out;
+        ReduceArgs r;
+        r.Z = X; r.ldz = ldx; r.Hin = nullptr; r.ldi = 0; r.dHout = dY; r.ldo = lddy;
+        r.mask = m; r.mask_words = mask_words;
+        r.partial = static_cast<float *>(ws); r.n = n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 1;
+        dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
+        if (use_mfma()) grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
+        else grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        SG_LAUNCH_CHECK();
+        FinalDst dst;
+        dst.ptr[0] = dW; dst.ptr[1] = db; dst.ptr[2] = dst.ptr[3] = nullptr;
+        dst.begin[0] = 0; dst.begin[1] = ww; dst.begin[2] = dst.begin[3] = dst.begin[4] = stride;
+        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(r.partial, nb, stride, stride, dst);
+        SG_LAUNCH_CHECK();
+    }
+    if (dX) {
+        PairArgs a;
+        a.A1 = dY; a.lda1 = lddy; a.A2 = nullptr; a.lda2 = 0;
+        a.B1 = W; a.B2 = nullptr; a.bias1 = a.bias2 = nullptr;
+        a.O1 = dX; a.ldo1 = lddx; a.O2 = nullptr; a.ldo2 = 0;
+        a.mask = const_cast<uint32_t *>(m); a.mask_words = mask_words;
+        a.n = n; a.K = w_out; a.Nout = w_in; a.ldw = w_out; a.act = act;
+        ProfScope prof(SLICEGCN_PROF_LINEAR_BWD, w_in, stream);
+        if (int rc = launch_pair<true>(a, stream)) return rc;
     }
     return SLICEGCN_OK;
 }
