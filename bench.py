@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 4 GiB device copy (reference for HBM byte counters) and exit")
     ap.add_argument("--spmm-only", type=int, default=0, help="time only this many round-robin slice aggregations per step")
+    ap.add_argument("--classifier", action="store_true",
+                    help="widen the step by the classifier MLP and the cross-entropy loss: the upstream gradient of the "
+                         "slice stack then comes from the loss instead of a seeded random matrix")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all k slices execute sequentially on it); "
@@ -81,7 +84,7 @@ def main():
     import synth
     from synth import configs, model
     import paper_2408_11500_amd as sg
-    from paper_2408_11500_amd.stack import SliceStack
+    from paper_2408_11500_amd.stack import Classifier, SliceStack
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -130,6 +133,11 @@ def main():
     del X
     st.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, device=dev, std=0.1))
     dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * hs, device=dev)
+    cls = labels = None
+    if args.classifier:
+        cls = Classifier(n, k * hs, w.hidden, w.classes, device=dev)
+        cls.set_params(*model.classifier_params(w, k * hs, device=dev))
+        labels = configs.labels(w, device=dev).to(torch.int32)
     torch.cuda.synchronize()
     log("inputs resident")
 
@@ -140,7 +148,9 @@ def main():
             for j in range(args.spmm_only):   # round-robin over the slices, as in the real pass
                 sg.slicegcn_spmm_slice(g, st.X[j % k][:, :width], Yspmm[:, :width])
         else:
-            st.forward()
+            H = st.forward()
+            if cls is not None:
+                cls.forward_backward(H, labels, dH)
             st.backward(dH)
 
     for _ in range(args.warmup):
@@ -178,7 +188,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={n}, nnz={view.nnz} (R-MAT, symmetrised + self loops), F={w.feat} in k={k} "
                                f"slices of {width}, {L} layers, per-slice hidden {hs}, full-batch fwd+bwd"
-                               + (" [aggregation only]" if args.spmm_only else ""),
+                               + (" [aggregation only]" if args.spmm_only else "")
+                               + (f" + classifier {k * hs}->{w.hidden}->{w.classes} and cross-entropy" if cls is not None else ""),
                    "n_nodes": n, "nnz": view.nnz, "k": k, "slice_width": width, "slice_hidden": hs, "layers": L},
         "epoch_ms": None if args.spmm_only else ms_per_step,
         "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,

@@ -98,3 +98,49 @@ class SliceStack:
                                      g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws,
                                      act=self.act(l))
                 g_out = g_in
+
+
+class Classifier:
+    """The paper's MLP_CLS on the concatenated representation followed by the mean softmax
+    cross-entropy of its loss equation: logits = relu(H W1 + b1) W2 + b2.  Owns buffers and orders
+    the library calls; every arithmetic step is a kernel of ``libslicegcn.so``."""
+
+    def __init__(self, n_nodes: int, width: int, hidden: int, classes: int, device="cuda"):
+        self.n, self.w, self.h, self.c = n_nodes, width, hidden, classes
+        self.dev = torch.device(device)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.W1 = torch.zeros((width, hidden), **f32); self.b1 = torch.zeros(hidden, **f32)
+        self.W2 = torch.zeros((hidden, classes), **f32); self.b2 = torch.zeros(classes, **f32)
+        self.dW1 = torch.empty_like(self.W1); self.db1 = torch.empty_like(self.b1)
+        self.dW2 = torch.empty_like(self.W2); self.db2 = torch.empty_like(self.b2)
+        self.A = torch.empty((n_nodes, hidden), **f32)
+        self.dA = torch.empty((n_nodes, hidden), **f32)
+        self.mask = torch.zeros((n_nodes, (hidden + 31) // 32), dtype=torch.int32, device=self.dev)
+        self.logits = torch.empty((n_nodes, classes), **f32)  # overwritten by its own gradient in backward
+        self.loss = torch.zeros(1, **f32)
+        ws = max(B.slicegcn_softmax_ce_workspace_bytes(n_nodes), B.slicegcn_linear_bwd_workspace_bytes(n_nodes, width, hidden),
+                 B.slicegcn_linear_bwd_workspace_bytes(n_nodes, hidden, classes))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    def set_params(self, W1, b1, W2, b2):
+        for dst, src in ((self.W1, W1), (self.b1, b1), (self.W2, W2), (self.b2, b2)):
+            dst.copy_(src)
+
+    def forward(self, H: torch.Tensor, labels: torch.Tensor) -> torch.Tensor:
+        """Loss of the batch (device scalar).  Leaves the gradient of the loss with respect to the
+        logits in ``self.logits`` for ``backward``."""
+        B.slicegcn_linear_fwd(H, self.W1, self.b1, self.A, self.mask, act=B.ACT_RELU)
+        B.slicegcn_linear_fwd(self.A, self.W2, self.b2, self.logits, None, act=B.ACT_NONE)
+        B.slicegcn_softmax_ce(self.logits, labels, self.loss, self.logits, self.ws)  # gradient in place
+        return self.loss
+
+    def backward(self, H: torch.Tensor, dH: torch.Tensor):
+        """dH receives the gradient of the loss with respect to H; the parameter gradients go to
+        dW1, db1, dW2, db2."""
+        B.slicegcn_linear_bwd(self.A, self.W2, None, self.logits, self.dA, self.dW2, self.db2, self.ws, act=B.ACT_NONE)
+        B.slicegcn_linear_bwd(H, self.W1, self.mask, self.dA, dH, self.dW1, self.db1, self.ws, act=B.ACT_RELU)
+
+    def forward_backward(self, H: torch.Tensor, labels: torch.Tensor, dH: torch.Tensor) -> torch.Tensor:
+        self.forward(H, labels)
+        self.backward(H, dH)
+        return self.loss

@@ -58,3 +58,17 @@ def slice_layer_params(w: configs.Workload, slice_id: int, layer: int, w_in: int
         b = torch.zeros(w_out, dtype=torch.float32, device=device)
         b_self = torch.zeros(w_out, dtype=torch.float32, device=device)
     return W_agg, b, W_self, b_self
+
+
+def classifier_params(w: configs.Workload, width: int, device="cpu", bias_std: float = 0.0):
+    """Seeded Glorot weights of the classifier MLP (width -> hidden -> classes); biases as above."""
+    tag = 1 << 20
+    W1 = configs.glorot(w.seed, tag, width, w.hidden, device)
+    W2 = configs.glorot(w.seed, tag + 1, w.hidden, w.classes, device)
+    if bias_std > 0:
+        b1 = (rng.normal(w.seed, configs.STREAM_W, rng.arange64(w.hidden, device) + ((tag + 2) << 32)) * bias_std).to(torch.float32)
+        b2 = (rng.normal(w.seed, configs.STREAM_W, rng.arange64(w.classes, device) + ((tag + 3) << 32)) * bias_std).to(torch.float32)
+    else:
+        b1 = torch.zeros(w.hidden, dtype=torch.float32, device=device)
+        b2 = torch.zeros(w.classes, dtype=torch.float32, device=device)
+    return W1, b1, W2, b2

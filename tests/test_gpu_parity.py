@@ -12,7 +12,7 @@ import synth
 from synth import configs, model
 import paper_2408_11500_amd as sg
 from paper_2408_11500_amd import binding as B
-from paper_2408_11500_amd.stack import SliceStack, padded_ld
+from paper_2408_11500_amd.stack import Classifier, SliceStack, padded_ld
 from gpu_util import (TOL, assert_close, dev, hub_edges, messy_edges, pack_mask, padded, rel_err, unpack_mask)
 
 pytestmark = pytest.mark.gpu
@@ -285,8 +285,10 @@ def test_concat_fwd_bwd():
 
 
 # ---------------------------------------------------------------------------------------
-def run_epoch_parity(w, slice_hidden, bias_std=0.05):
-    """All k slices x L layers + encoding/concat, forward and backward, against the oracle."""
+def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False):
+    """All k slices x L layers + encoding/concat, forward and backward, against the oracle.  With
+    ``classifier`` the upstream gradient comes from the classifier MLP and the cross-entropy loss
+    (also checked against the oracle) instead of a seeded random matrix."""
     s, d = configs.edges(w)
     o, g = build_both(s.numpy(), d.numpy(), w.n_nodes)
     k, L, n = w.k, w.layers, w.n_nodes
@@ -331,8 +333,34 @@ def run_epoch_parity(w, slice_hidden, bias_std=0.05):
             flips += int(differ.sum())
             st.mask[i][l].copy_(torch.as_tensor(pack_mask((Po > 0).astype(np.uint8))))
 
-    dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * slice_hidden)
-    st.backward(dH.cuda())
+    if classifier:
+        cp = model.classifier_params(w, k * slice_hidden, bias_std=bias_std)
+        W1, b1, W2, b2 = (t.numpy() for t in cp)
+        y = configs.labels(w)
+        cl = Classifier(n, k * slice_hidden, w.hidden, w.classes)
+        cl.set_params(*cp)
+        loss = cl.forward(st.Hcat, y.cuda().to(torch.int32)).item()
+        Ao, P1 = oracle.linear_fwd(want, W1, b1, act=1)
+        Lo, _ = oracle.linear_fwd(Ao, W2, b2, act=0)
+        lo, dLo = oracle.softmax_ce(Lo, y.numpy())
+        assert abs(loss - lo) <= TOL * lo
+        got = unpack_mask(cl.mask.cpu().numpy(), w.hidden)
+        differ = got != (P1 > 0)
+        assert np.all(np.abs(P1[differ]) <= 1e-5 * np.sqrt(np.mean(P1 * P1)))
+        cl.mask.copy_(torch.as_tensor(pack_mask((P1 > 0).astype(np.uint8))))
+        dHd = torch.empty((n, k * slice_hidden), dtype=torch.float32, device="cuda")
+        cl.backward(st.Hcat, dHd)
+        g2 = oracle.linear_bwd(Ao, W2, np.ones_like(Lo, dtype=bool), dLo)
+        g1 = oracle.linear_bwd(want, W1, P1 > 0, g2["dX"])
+        for got_t, want_a, what in ((cl.dW2, g2["dW"], "dW2"), (cl.db2, g2["db"], "db2"), (cl.dW1, g1["dW"], "dW1"),
+                                    (cl.db1, g1["db"], "db1"), (dHd, g1["dX"], "dH from the loss")):
+            assert_close(got_t.cpu().numpy(), want_a, what)
+        dH = torch.as_tensor(g1["dX"], dtype=torch.float32)  # the slice stack is differentiated from the oracle's dH
+        st.backward(dH.cuda())
+        dH = dH.double()
+    else:
+        dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * slice_hidden)
+        st.backward(dH.cuda())
     blocks, dE = oracle.encode_concat_bwd(dH.numpy(), [slice_hidden] * k)
     assert_close(st.dE.cpu().numpy(), dE, "dE")
     worst = 0.0
@@ -358,3 +386,8 @@ def test_epoch_cfg1_both_hidden_readings():
 def test_epoch_cfg2():
     w = synth.WORKLOADS["cfg2"]
     run_epoch_parity(w, w.slice_hidden)
+
+
+def test_epoch_with_classifier_and_loss():
+    w = synth.WORKLOADS["cfg1"]
+    run_epoch_parity(w, w.slice_hidden, classifier=True)
