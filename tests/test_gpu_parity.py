@@ -285,14 +285,16 @@ def test_concat_fwd_bwd():
 
 
 # ---------------------------------------------------------------------------------------
-def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False):
+def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0):
     """All k slices x L layers + encoding/concat, forward and backward, against the oracle.  With
     ``classifier`` the upstream gradient comes from the classifier MLP and the cross-entropy loss
     (also checked against the oracle) instead of a seeded random matrix."""
     s, d = configs.edges(w)
     o, g = build_both(s.numpy(), d.numpy(), w.n_nodes)
     k, L, n = w.k, w.layers, w.n_nodes
-    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
+    sl, _ = sg.slicegcn_slice_strategy(w.feat, k, scale)
+    assert sl == oracle.slice_strategy(w.feat, k, scale)[0]
+    c = sl[0][1] - sl[0][0]  # every slice of a strategy has the same width
     st = SliceStack(g, n, k, c, slice_hidden, L)
     X = configs.features(w)
     Xd = X.cuda()
@@ -386,6 +388,18 @@ def test_epoch_cfg1_both_hidden_readings():
 def test_epoch_cfg2():
     w = synth.WORKLOADS["cfg2"]
     run_epoch_parity(w, w.slice_hidden)
+
+
+def test_epoch_overlapping_and_scaled_slices():
+    """Slice counts that do not divide the feature width (the last slice is shifted left and overlaps
+    its predecessor, as in the paper's start/end equation) and slice_size_scale != 1 (overlaps or gaps)."""
+    import dataclasses
+    base = synth.WORKLOADS["cfg1"]
+    w = dataclasses.replace(base, feat=101, k=3, hidden=96)  # slices (0,34) (34,68) (67,101)
+    assert sg.slicegcn_slice_strategy(101, 3)[0] == [(0, 34), (34, 68), (67, 101)]
+    run_epoch_parity(w, 32)
+    run_epoch_parity(w, 32, scale=1.5)                       # 51 wide: (0,51) (34,85) (50,101)
+    run_epoch_parity(dataclasses.replace(base, feat=50, k=2, hidden=64), 32, scale=0.5)  # 12 wide, gaps
 
 
 def test_epoch_with_classifier_and_loss():
