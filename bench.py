@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 4 GiB device copy (reference for HBM byte counters) and exit")
     ap.add_argument("--spmm-only", type=int, default=0, help="time only this many round-robin slice aggregations per step")
+    ap.add_argument("--ff", action="store_true",
+                    help="feature-fusion variant: a shared two-layer MLP F -> F -> slice width feeds every slice model "
+                         "(learned, so the first layer's input gradient and the MLP's backward join the step)")
     ap.add_argument("--classifier", action="store_true",
                     help="widen the step by the classifier MLP and the cross-entropy loss: the upstream gradient of the "
                          "slice stack then comes from the loss instead of a seeded random matrix")
@@ -84,7 +87,7 @@ def main():
     import synth
     from synth import configs, model
     import paper_2408_11500_amd as sg
-    from paper_2408_11500_amd.stack import Classifier, SliceStack
+    from paper_2408_11500_amd.stack import Classifier, FeatureFusion, SliceStack
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -124,13 +127,20 @@ def main():
 
     slices, width = sg.slicegcn_slice_strategy(w.feat, w.k)
     hs, L, k, n = w.slice_hidden, w.layers, w.k, w.n_nodes
-    st = SliceStack(g, n, k, width, hs, L, device=dev)
     X = configs.features(w, device=dev)
+    ff = None
+    if args.ff:
+        ff = FeatureFusion(n, w.feat, width, device=dev)
+        ff.set_params(*model.fusion_params(w, width, device=dev))
+        ff.forward(X)
+    st = SliceStack(g, n, k, width, hs, L, device=dev, shared_input=ff.Xff if ff is not None else None)
     for i, (a, b) in enumerate(slices):
-        sg.slicegcn_slice_feature(X, a, b, st.X[i])
+        if ff is None:
+            sg.slicegcn_slice_feature(X, a, b, st.X[i])
         for l, (wi, wo) in enumerate(st.widths):
             st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, device=dev))
-    del X
+    if ff is None:
+        del X
     st.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, device=dev, std=0.1))
     dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * hs, device=dev)
     cls = labels = None
@@ -148,10 +158,14 @@ def main():
             for j in range(args.spmm_only):   # round-robin over the slices, as in the real pass
                 sg.slicegcn_spmm_slice(g, st.X[j % k][:, :width], Yspmm[:, :width])
         else:
+            if ff is not None:
+                ff.forward(X)
             H = st.forward()
             if cls is not None:
                 cls.forward_backward(H, labels, dH)
             st.backward(dH)
+            if ff is not None:
+                ff.backward(X, st.dXin[:, :width])
 
     for _ in range(args.warmup):
         step()
@@ -189,6 +203,7 @@ def main():
         "config": {"workload": f"{w.name}: N={n}, nnz={view.nnz} (R-MAT, symmetrised + self loops), F={w.feat} in k={k} "
                                f"slices of {width}, {L} layers, per-slice hidden {hs}, full-batch fwd+bwd"
                                + (" [aggregation only]" if args.spmm_only else "")
+                               + (f" + feature fusion {w.feat}->{w.feat}->{width}" if ff is not None else "")
                                + (f" + classifier {k * hs}->{w.hidden}->{w.classes} and cross-entropy" if cls is not None else ""),
                    "n_nodes": n, "nnz": view.nnz, "k": k, "slice_width": width, "slice_hidden": hs, "layers": L},
         "epoch_ms": None if args.spmm_only else ms_per_step,

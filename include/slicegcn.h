@@ -239,6 +239,15 @@ int slicegcn_linear_bwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, in
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * dst[:, 0:w] += src[:, 0:w] (n rows).  With feature fusion (the paper's feature-fusion equation:
+ * one learned projection feeds every slice model) the gradient of the fused features is the sum
+ * of the k slice models' input gradients; this adds one of them.  dst and src must not overlap.
+ * EINVAL: NULL pointer, sizes < 1, ld < w.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_accumulate(float *dst, int64_t ldd, const float *src, int64_t lds, int64_t n, int32_t w,
+                        void *stream);
+
+/* ---------------------------------------------------------------------------------------
  * Mean softmax cross-entropy over all n nodes and its gradient (the paper's loss equation with
  * every node labelled):
  *   *loss = -(1/n) sum_v log softmax(logits[v, :])[labels[v]]           (DEVICE float scalar)
@@ -273,6 +282,7 @@ int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, int32_t n_cl
 #define SLICEGCN_PROF_LINEAR_BWD 7  /* dense layer input gradient; width = w_in                       */
 #define SLICEGCN_PROF_LINEAR_GRAD 8 /* dense layer weight/bias gradients; width = w_out               */
 #define SLICEGCN_PROF_LOSS 9        /* softmax cross-entropy; width = classes                         */
+#define SLICEGCN_PROF_ACCUM 10      /* gradient accumulation over slices; width = w                   */
 typedef struct {
     int32_t kind;
     int32_t width;

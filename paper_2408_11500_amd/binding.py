@@ -30,11 +30,11 @@ EXPORTS = [
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
     "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_begin", "slicegcn_profile_end",
     "slicegcn_linear_fwd", "slicegcn_linear_bwd_workspace_bytes", "slicegcn_linear_bwd",
-    "slicegcn_softmax_ce_workspace_bytes", "slicegcn_softmax_ce",
+    "slicegcn_softmax_ce_workspace_bytes", "slicegcn_softmax_ce", "slicegcn_accumulate",
 ]
 
 PROF_KINDS = {0: "spmm", 1: "dense_fwd", 2: "dense_bwd", 3: "grad_reduce", 4: "concat", 5: "spmm_add",
-              6: "linear_fwd", 7: "linear_bwd", 8: "linear_grad", 9: "loss"}
+              6: "linear_fwd", 7: "linear_bwd", 8: "linear_grad", 9: "loss", 10: "accumulate"}
 
 
 class SliceGCNError(RuntimeError):
@@ -107,6 +107,7 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_softmax_ce_workspace_bytes.argtypes = [i64]
         L.slicegcn_softmax_ce_workspace_bytes.restype = sz
         L.slicegcn_softmax_ce.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, sz, vp]
+        L.slicegcn_accumulate.argtypes = [vp, i64, vp, i64, i64, i32, vp]
         L.slicegcn_strerror.argtypes = [ctypes.c_int]
         L.slicegcn_strerror.restype = ctypes.c_char_p
         L.slicegcn_last_error.restype = ctypes.c_char_p
@@ -377,6 +378,16 @@ def slicegcn_linear_bwd(X, W, mask, dY, dX, dW, db, ws, act: int = ACT_NONE):
     pws, nws = _ws(ws)
     _check(lib().slicegcn_linear_bwd(px, ldx, X.shape[0], w_in, w_out, _vec(W, "W"), act, pm, ldm, pg, ldg, pdx, lddx,
                                      _vec(dW, "dW"), _vec(db, "db"), pws, nws, _stream()))
+
+
+def slicegcn_accumulate(dst, src):
+    """dst += src (same shape; leading dimensions may differ)."""
+    pd, ldd = _mat(dst, "dst")
+    ps, lds = _mat(src, "src")
+    if dst.shape != src.shape:
+        raise ValueError("dst and src differ in shape")
+    _check(lib().slicegcn_accumulate(pd, ldd, ps, lds, dst.shape[0], dst.shape[1], _stream()))
+    return dst
 
 
 def slicegcn_softmax_ce_workspace_bytes(n: int) -> int:

@@ -95,6 +95,27 @@ __global__ __launch_bounds__(256) void copy_cols_vec_kernel(const float *__restr
     }
 }
 
+// dst[r, c] += src[r, c] for c < w; 16 bytes per thread when VEC (aligned bases, lds and w multiples of 4).
+template <bool VEC>
+__global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ dst, int64_t ldd, const float *__restrict__ src,
+                                                         int64_t lds_, int64_t n, int32_t w)
+{
+    const int q = VEC ? w >> 2 : w; // elements (float4 or float) per row
+    const int64_t total = n * (int64_t)q;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t r = t / q;
+        const int c = (int)(t - r * q);
+        if (VEC) {
+            float4 d = *reinterpret_cast<const float4 *>(dst + r * ldd + 4 * c);
+            const float4 v = *reinterpret_cast<const float4 *>(src + r * lds_ + 4 * c);
+            d.x += v.x; d.y += v.y; d.z += v.z; d.w += v.w;
+            *reinterpret_cast<float4 *>(dst + r * ldd + 4 * c) = d;
+        } else {
+            dst[r * ldd + c] += src[r * lds_ + c];
+        }
+    }
+}
+
 inline unsigned grid_for(int64_t total)
 {
     const int64_t b = (total + 255) / 256;
@@ -118,6 +139,18 @@ int launch_copy_cols(const float *src, int64_t lds_, float *dst, int64_t ldd, in
 } // namespace slicegcn
 
 using namespace slicegcn;
+
+extern "C" int slicegcn_accumulate(float *dst, int64_t ldd, const float *src, int64_t lds_, int64_t n, int32_t w, void *stream)
+{
+    SG_REQUIRE(dst && src, SLICEGCN_EINVAL, "accumulate: NULL pointer");
+    SG_REQUIRE(n >= 1 && w >= 1 && ldd >= w && lds_ >= w, SLICEGCN_EINVAL, "accumulate: sizes or leading dimensions too small");
+    ProfScope prof(SLICEGCN_PROF_ACCUM, w, as_stream(stream));
+    const bool vec = aligned16(dst) && aligned16(src) && ldd % 4 == 0 && lds_ % 4 == 0 && w % 4 == 0;
+    if (vec) accumulate_kernel<true><<<grid_for(n * (w / 4)), 256, 0, as_stream(stream)>>>(dst, ldd, src, lds_, n, w);
+    else accumulate_kernel<false><<<grid_for(n * (int64_t)w), 256, 0, as_stream(stream)>>>(dst, ldd, src, lds_, n, w);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
 
 extern "C" int slicegcn_slice_strategy(int32_t in_d, int32_t p, double slice_size_scale,
                                        int32_t *starts, int32_t *ends, int32_t *slice_size)

@@ -19,7 +19,10 @@ def padded_ld(width: int) -> int:
 
 class SliceStack:
     def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
-                 device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU):
+                 device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU,
+                 shared_input: torch.Tensor | None = None):
+        """``shared_input``: with feature fusion every slice model reads the same fused n x first_width
+        matrix; the stack then also returns the gradient with respect to it (``dXin``)."""
         self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
         self.w0, self.hs = first_width, slice_hidden
         self.dev = torch.device(device)
@@ -27,7 +30,11 @@ class SliceStack:
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.widths = [(first_width if l == 0 else slice_hidden, slice_hidden) for l in range(layers)]
         # inputs
-        self.X = [torch.zeros((n_nodes, padded_ld(first_width)), **f32) for _ in range(k)]
+        self.shared = shared_input is not None
+        self.X = ([shared_input] * k if self.shared
+                  else [torch.zeros((n_nodes, padded_ld(first_width)), **f32) for _ in range(k)])
+        self.dXin = torch.empty((n_nodes, padded_ld(first_width)), **f32) if self.shared else None
+        self.dXtmp = torch.empty((n_nodes, padded_ld(first_width)), **f32) if self.shared and k > 1 else None
         # parameters and their gradients: [slice][layer] -> dict
         self.params = [[None] * layers for _ in range(k)]
         self.grads = [[None] * layers for _ in range(k)]
@@ -43,7 +50,7 @@ class SliceStack:
         self.dbuf = [torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
         ws = 0
         for l, (wi, wo) in enumerate(self.widths):
-            ws = max(ws, B.slicegcn_layer_bwd_workspace_bytes(n_nodes, wi, wo, l > 0))
+            ws = max(ws, B.slicegcn_layer_bwd_workspace_bytes(n_nodes, wi, wo, l > 0 or self.shared))
         ws = max(ws, B.slicegcn_concat_bwd_workspace_bytes(n_nodes, [slice_hidden] * k))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
@@ -93,10 +100,17 @@ class SliceStack:
             for l in reversed(range(self.L)):
                 p, gr = self.params[i][l], self.grads[i][l]
                 wi = self.widths[l][0]
-                g_in = self.dbuf[l % 2][:, :wi] if l > 0 else None  # raw features need no gradient
+                if l > 0:
+                    g_in = self.dbuf[l % 2][:, :wi]
+                elif self.shared:  # the fused features are learned: the first slice writes, the others add
+                    g_in = (self.dXin if i == 0 else self.dXtmp)[:, :wi]
+                else:
+                    g_in = None  # raw features need no gradient
                 B.slicegcn_layer_bwd(self.g, self.hin(i, l), p["W_agg"], p["W_self"], self.Z[i][l][:, :wi], self.mask[i][l],
                                      g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws,
                                      act=self.act(l))
+                if l == 0 and self.shared and i > 0:
+                    B.slicegcn_accumulate(self.dXin[:, :wi], g_in)
                 g_out = g_in
 
 
@@ -144,3 +158,39 @@ class Classifier:
         self.forward(H, labels)
         self.backward(H, dH)
         return self.loss
+
+
+class FeatureFusion:
+    """The paper's MLP_FF (feature-fusion equation; two dense layers d' -> d' -> slice_size with a ReLU
+    between them, shared by all slices): Xff = relu(X W1 + b1) W2 + b2.  Owns buffers and orders the
+    library calls; every arithmetic step is a kernel of ``libslicegcn.so``."""
+
+    def __init__(self, n_nodes: int, feat: int, out_width: int, device="cuda"):
+        self.n, self.f, self.s = n_nodes, feat, out_width
+        self.dev = torch.device(device)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.W1 = torch.zeros((feat, feat), **f32); self.b1 = torch.zeros(feat, **f32)
+        self.W2 = torch.zeros((feat, out_width), **f32); self.b2 = torch.zeros(out_width, **f32)
+        self.dW1 = torch.empty_like(self.W1); self.db1 = torch.empty_like(self.b1)
+        self.dW2 = torch.empty_like(self.W2); self.db2 = torch.empty_like(self.b2)
+        self.A = torch.empty((n_nodes, feat), **f32)
+        self.dA = torch.empty((n_nodes, feat), **f32)
+        self.mask = torch.zeros((n_nodes, (feat + 31) // 32), dtype=torch.int32, device=self.dev)
+        self.Xff = torch.zeros((n_nodes, padded_ld(out_width)), **f32)  # padding columns stay zero
+        ws = max(B.slicegcn_linear_bwd_workspace_bytes(n_nodes, feat, feat),
+                 B.slicegcn_linear_bwd_workspace_bytes(n_nodes, feat, out_width))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    def set_params(self, W1, b1, W2, b2):
+        for dst, src in ((self.W1, W1), (self.b1, b1), (self.W2, W2), (self.b2, b2)):
+            dst.copy_(src)
+
+    def forward(self, X: torch.Tensor) -> torch.Tensor:
+        B.slicegcn_linear_fwd(X, self.W1, self.b1, self.A, self.mask, act=B.ACT_RELU)
+        B.slicegcn_linear_fwd(self.A, self.W2, self.b2, self.Xff[:, :self.s], None, act=B.ACT_NONE)
+        return self.Xff
+
+    def backward(self, X: torch.Tensor, dXff: torch.Tensor):
+        """dXff: n x out_width gradient of the fused features (the sum over the slice models)."""
+        B.slicegcn_linear_bwd(self.A, self.W2, None, dXff, self.dA, self.dW2, self.db2, self.ws, act=B.ACT_NONE)
+        B.slicegcn_linear_bwd(X, self.W1, self.mask, self.dA, None, self.dW1, self.db1, self.ws, act=B.ACT_RELU)

@@ -72,3 +72,17 @@ def classifier_params(w: configs.Workload, width: int, device="cpu", bias_std: f
         b1 = torch.zeros(w.hidden, dtype=torch.float32, device=device)
         b2 = torch.zeros(w.classes, dtype=torch.float32, device=device)
     return W1, b1, W2, b2
+
+
+def fusion_params(w: configs.Workload, out_width: int, device="cpu", bias_std: float = 0.0):
+    """Seeded Glorot weights of the feature-fusion MLP (feat -> feat -> out_width); biases as above."""
+    tag = (1 << 20) + 16
+    W1 = configs.glorot(w.seed, tag, w.feat, w.feat, device)
+    W2 = configs.glorot(w.seed, tag + 1, w.feat, out_width, device)
+    if bias_std > 0:
+        b1 = (rng.normal(w.seed, configs.STREAM_W, rng.arange64(w.feat, device) + ((tag + 2) << 32)) * bias_std).to(torch.float32)
+        b2 = (rng.normal(w.seed, configs.STREAM_W, rng.arange64(out_width, device) + ((tag + 3) << 32)) * bias_std).to(torch.float32)
+    else:
+        b1 = torch.zeros(w.feat, dtype=torch.float32, device=device)
+        b2 = torch.zeros(out_width, dtype=torch.float32, device=device)
+    return W1, b1, W2, b2
