@@ -185,36 +185,45 @@ __device__ inline float4 load_k4(const float *__restrict__ base, int64_t ld, int
 __device__ inline float pick(const float4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
 // MFMA pair kernel.  Workgroup = 4 wavefronts = 128 rows (32 per wavefront) x NT*32 output
-// columns.  The reduction axis is walked in chunks of 32: both A tiles (128 x 32) and both B
-// tiles (32 x NT*32) are staged in LDS; a lane then reads 4 consecutive k of its row with one
+// columns.  The reduction axis is walked in chunks of 32: the A tile(s) (128 x 32) and the B
+// tile(s) (32 x NT*32) are staged in LDS; a lane then reads 4 consecutive k of its row with one
 // 16-byte LDS read and feeds them to four MFMA steps (the k pairing of a step is (k, k+4), the B
-// tile is read with the same pairing).
-template <int NT, bool BWD>
-__global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
+// tile is read with the same pairing).  The global loads of chunk c+1 are issued into registers
+// before the MFMAs of chunk c and written to LDS after them, so memory latency hides behind the
+// matrix instructions.  TWO: second product A2 B2 (self term / T output) present.
+// Workgroups are numbered so that the column tiles of one row tile run back to back on the same
+// XCD (workgroup b goes to XCD b mod 8): the A tile is fetched from HBM once and re-read from L2.
+template <int NT, bool BWD, bool TWO>
+__global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_col_tiles)
 {
-    constexpr int BM = 128, KC = 32, AS = KC + 4, BN = NT * 32;
+    constexpr int BM = 128, KC = 32, AS = KC + 4, BN = NT * 32, BS = BN + 1;
+    constexpr int BPT = KC * BN / 256; // B-tile elements per thread and chunk
     __shared__ __attribute__((aligned(16))) float As1[BM][AS];
-    __shared__ __attribute__((aligned(16))) float As2[BM][AS];
-    __shared__ float Bs1[KC][BN];
-    __shared__ float Bs2[KC][BN];
+    __shared__ __attribute__((aligned(16))) float As2[TWO ? BM : 1][AS];
+    __shared__ float Bs1[KC][BS];
+    __shared__ float Bs2[TWO ? KC : 1][BS];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int m = lane & 31, h = lane >> 5;
-    const int64_t row0 = (int64_t)blockIdx.x * BM;
-    const int col0 = blockIdx.y * BN;
-    const bool two = a.A2 != nullptr && a.B2 != nullptr;
+    const int64_t b = blockIdx.x;
+    const int64_t row_tile = (b / (8 * n_col_tiles)) * 8 + (b % 8);
+    const int col_tile = (int)((b / 8) % n_col_tiles);
+    const int64_t row0 = row_tile * BM;
+    if (row0 >= a.n) return; // uniform per workgroup (the last group of 8 row tiles may be partial)
+    const int col0 = col_tile * BN;
     const bool vec1 = aligned16(a.A1) && (a.lda1 % 4 == 0);
-    const bool vec2 = two && aligned16(a.A2) && (a.lda2 % 4 == 0);
+    const bool vec2 = TWO && !BWD && aligned16(a.A2) && (a.lda2 % 4 == 0);
 
-    floatx16 acc1[NT], acc2[NT];
+    floatx16 acc1[NT], acc2[TWO ? NT : 1];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; acc2[t][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; if (TWO) acc2[t][r] = 0.f; }
 
-    for (int k0 = 0; k0 < a.K; k0 += KC) {
-        // ---- stage the A tiles: 128 rows x 32 k, one float4 per thread and iteration ----
+    float4 ra1[4], ra2[TWO ? 4 : 1];
+    float rb1[BPT], rb2[TWO ? BPT : 1];
+    auto fetch = [&](int k0) { // this thread's share of the tiles of chunk k0, into registers
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int idx = tid + it * 256;
@@ -223,12 +232,11 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
             const int kk = k0 + c4;
             float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
             if (row < a.n && kk < a.K) {
+                v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
                 if (!BWD) {
-                    v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
-                    if (two) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                    if (TWO) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
                 } else {
-                    const float4 g = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
-                    v1 = g;
+                    if (TWO) v2 = v1;
                     if (a.mask) { // four mask bits of this row; kk % 4 == 0 keeps them inside one word
                         const uint32_t bits = a.mask[row * a.mask_words + (kk >> 5)] >> (kk & 31);
                         if (!(bits & 1u)) v1.x = 0.f;
@@ -236,37 +244,61 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
                         if (!(bits & 4u)) v1.z = 0.f;
                         if (!(bits & 8u)) v1.w = 0.f;
                     }
-                    if (two) v2 = g;
                 }
             }
-            *reinterpret_cast<float4 *>(&As1[r][c4]) = v1;
-            *reinterpret_cast<float4 *>(&As2[r][c4]) = v2;
+            ra1[it] = v1;
+            if (TWO) ra2[it] = v2;
         }
-        // ---- stage the B tiles: 32 k x BN columns ----
-        for (int idx = tid; idx < KC * BN; idx += 256) {
-            const int kk = idx / BN, j = idx % BN;
+#pragma unroll
+        for (int it = 0; it < BPT; ++it) {
+            const int idx = tid + it * 256;
+            // consecutive threads walk the contiguous axis of W: columns forward, k backward (W^T)
+            const int kk = BWD ? idx % KC : idx / BN, j = BWD ? idx / KC : idx % BN;
             const int gk = k0 + kk, col = col0 + j;
             float w1 = 0.f, w2 = 0.f;
             if (gk < a.K && col < a.Nout) {
                 const int64_t id = BWD ? (int64_t)col * a.ldw + gk : (int64_t)gk * a.ldw + col;
                 w1 = a.B1[id];
-                if (two) w2 = a.B2[id];
+                if (TWO) w2 = a.B2[id];
             }
-            Bs1[kk][j] = w1;
-            Bs2[kk][j] = w2;
+            rb1[it] = w1;
+            if (TWO) rb2[it] = w2;
         }
+    };
+    auto stash = [&]() { // registers -> LDS
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = tid + it * 256;
+            const int r = idx >> 3, c4 = (idx & 7) * 4;
+            *reinterpret_cast<float4 *>(&As1[r][c4]) = ra1[it];
+            if (TWO) *reinterpret_cast<float4 *>(&As2[r][c4]) = ra2[it];
+        }
+#pragma unroll
+        for (int it = 0; it < BPT; ++it) {
+            const int idx = tid + it * 256;
+            const int kk = BWD ? idx % KC : idx / BN, j = BWD ? idx / KC : idx % BN;
+            Bs1[kk][j] = rb1[it];
+            if (TWO) Bs2[kk][j] = rb2[it];
+        }
+    };
+
+    fetch(0);
+    for (int k0 = 0; k0 < a.K; k0 += KC) {
+        stash();
         __syncthreads();
+        if (k0 + KC < a.K) fetch(k0 + KC);
 #pragma unroll
         for (int j8 = 0; j8 < 4; ++j8) {
             const float4 a1 = *reinterpret_cast<const float4 *>(&As1[wave * 32 + m][8 * j8 + 4 * h]);
-            const float4 a2 = *reinterpret_cast<const float4 *>(&As2[wave * 32 + m][8 * j8 + 4 * h]);
+            float4 a2 = a1;
+            if (TWO) a2 = *reinterpret_cast<const float4 *>(&As2[wave * 32 + m][8 * j8 + 4 * h]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int kk = 8 * j8 + 4 * h + i;
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1, i), Bs1[kk][t * 32 + m], acc1[t], 0, 0, 0);
-                    if (two) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2, i), Bs2[kk][t * 32 + m], acc2[t], 0, 0, 0);
+                    if (TWO) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2, i), Bs2[kk][t * 32 + m], acc2[t], 0, 0, 0);
                 }
             }
         }
@@ -279,7 +311,7 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
         const int col = col0 + t * 32 + m;
         const bool col_ok = col < a.Nout;
         const float bias1 = (!BWD && a.bias1 && col_ok) ? a.bias1[col] : 0.f;
-        const float bias2 = (!BWD && two && a.bias2 && col_ok) ? a.bias2[col] : 0.f;
+        const float bias2 = (!BWD && TWO && a.bias2 && col_ok) ? a.bias2[col] : 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int64_t row = row0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
@@ -293,12 +325,12 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a)
                         a.mask[row * a.mask_words + ((col0 + t * 32) >> 5)] = h ? (uint32_t)(bal >> 32) : (uint32_t)bal;
                 }
                 const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
-                const float o = rl + (two ? acc2[t][r] + bias2 : 0.f);
+                const float o = rl + (TWO ? acc2[t][r] + bias2 : 0.f);
                 if (row < a.n && col_ok) a.O1[row * a.ldo1 + col] = o;
             } else {
                 if (row < a.n && col_ok) {
                     a.O1[row * a.ldo1 + col] = acc1[t][r];
-                    if (a.O2) a.O2[row * a.ldo2 + col] = acc2[t][r];
+                    if (TWO && a.O2) a.O2[row * a.ldo2 + col] = acc2[t][r];
                 }
             }
         }
@@ -446,11 +478,30 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
     }
-    switch (nt) {
-    case 1: pair_mfma_kernel<1, BWD><<<grid, 256, 0, stream>>>(a); break;
-    case 2: pair_mfma_kernel<2, BWD><<<grid, 256, 0, stream>>>(a); break;
-    case 3: pair_mfma_kernel<3, BWD><<<grid, 256, 0, stream>>>(a); break;
-    default: pair_mfma_kernel<4, BWD><<<grid, 256, 0, stream>>>(a); break;
+    // staged kernel: 1-D grid, 8 row tiles x all column tiles per group of workgroups (see the kernel)
+    const bool two = a.A2 != nullptr && a.B2 != nullptr;
+    const int nt2 = (!two && a.Nout > 128) ? 8 : nt; // a single product leaves registers for 256 columns
+    const int bn = nt2 * 32;
+    const int n_col = (a.Nout + bn - 1) / bn;
+    const int64_t row_tiles = (a.n + 127) / 128;
+    const int64_t blocks = (row_tiles + 7) / 8 * 8 * n_col;
+    SG_REQUIRE(blocks <= INT32_MAX, SLICEGCN_ERANGE, "dense product: grid too large");
+    const unsigned gb = (unsigned)blocks;
+    if (two) {
+        switch (nt2) {
+        case 1: pair_mfma_kernel<1, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
+        case 2: pair_mfma_kernel<2, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
+        case 3: pair_mfma_kernel<3, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
+        default: pair_mfma_kernel<4, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
+        }
+    } else {
+        switch (nt2) {
+        case 1: pair_mfma_kernel<1, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        case 2: pair_mfma_kernel<2, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        case 3: pair_mfma_kernel<3, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        case 4: pair_mfma_kernel<4, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        default: pair_mfma_kernel<8, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        }
     }
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
@@ -674,6 +725,107 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
             const float sum = ((bsum[0][lane] + bsum[1][lane]) + bsum[2][lane]) + bsum[3][lane];
             if (j < a.w_out && !(a.compact && h)) out[(a.compact ? ww : 2 * ww) + (h ? a.w_out : 0) + j] = sum;
         }
+    }
+}
+
+// Partial weight gradient of a single product (compact layout: [X^T dP | colsum dP]) for wide
+// layers: one workgroup per 128 x 128 output tile and block of RED_ROWS rows, each wavefront owning a
+// 64 x 64 quarter (four MFMA accumulators).  Per step 32 rows of the X tile and of the dP tile are
+// staged in LDS (the next step's loads are issued into registers before this step's MFMAs); the
+// node axis is the MFMA's k axis.  32 flop per staged byte instead of 8 for 32 x 32 tiles.
+constexpr int GB_T = 128;
+
+__global__ __launch_bounds__(256) void grad_big_mfma_kernel(const ReduceArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float Xs[RED_RK][GB_T];
+    __shared__ __attribute__((aligned(16))) float Ps[RED_RK][GB_T];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int i_base = blockIdx.y * GB_T, j_base = blockIdx.z * GB_T;
+    const int wi = (wave >> 1) * 64, wj = (wave & 1) * 64;
+    const int64_t r_begin = (int64_t)blockIdx.x * RED_ROWS;
+    const int64_t r_end = r_begin + RED_ROWS < a.n ? r_begin + RED_ROWS : a.n;
+    const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vg = aligned16(a.dHout) && a.ldo % 4 == 0;
+    const bool bias_wave = blockIdx.y == 0 && (wave >> 1) == 0;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[ti][tj][r] = 0.f;
+    float accb = 0.f; // column j_base + wj + lane of dP
+
+    float4 rx[4], rp[4];
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = tid + it * 256;
+            const int r = idx >> 5, c4 = (idx & 31) * 4;
+            const int64_t row = r0 + r;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f), p = x;
+            if (row < r_end) {
+                if (i_base + c4 < a.w_in) x = load_k4(a.Z, a.ldz, row, i_base + c4, a.w_in, vz);
+                if (j_base + c4 < a.w_out) {
+                    p = load_k4(a.dHout, a.ldo, row, j_base + c4, a.w_out, vg);
+                    if (a.mask) {
+                        const int j = j_base + c4;
+                        const uint32_t bits = a.mask[row * a.mask_words + (j >> 5)] >> (j & 31);
+                        if (!(bits & 1u)) p.x = 0.f;
+                        if (!(bits & 2u)) p.y = 0.f;
+                        if (!(bits & 4u)) p.z = 0.f;
+                        if (!(bits & 8u)) p.w = 0.f;
+                    }
+                }
+            }
+            rx[it] = x;
+            rp[it] = p;
+        }
+    };
+    fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = tid + it * 256;
+            const int r = idx >> 5, c4 = (idx & 31) * 4;
+            *reinterpret_cast<float4 *>(&Xs[r][c4]) = rx[it];
+            *reinterpret_cast<float4 *>(&Ps[r][c4]) = rp[it];
+        }
+        __syncthreads();
+        if (r0 + RED_RK < r_end) fetch(r0 + RED_RK);
+#pragma unroll
+        for (int kp = 0; kp < RED_RK / 2; ++kp) {
+            const int k = 2 * kp + h;
+            const float a0 = Xs[k][wi + m], a1 = Xs[k][wi + 32 + m];
+            const float b0 = Ps[k][wj + m], b1 = Ps[k][wj + 32 + m];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (bias_wave) {
+#pragma unroll
+            for (int r = 0; r < RED_RK; ++r) accb += Ps[r][wj + lane];
+        }
+        __syncthreads();
+    }
+
+    float *out = a.partial + (int64_t)blockIdx.x * a.stride;
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i_base + wi + 32 * ti + 8 * (r / 4) + 4 * h + (r % 4);
+                const int j = j_base + wj + 32 * tj + m;
+                if (i < a.w_in && j < a.w_out) out[i * a.w_out + j] = acc[ti][tj][r];
+            }
+    if (bias_wave) {
+        const int j = j_base + wj + lane;
+        if (j < a.w_out) out[a.w_in * a.w_out + j] = accb;
     }
 }
 
@@ -997,8 +1149,14 @@ extern "C" int slicegcn_linear_bwd(const float *X, int64_t ldx, int64_t n, int32
         r.mask = m; r.mask_words = mask_words;
         r.partial = static_cast<float *>(ws); r.n = n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 1;
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
-        if (use_mfma()) grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
-        else grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        if (use_mfma() && (w_in > 64 || w_out > 64)) { // wide layer: 128 x 128 output tiles
+            dim3 big((unsigned)nb, (unsigned)((w_in + GB_T - 1) / GB_T), (unsigned)((w_out + GB_T - 1) / GB_T));
+            grad_big_mfma_kernel<<<big, 256, 0, stream>>>(r);
+        } else if (use_mfma()) {
+            grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
+        } else {
+            grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        }
         SG_LAUNCH_CHECK();
         FinalDst dst;
         dst.ptr[0] = dW; dst.ptr[1] = db; dst.ptr[2] = dst.ptr[3] = nullptr;
