@@ -372,6 +372,9 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
 
     const int64_t n_tiles = (a.n + 127) / 128;
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        // the weight tiles are re-read from LDS for every row tile: keeping them in registers across
+        // the loop would cost 64 registers per product and halve the wavefronts per SIMD
+        asm volatile("" ::: "memory");
         const int64_t row = tile * 128 + wave * 32 + m; // the row this lane feeds as A operand
         float4 a1[KCH * 4], a2[KCH * 4];
 #pragma unroll
@@ -419,6 +422,7 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
             const bool col_ok = col < a.Nout;
             const float bias1 = (!BWD && a.bias1 && col_ok) ? a.bias1[col] : 0.f;
             const float bias2 = (!BWD && two && a.bias2 && col_ok) ? a.bias2[col] : 0.f;
+            uint32_t my_word = 0u; // lane L < 32 collects the activation word of strip row L
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t orow = row0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
@@ -426,9 +430,10 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
                     const float p = acc1[t][r] + bias1;
                     const bool pos = p > 0.f && col_ok;
                     if (a.act == SLICEGCN_ACT_RELU) {
+                        // lanes 0..31 hold strip row 8*(r/4) + r%4 of this tile, lanes 32..63 the row four below it
                         const unsigned long long bal = __ballot(pos);
-                        if (m == 0 && orow < a.n && col0 + t * 32 < a.Nout)
-                            a.mask[orow * a.mask_words + ((col0 + t * 32) >> 5)] = h ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+                        if (lane < 32 && r == 4 * (lane >> 3) + (lane & 3))
+                            my_word = ((lane >> 2) & 1) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
                     }
                     const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
                     const float o = rl + (two ? acc2[t][r] + bias2 : 0.f);
@@ -439,6 +444,10 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
                         if (a.O2) a.O2[orow * a.ldo2 + col] = acc2[t][r];
                     }
                 }
+            }
+            if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && col0 + t * 32 < a.Nout) {
+                const int64_t wrow = row0 + wave * 32 + lane; // one coalesced store of the strip's 32 words
+                if (wrow < a.n) a.mask[wrow * a.mask_words + ((col0 + t * 32) >> 5)] = my_word;
             }
         }
     }
