@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 4 GiB device copy (reference for HBM byte counters) and exit")
     ap.add_argument("--spmm-only", type=int, default=0, help="time only this many round-robin slice aggregations per step")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step into a HIP graph and time its replays (graph_ms_per_step); the "
+                         "per-kernel figures still come from the eager steps")
     ap.add_argument("--ff", action="store_true",
                     help="feature-fusion variant: a shared two-layer MLP F -> F -> slice width feeds every slice model "
                          "(learned, so the first layer's input gradient and the MLP's backward join the step)")
@@ -87,7 +90,7 @@ def main():
     import synth
     from synth import configs, model
     import paper_2408_11500_amd as sg
-    from paper_2408_11500_amd.stack import Classifier, FeatureFusion, SliceStack
+    from paper_2408_11500_amd.stack import Classifier, FeatureFusion, GraphedStep, SliceStack
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -181,6 +184,19 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     log(f"{args.steps} steps, {ms_per_step:.2f} ms/step")
 
+    graph_ms = None
+    if args.graph:
+        gs = GraphedStep(step)
+        for _ in range(args.warmup):
+            gs.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            gs.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        log(f"HIP graph replay: {graph_ms:.2f} ms/step")
+
     kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt} for kind, wd, cnt, tot in prof}
     dom = next(((cnt, tot) for kind, wd, cnt, tot in prof if kind == "spmm" and wd == width), None)
     if dom is None:
@@ -208,6 +224,7 @@ def main():
                    "n_nodes": n, "nnz": view.nnz, "k": k, "slice_width": width, "slice_hidden": hs, "layers": L},
         "epoch_ms": None if args.spmm_only else ms_per_step,
         "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,
+        "graph_ms_per_step": graph_ms,
         "spmm_avg_ms": avg_s * 1e3, "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "slice aggregation (spmm_wave_items + spmm_group_items + spmm_tiny_rows + spmm_fix kernels of one call)",

@@ -255,9 +255,9 @@ int slicegcn_accumulate(float *dst, int64_t ldd, const float *src, int64_t lds, 
  * logits: n x n_classes (ld); labels: DEVICE int32 [n] in [0, n_classes); dlogits may alias
  * logits only if ldd == ld (each row is fully read before it is written).  Row losses are added
  * in fp64 in a fixed order.  ws: 256-byte aligned, slicegcn_softmax_ce_workspace_bytes(n) bytes.
- * Synchronises `stream` (the label check comes back to the host).
- * EINVAL: NULL pointer, sizes < 1, ld < n_classes; ERANGE: a label outside [0, n_classes)
- * (outputs are then unspecified); EWORKSPACE: ws NULL or too small.
+ * Asynchronous like every other device call, so a label outside [0, n_classes) cannot come back
+ * as a status: it makes *loss NaN (the gradient rows of such nodes are unspecified).
+ * EINVAL: NULL pointer, sizes < 1, ld < n_classes; EWORKSPACE: ws NULL or too small.
  * ------------------------------------------------------------------------------------- */
 size_t slicegcn_softmax_ce_workspace_bytes(int64_t n);
 int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, int32_t n_classes,

@@ -6,7 +6,8 @@
 // gradient), each lane taking columns sub, sub + 16, ...; the row was just read, so the second
 // and third sweep hit L1/L2.  Row losses are added per workgroup (64 rows) in fp64 in a fixed
 // order, and a single-workgroup kernel adds the workgroup sums in fp64 in a fixed order: no
-// floating-point atomics, bitwise reproducible.
+// floating-point atomics, bitwise reproducible.  A label outside [0, c) cannot be reported to the
+// host without a synchronisation, so it poisons the result instead: the loss becomes NaN.
 #include "common.h"
 
 namespace slicegcn {
@@ -19,7 +20,7 @@ constexpr int CE_ROWS_PER_BLOCK = 4 * CE_ROWS; // each group handles four rows
 
 __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict__ logits, int64_t ld, int64_t n, int32_t c,
                                                          const int32_t *__restrict__ labels, float *__restrict__ dlogits,
-                                                         int64_t ldd, double *__restrict__ partial, int *__restrict__ bad)
+                                                         int64_t ldd, double *__restrict__ partial)
 {
     __shared__ double row_loss[CE_ROWS_PER_BLOCK];
     const int grp = threadIdx.x / CE_LPR, sub = threadIdx.x % CE_LPR;
@@ -31,7 +32,8 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict
         if (v < n) { // uniform within the 16-lane group
             const float *x = logits + v * ld;
             int y = labels[v];
-            if (y < 0 || y >= c) { if (sub == 0) atomicAdd(bad, 1); y = 0; }
+            const bool bad = y < 0 || y >= c;
+            if (bad) y = 0;
             float m = -INFINITY;
             for (int j = sub; j < c; j += CE_LPR) m = fmaxf(m, x[j]);
 #pragma unroll
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict
             for (int j = sub; j < c; j += CE_LPR) sum += expf(x[j] - m);
 #pragma unroll
             for (int s = 1; s < CE_LPR; s <<= 1) sum += __shfl_xor(sum, s, 64);
-            loss = (double)(m + logf(sum)) - (double)x[y];
+            loss = bad ? (double)NAN : (double)(m + logf(sum)) - (double)x[y];
             if (dlogits) {
                 float *g = dlogits + v * ldd;
                 const float inv_sum = 1.0f / sum;
@@ -85,7 +87,7 @@ using namespace slicegcn;
 extern "C" size_t slicegcn_softmax_ce_workspace_bytes(int64_t n)
 {
     if (n < 1) return 0;
-    return (size_t)round_up(ce_blocks(n) * (int64_t)sizeof(double), 256) + 256;
+    return (size_t)round_up(ce_blocks(n) * (int64_t)sizeof(double), 256);
 }
 
 extern "C" int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, int32_t n_classes, const int32_t *labels,
@@ -103,16 +105,10 @@ extern "C" int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, i
     const int64_t nb = ce_blocks(n);
     SG_REQUIRE(nb <= INT32_MAX, SLICEGCN_ERANGE, "softmax_ce: too many rows for one launch");
     double *partial = static_cast<double *>(ws);
-    int *bad = reinterpret_cast<int *>(static_cast<char *>(ws) + round_up(nb * (int64_t)sizeof(double), 256));
-    SG_HIP(hipMemsetAsync(bad, 0, sizeof(int), stream));
     ProfScope prof(SLICEGCN_PROF_LOSS, n_classes, stream);
-    softmax_ce_kernel<<<(unsigned)nb, 256, 0, stream>>>(logits, ld, n, n_classes, labels, dlogits, ldd, partial, bad);
+    softmax_ce_kernel<<<(unsigned)nb, 256, 0, stream>>>(logits, ld, n, n_classes, labels, dlogits, ldd, partial);
     SG_LAUNCH_CHECK();
     ce_final_kernel<<<1, 256, 0, stream>>>(partial, nb, n, loss);
     SG_LAUNCH_CHECK();
-    int h_bad = 0;
-    SG_HIP(hipMemcpyAsync(&h_bad, bad, sizeof(int), hipMemcpyDeviceToHost, stream));
-    SG_HIP(hipStreamSynchronize(stream));
-    SG_REQUIRE(h_bad == 0, SLICEGCN_ERANGE, "softmax_ce: %d label(s) outside [0, %d)", h_bad, n_classes);
     return SLICEGCN_OK;
 }

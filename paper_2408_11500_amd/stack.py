@@ -194,3 +194,29 @@ class FeatureFusion:
         """dXff: n x out_width gradient of the fused features (the sum over the slice models)."""
         B.slicegcn_linear_bwd(self.A, self.W2, None, dXff, self.dA, self.dW2, self.db2, self.ws, act=B.ACT_NONE)
         B.slicegcn_linear_bwd(X, self.W1, self.mask, self.dA, None, self.dW1, self.db1, self.ws, act=B.ACT_RELU)
+
+
+class GraphedStep:
+    """A sequence of library calls captured once into a HIP graph and replayed with one launch.
+
+    For the small workloads a pass is a few hundred kernels of microseconds each and the time goes
+    into launching them; a replayed graph removes that.  ``fn`` must only issue library calls on the
+    current stream and touch preallocated buffers (every entry point except graph construction
+    qualifies: none allocates, synchronises or clears memory with a memset node).  The buffers are
+    read through their addresses, so new inputs written into the same tensors are picked up by the
+    next replay."""
+
+    def __init__(self, fn, warmup: int = 1):
+        self.stream = torch.cuda.Stream()
+        self.stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(self.stream):
+            for _ in range(warmup):
+                fn()
+        torch.cuda.current_stream().wait_stream(self.stream)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph, stream=self.stream):
+            fn()
+
+    def replay(self):
+        self.graph.replay()

@@ -12,7 +12,7 @@ import synth
 from synth import configs, model
 import paper_2408_11500_amd as sg
 from paper_2408_11500_amd import binding as B
-from paper_2408_11500_amd.stack import Classifier, FeatureFusion, SliceStack, padded_ld
+from paper_2408_11500_amd.stack import Classifier, FeatureFusion, GraphedStep, SliceStack, padded_ld
 from gpu_util import (TOL, assert_close, dev, hub_edges, messy_edges, pack_mask, padded, rel_err, unpack_mask)
 
 pytestmark = pytest.mark.gpu
@@ -470,3 +470,56 @@ def test_epoch_feature_fusion():
 def test_epoch_with_classifier_and_loss():
     w = synth.WORKLOADS["cfg1"]
     run_epoch_parity(w, w.slice_hidden, classifier=True)
+
+
+def test_graph_replay_matches_eager():
+    """The whole pass (slices, encoding + concat, classifier, loss, backward) captured into a HIP graph:
+    every replay, with eager work and synchronisations in between and with changed inputs, must equal
+    the eager result bit for bit."""
+    w = synth.WORKLOADS["cfg1"]
+    s_, d_ = configs.edges(w)
+    g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
+    k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
+    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
+    st = SliceStack(g, n, k, c, hs, L)
+    Xd = configs.features(w).cuda()
+    for i, (a, b_) in enumerate(sl):
+        sg.slicegcn_slice_feature(Xd, a, b_, st.X[i])
+        for l, (wi, wo) in enumerate(st.widths):
+            st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, bias_std=0.05))
+    st.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, std=0.1))
+    cl = Classifier(n, k * hs, w.hidden, w.classes)
+    cl.set_params(*model.classifier_params(w, k * hs, bias_std=0.05))
+    y = configs.labels(w).cuda().to(torch.int32)
+    dH = torch.empty((n, k * hs), dtype=torch.float32, device="cuda")
+
+    def step():
+        H = st.forward()
+        cl.forward_backward(H, y, dH)
+        st.backward(dH)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        out = [st.Hcat.clone(), cl.loss.clone(), cl.dW1.clone(), dH.clone(), st.dE.clone()]
+        out += [st.grads[i][l][key].clone() for i in range(k) for l in range(L) for key in ("dW_agg", "db", "dW_self", "db_self")]
+        return out
+
+    X0 = [x.clone() for x in st.X]
+    step(); ref1 = snapshot()
+    for x in st.X:
+        x.mul_(-0.5)
+    step(); ref2 = snapshot()
+    for x, x0 in zip(st.X, X0):
+        x.copy_(x0)
+    gs = GraphedStep(step)
+    for rep in range(4):
+        variant2 = rep % 2 == 1
+        for x, x0 in zip(st.X, X0):
+            x.copy_(x0 * (-0.5 if variant2 else 1.0))
+        gs.replay()
+        got = snapshot()
+        for a_, b2 in zip(got, ref2 if variant2 else ref1):
+            assert torch.equal(a_, b2), f"replay {rep} differs from the eager pass"
+        sg.slicegcn_spmm_slice(g, st.X[0][:, :c], st.Z[0][0][:, :c])  # eager work between replays
+        torch.cuda.synchronize()
+    g.destroy()
