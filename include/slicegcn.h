@@ -64,10 +64,14 @@ typedef struct {
     int32_t symmetric;     /* 1 when the pattern was symmetrised              */
 } slicegcn_csr_view;
 
+/* flags of slicegcn_layer_desc.flags */
+#define SLICEGCN_LAYER_Z_VALID 1u /* forward only: saved->Z already holds A^ Hin, skip the aggregation */
+
 typedef struct {
-    int32_t w_in;  /* width of the layer input  (columns of Hin, rows of W)    */
-    int32_t w_out; /* width of the layer output (columns of Hout, cols of W)   */
-    int32_t act;   /* SLICEGCN_ACT_*                                           */
+    int32_t w_in;   /* width of the layer input  (columns of Hin, rows of W)    */
+    int32_t w_out;  /* width of the layer output (columns of Hout, cols of W)   */
+    int32_t act;    /* SLICEGCN_ACT_*                                           */
+    uint32_t flags; /* SLICEGCN_LAYER_* or 0                                    */
 } slicegcn_layer_desc;
 
 /* Parameters of one layer of one slice.  W_* are row-major w_in x w_out, contiguous
@@ -160,9 +164,12 @@ int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, 
  * straight into its column block of the concatenated representation).  saved->Z is always
  * written (it is the staging buffer of the aggregation); saved->mask is written for ACT_RELU.
  * Hin must satisfy the fast-path layout of slicegcn_spmm_slice or the scalar path is taken.
+ * With SLICEGCN_LAYER_Z_VALID the caller vouches that saved->Z still holds A^ Hin from an earlier
+ * call with the same graph and Hin (the first layer over raw, constant features is the same in
+ * every epoch); the aggregation is then skipped.  The paper's own implementation recomputes it.
  * No workspace is needed.
  * EINVAL: NULL Hin/Hout/W_agg/saved->Z, widths < 1, ld too small, ldz not a multiple of 4,
- *         mask NULL or mask_words too small with ACT_RELU, unknown act.
+ *         mask NULL or mask_words too small with ACT_RELU, unknown act or flag.
  * ------------------------------------------------------------------------------------- */
 int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
                        const slicegcn_layer_params *params, const float *Hin, int64_t ldi,

@@ -21,6 +21,7 @@ SYMMETRIZE = 1
 ADD_SELF_LOOPS = 2
 ACT_NONE = 0
 ACT_RELU = 1
+LAYER_Z_VALID = 1
 
 OK, EINVAL, ERANGE, ENOMEM, EHIP, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 
@@ -50,7 +51,7 @@ class _CsrView(ctypes.Structure):
 
 
 class _LayerDesc(ctypes.Structure):
-    _fields_ = [("w_in", ctypes.c_int32), ("w_out", ctypes.c_int32), ("act", ctypes.c_int32)]
+    _fields_ = [("w_in", ctypes.c_int32), ("w_out", ctypes.c_int32), ("act", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
 
 class _LayerParams(ctypes.Structure):
@@ -251,8 +252,8 @@ def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int |
     return Y
 
 
-def _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self):
-    desc = _LayerDesc(w_in, w_out, act)
+def _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, flags=0):
+    desc = _LayerDesc(w_in, w_out, act, flags)
     for name, W in (("W_agg", W_agg), ("W_self", W_self)):
         if W is not None and (tuple(W.shape) != (w_in, w_out)):
             raise ValueError(f"{name} must be w_in x w_out")
@@ -269,11 +270,12 @@ def _saved_struct(Z: torch.Tensor, mask):
 
 
 def slicegcn_layer_fwd(g: Graph, Hin, W_agg, b, W_self, b_self, Hout, Z, mask, act: int = ACT_RELU,
-                       w_in: int | None = None, w_out: int | None = None):
-    """Hout = act(A^ Hin W_agg + b) + Hin W_self + b_self; fills Z (and mask for ReLU)."""
+                       w_in: int | None = None, w_out: int | None = None, z_valid: bool = False):
+    """Hout = act(A^ Hin W_agg + b) + Hin W_self + b_self; fills Z (and mask for ReLU).
+    ``z_valid``: Z already holds A^ Hin (same graph and Hin as an earlier call): skip the aggregation."""
     w_in = int(W_agg.shape[0] if w_in is None else w_in)
     w_out = int(W_agg.shape[1] if w_out is None else w_out)
-    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, LAYER_Z_VALID if z_valid else 0)
     pi, ldi = _mat(Hin, "Hin")
     po, ldo = _mat(Hout, "Hout")
     saved = _saved_struct(Z, mask)
@@ -283,7 +285,7 @@ def slicegcn_layer_fwd(g: Graph, Hin, W_agg, b, W_self, b_self, Hout, Z, mask, a
 
 
 def slicegcn_layer_bwd_workspace_bytes(n_nodes: int, w_in: int, w_out: int, need_dHin: bool) -> int:
-    desc = _LayerDesc(w_in, w_out, ACT_RELU)
+    desc = _LayerDesc(w_in, w_out, ACT_RELU, 0)
     return int(lib().slicegcn_layer_bwd_workspace_bytes(n_nodes, ctypes.byref(desc), int(need_dHin)))
 
 

@@ -946,6 +946,7 @@ int check_layer(const slicegcn_graph *g, const slicegcn_layer_desc *d, const sli
     SG_REQUIRE(g && d && p, SLICEGCN_EINVAL, "%s: NULL graph, desc or params", who);
     SG_REQUIRE(d->w_in >= 1 && d->w_out >= 1, SLICEGCN_EINVAL, "%s: widths must be >= 1", who);
     SG_REQUIRE(d->act == SLICEGCN_ACT_NONE || d->act == SLICEGCN_ACT_RELU, SLICEGCN_EINVAL, "%s: unknown act %d", who, d->act);
+    SG_REQUIRE((d->flags & ~SLICEGCN_LAYER_Z_VALID) == 0, SLICEGCN_EINVAL, "%s: unknown flag bits 0x%x", who, d->flags);
     SG_REQUIRE(p->W_agg != nullptr, SLICEGCN_EINVAL, "%s: W_agg is NULL", who);
     SG_REQUIRE(p->W_self != nullptr || p->b_self == nullptr, SLICEGCN_EINVAL, "%s: b_self without W_self", who);
     return SLICEGCN_OK;
@@ -1002,7 +1003,8 @@ extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_
     if (int rc = check_saved(desc, saved, "layer_fwd")) return rc;
     hipStream_t stream = as_stream(stream_);
 
-    if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, stream)) return rc;
+    if (!(desc->flags & SLICEGCN_LAYER_Z_VALID))
+        if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, stream)) return rc;
 
     PairArgs a;
     a.A1 = saved->Z; a.lda1 = saved->ldz;

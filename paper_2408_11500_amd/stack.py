@@ -20,7 +20,7 @@ def padded_ld(width: int) -> int:
 class SliceStack:
     def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
                  device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU,
-                 shared_input: torch.Tensor | None = None):
+                 shared_input: torch.Tensor | None = None, cache_first_aggregation: bool = False):
         """``shared_input``: with feature fusion every slice model reads the same fused n x first_width
         matrix; the stack then also returns the gradient with respect to it (``dXin``)."""
         self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
@@ -30,6 +30,10 @@ class SliceStack:
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.widths = [(first_width if l == 0 else slice_hidden, slice_hidden) for l in range(layers)]
         # inputs
+        # with direct slicing the first layer aggregates constant features: A^ X_s can be kept across passes
+        # (the paper's implementation recomputes it; off by default so that a pass measures every kernel)
+        self.cache_first = cache_first_aggregation and shared_input is None
+        self.first_valid = [False] * k
         self.shared = shared_input is not None
         self.X = ([shared_input] * k if self.shared
                   else [torch.zeros((n_nodes, padded_ld(first_width)), **f32) for _ in range(k)])
@@ -65,6 +69,10 @@ class SliceStack:
                                 dW_self=torch.empty((wi, wo), **f32) if W_self is not None else None,
                                 db_self=torch.empty(wo, **f32) if W_self is not None else None)
 
+    def inputs_changed(self):
+        """Call after writing new features into ``X``: cached first-layer aggregations are dropped."""
+        self.first_valid = [False] * self.k
+
     def hin(self, i: int, l: int) -> torch.Tensor:
         wi = self.widths[l][0]
         return (self.X[i] if l == 0 else self.H[i][l - 1])[:, :wi]
@@ -83,7 +91,9 @@ class SliceStack:
             p = self.params[i][l]
             wi = self.widths[l][0]
             B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], p["b_self"], self.hout(i, l),
-                                 self.Z[i][l][:, :wi], self.mask[i][l], act=self.act(l))
+                                 self.Z[i][l][:, :wi], self.mask[i][l], act=self.act(l),
+                                 z_valid=l == 0 and self.cache_first and self.first_valid[i])
+        self.first_valid[i] = True
 
     def forward(self) -> torch.Tensor:
         for i in range(self.k):

@@ -523,3 +523,35 @@ def test_graph_replay_matches_eager():
         sg.slicegcn_spmm_slice(g, st.X[0][:, :c], st.Z[0][0][:, :c])  # eager work between replays
         torch.cuda.synchronize()
     g.destroy()
+
+
+def test_cached_first_aggregation_equals_recomputed():
+    """SLICEGCN_LAYER_Z_VALID: keeping A^ X_s of the constant raw features across passes gives the same
+    bits as recomputing it, and new features are picked up after inputs_changed()."""
+    w = synth.WORKLOADS["cfg1"]
+    s_, d_ = configs.edges(w)
+    g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
+    k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
+    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
+    Xd = configs.features(w).cuda()
+    stacks = [SliceStack(g, n, k, c, hs, L, cache_first_aggregation=flag) for flag in (False, True)]
+    for st in stacks:
+        for i, (a, b_) in enumerate(sl):
+            sg.slicegcn_slice_feature(Xd, a, b_, st.X[i])
+            for l, (wi, wo) in enumerate(st.widths):
+                st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, bias_std=0.05))
+    plain, cached = stacks
+    ref = plain.forward().clone()
+    assert torch.equal(cached.forward(), ref)
+    for st in stacks:  # clobber the saved aggregation: the cached stack must not recompute it, the plain one must
+        st.Z[0][0].zero_()
+    assert torch.equal(plain.forward(), ref)
+    assert not torch.equal(cached.forward(), ref)
+    cached.inputs_changed()
+    assert torch.equal(cached.forward(), ref) and torch.equal(cached.forward(), ref)
+    with pytest.raises(B.SliceGCNError):  # unknown flag bit
+        desc, params = B._layer_structs(c, hs, 1, plain.params[0][0]["W_agg"], None, None, None, flags=2)
+        B._check(B.lib().slicegcn_layer_fwd(g.handle, __import__("ctypes").byref(desc), __import__("ctypes").byref(params),
+                                            plain.X[0].data_ptr(), plain.X[0].stride(0), plain.Hcat.data_ptr(), plain.Hcat.stride(0),
+                                            __import__("ctypes").byref(B._saved_struct(plain.Z[0][0], plain.mask[0][0])), 0))
+    g.destroy()
