@@ -261,3 +261,20 @@ def softmax_ce(logits, labels, want_grad: bool = True):
                                  _p(labels, ctypes.c_int32), ctypes.byref(loss), _p(dl, ctypes.c_double), ctypes.c_int64(c))
     _check(rc, "softmax_ce")
     return loss.value, dl
+
+
+def adam_step(p, g, m, v, lr, t, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """One Adam step in place on the fp64 arrays p, m, v (t >= 1 is the step count)."""
+    for a in (p, g, m, v):
+        if a.dtype != np.float64 or not a.flags.c_contiguous or a.shape != p.shape:
+            raise ValueError("contiguous fp64 arrays of one shape expected")
+    d = ctypes.c_double
+    rc = lib().oracle_adam_step(_p(p, d), _p(g, d), _p(m, d), _p(v, d), ctypes.c_int64(p.size), d(lr), d(beta1), d(beta2),
+                                d(eps), d(weight_decay), ctypes.c_int32(t))
+    _check(rc, "adam_step")
+
+
+def cosine_lr(lr_max: float, lr_min: float, t: int, t_max: int) -> float:
+    f = lib().oracle_cosine_lr
+    f.restype = ctypes.c_double
+    return float(f(ctypes.c_double(lr_max), ctypes.c_double(lr_min), ctypes.c_int32(t), ctypes.c_int32(t_max)))

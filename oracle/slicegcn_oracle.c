@@ -472,6 +472,33 @@ int oracle_softmax_ce(int64_t n, int32_t c, const double *logits, int64_t ld, co
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------------------------------------------
+ * Optimiser of the paper's experiments: Adam with a cosine-annealed learning rate.
+ * One Adam step on `count` parameters (Kingma & Ba, with bias correction), step t >= 1:
+ *   g' = g + weight_decay * p;  m = b1 m + (1 - b1) g';  v = b2 v + (1 - b2) g'^2;
+ *   p -= lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
+ * ---------------------------------------------------------------------------------- */
+int oracle_adam_step(double *p, const double *g, double *m, double *v, int64_t count, double lr,
+                     double beta1, double beta2, double eps, double weight_decay, int32_t t)
+{
+    if (!p || !g || !m || !v || count < 0 || t < 1) return ORACLE_EINVAL;
+    const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < count; ++i) {
+        const double gi = g[i] + weight_decay * p[i];
+        m[i] = beta1 * m[i] + (1.0 - beta1) * gi;
+        v[i] = beta2 * v[i] + (1.0 - beta2) * gi * gi;
+        p[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+    }
+    return ORACLE_OK;
+}
+
+/* Cosine annealing: lr(t) = lr_min + (lr_max - lr_min) (1 + cos(pi t / t_max)) / 2 for epoch t in [0, t_max]. */
+double oracle_cosine_lr(double lr_max, double lr_min, int32_t t, int32_t t_max)
+{
+    const double pi = 3.14159265358979323846;
+    return lr_min + 0.5 * (lr_max - lr_min) * (1.0 + cos(pi * (double)t / (double)t_max));
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
