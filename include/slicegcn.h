@@ -272,6 +272,22 @@ int slicegcn_softmax_ce(const float *logits, int64_t ld, int64_t n, int32_t n_cl
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Optimiser of the paper's experiments (its experimental settings: Adam with cosine-annealed
+ * learning rate).  One bias-corrected Adam step, step >= 1, on `count` contiguous fp32 parameters:
+ *   g' = grad + weight_decay * param;  m = beta1 m + (1 - beta1) g';  v = beta2 v + (1 - beta2) g'^2;
+ *   param -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * param, m, v are updated in place (m and v start as zeros); the four arrays must not overlap.
+ * Keeping all parameters of a model in one buffer makes this one launch per step.
+ * EINVAL: NULL pointer, count < 1, step < 1, beta outside [0, 1), eps < 0.
+ * ------------------------------------------------------------------------------------- */
+int slicegcn_adam_step(float *param, const float *grad, float *m, float *v, int64_t count, double lr,
+                       double beta1, double beta2, double eps, double weight_decay, int32_t step, void *stream);
+
+/* HOST: cosine annealing, lr(t) = lr_min + (lr_max - lr_min) (1 + cos(pi t / t_max)) / 2 for
+ * epoch t in [0, t_max]; returns lr_max when t_max < 1. */
+double slicegcn_cosine_lr(double lr_max, double lr_min, int32_t t, int32_t t_max);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the
  * stream each kernel is launched on.  Between slicegcn_profile_begin and slicegcn_profile_end
  * every kernel group the library launches is bracketed by an event pair.  _end synchronises

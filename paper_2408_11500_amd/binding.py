@@ -32,6 +32,7 @@ EXPORTS = [
     "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_begin", "slicegcn_profile_end",
     "slicegcn_linear_fwd", "slicegcn_linear_bwd_workspace_bytes", "slicegcn_linear_bwd",
     "slicegcn_softmax_ce_workspace_bytes", "slicegcn_softmax_ce", "slicegcn_accumulate",
+    "slicegcn_adam_step", "slicegcn_cosine_lr",
 ]
 
 PROF_KINDS = {0: "spmm", 1: "dense_fwd", 2: "dense_bwd", 3: "grad_reduce", 4: "concat", 5: "spmm_add",
@@ -109,6 +110,10 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_softmax_ce_workspace_bytes.restype = sz
         L.slicegcn_softmax_ce.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, vp, sz, vp]
         L.slicegcn_accumulate.argtypes = [vp, i64, vp, i64, i64, i32, vp]
+        f64 = ctypes.c_double
+        L.slicegcn_adam_step.argtypes = [vp, vp, vp, vp, i64, f64, f64, f64, f64, f64, i32, vp]
+        L.slicegcn_cosine_lr.argtypes = [ctypes.c_double, ctypes.c_double, i32, i32]
+        L.slicegcn_cosine_lr.restype = ctypes.c_double
         L.slicegcn_strerror.argtypes = [ctypes.c_int]
         L.slicegcn_strerror.restype = ctypes.c_char_p
         L.slicegcn_last_error.restype = ctypes.c_char_p
@@ -390,6 +395,20 @@ def slicegcn_accumulate(dst, src):
         raise ValueError("dst and src differ in shape")
     _check(lib().slicegcn_accumulate(pd, ldd, ps, lds, dst.shape[0], dst.shape[1], _stream()))
     return dst
+
+
+def slicegcn_adam_step(param, grad, m, v, lr: float, step: int, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """One Adam step in place on flat (contiguous) fp32 device tensors of equal size."""
+    n = param.numel()
+    for t, name in ((grad, "grad"), (m, "m"), (v, "v")):
+        if t.numel() != n:
+            raise ValueError(f"{name} differs in size from param")
+    _check(lib().slicegcn_adam_step(_vec(param, "param"), _vec(grad, "grad"), _vec(m, "m"), _vec(v, "v"), n, lr, beta1, beta2,
+                                    eps, weight_decay, step, _stream()))
+
+
+def slicegcn_cosine_lr(lr_max: float, lr_min: float, t: int, t_max: int) -> float:
+    return float(lib().slicegcn_cosine_lr(lr_max, lr_min, t, t_max))
 
 
 def slicegcn_softmax_ce_workspace_bytes(n: int) -> int:

@@ -2,6 +2,8 @@
 // error-text plumbing of the C ABI.
 #include "common.h"
 
+#include <cmath>
+
 #include <cstdarg>
 #include <map>
 #include <mutex>
@@ -116,6 +118,23 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ dst
     }
 }
 
+// One Adam step on `count` contiguous parameters (bias-corrected, optional L2 weight decay).
+// c1 = 1 - beta1^t and c2 = 1 - beta2^t are computed on the host in fp64.
+__global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ p, const float *__restrict__ g, float *__restrict__ m,
+                                                   float *__restrict__ v, int64_t count, float lr, float beta1, float omb1,
+                                                   float beta2, float omb2, float eps, float wd, float inv_c1, float inv_c2)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+        const float pi = p[i];
+        const float gi = g[i] + wd * pi;
+        const float mi = beta1 * m[i] + omb1 * gi; // omb = 1 - beta, rounded from fp64 on the host
+        const float vi = beta2 * v[i] + omb2 * gi * gi;
+        m[i] = mi;
+        v[i] = vi;
+        p[i] = pi - lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+    }
+}
+
 inline unsigned grid_for(int64_t total)
 {
     const int64_t b = (total + 255) / 256;
@@ -150,6 +169,27 @@ extern "C" int slicegcn_accumulate(float *dst, int64_t ldd, const float *src, in
     else accumulate_kernel<false><<<grid_for(n * (int64_t)w), 256, 0, as_stream(stream)>>>(dst, ldd, src, lds_, n, w);
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_adam_step(float *param, const float *grad, float *m, float *v, int64_t count, double lr, double beta1,
+                                  double beta2, double eps, double weight_decay, int32_t step, void *stream)
+{
+    SG_REQUIRE(param && grad && m && v, SLICEGCN_EINVAL, "adam_step: NULL pointer");
+    SG_REQUIRE(count >= 1 && step >= 1, SLICEGCN_EINVAL, "adam_step: count and step must be >= 1");
+    SG_REQUIRE(beta1 >= 0.0 && beta1 < 1.0 && beta2 >= 0.0 && beta2 < 1.0 && eps >= 0.0, SLICEGCN_EINVAL,
+               "adam_step: betas must lie in [0, 1) and eps must not be negative");
+    const double c1 = 1.0 - pow(beta1, (double)step), c2 = 1.0 - pow(beta2, (double)step);
+    adam_kernel<<<grid_for(count), 256, 0, as_stream(stream)>>>(param, grad, m, v, count, (float)lr, (float)beta1,
+                                                                (float)(1.0 - beta1), (float)beta2, (float)(1.0 - beta2), (float)eps,
+                                                                (float)weight_decay, (float)(1.0 / c1), (float)(1.0 / c2));
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
+extern "C" double slicegcn_cosine_lr(double lr_max, double lr_min, int32_t t, int32_t t_max)
+{
+    if (t_max < 1) return lr_max;
+    return lr_min + 0.5 * (lr_max - lr_min) * (1.0 + cos(3.14159265358979323846 * (double)t / (double)t_max));
 }
 
 extern "C" int slicegcn_slice_strategy(int32_t in_d, int32_t p, double slice_size_scale,

@@ -69,6 +69,18 @@ class SliceStack:
                                 dW_self=torch.empty((wi, wo), **f32) if W_self is not None else None,
                                 db_self=torch.empty(wo, **f32) if W_self is not None else None)
 
+    def parameter_slots(self):
+        """(holder of the parameter, key, holder of its gradient, key) for every learnable tensor."""
+        out = []
+        for i in range(self.k):
+            for l in range(self.L):
+                for pn, gn in (("W_agg", "dW_agg"), ("b", "db"), ("W_self", "dW_self"), ("b_self", "db_self")):
+                    if self.params[i][l][pn] is not None:
+                        out.append((self.params[i][l], pn, self.grads[i][l], gn))
+        if self.E is not None:
+            out.append((self, "E", self, "dE"))
+        return out
+
     def inputs_changed(self):
         """Call after writing new features into ``X``: cached first-layer aggregations are dropped."""
         self.first_valid = [False] * self.k
@@ -204,6 +216,54 @@ class FeatureFusion:
         """dXff: n x out_width gradient of the fused features (the sum over the slice models)."""
         B.slicegcn_linear_bwd(self.A, self.W2, None, dXff, self.dA, self.dW2, self.db2, self.ws, act=B.ACT_NONE)
         B.slicegcn_linear_bwd(X, self.W1, self.mask, self.dA, None, self.dW1, self.db1, self.ws, act=B.ACT_RELU)
+
+
+def _dense_slots(obj):
+    return [(obj, "W1", obj, "dW1"), (obj, "b1", obj, "db1"), (obj, "W2", obj, "dW2"), (obj, "b2", obj, "db2")]
+
+
+Classifier.parameter_slots = _dense_slots
+FeatureFusion.parameter_slots = _dense_slots
+
+
+class Optimizer:
+    """Adam with a cosine-annealed learning rate (the paper's experimental settings) over all learnable
+    tensors of the given models.  The tensors are moved into one flat buffer (gradients into another) and
+    the models' attributes rebound to views of it, so one library call updates every parameter."""
+
+    ALIGN = 64  # floats: every tensor starts on a 256-byte boundary, so vector paths stay usable
+
+    def __init__(self, models, lr_max: float, lr_min: float = 0.0, t_max: int = 1, beta1: float = 0.9,
+                 beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.0):
+        slots = [s for m in models for s in m.parameter_slots()]
+        get = lambda o, k: o[k] if isinstance(o, dict) else getattr(o, k)
+        offs, total = [], 0
+        for po, pk, _, _ in slots:
+            offs.append(total)
+            total += (get(po, pk).numel() + self.ALIGN - 1) // self.ALIGN * self.ALIGN
+        dev = get(slots[0][0], slots[0][1]).device
+        self.P, self.G, self.M, self.V = (torch.zeros(total, dtype=torch.float32, device=dev) for _ in range(4))
+        for (po, pk, go, gk), o in zip(slots, offs):
+            old = get(po, pk)
+            pv = self.P[o:o + old.numel()].view(old.shape)
+            pv.copy_(old)
+            gv = self.G[o:o + old.numel()].view(old.shape)
+            for holder, key, view in ((po, pk, pv), (go, gk, gv)):
+                if isinstance(holder, dict):
+                    holder[key] = view
+                else:
+                    setattr(holder, key, view)
+        self.hyper = (beta1, beta2, eps, weight_decay)
+        self.lr_max, self.lr_min, self.t_max = lr_max, lr_min, t_max
+        self.t = 0
+
+    def step(self, epoch: int) -> float:
+        """One update with the learning rate of ``epoch`` (0-based); returns that rate."""
+        self.t += 1
+        lr = B.slicegcn_cosine_lr(self.lr_max, self.lr_min, epoch, self.t_max)
+        b1, b2, eps, wd = self.hyper
+        B.slicegcn_adam_step(self.P, self.G, self.M, self.V, lr, self.t, b1, b2, eps, wd)
+        return lr
 
 
 class GraphedStep:

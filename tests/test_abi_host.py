@@ -29,7 +29,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_symbols()
-    assert len(names) == 22 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 24 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(L, n) is not None
 
@@ -49,6 +49,12 @@ def test_slice_strategy_rejects(L, args):
     assert e.value.status == binding.EINVAL
     with pytest.raises(ValueError):
         oracle.slice_strategy(*args)
+
+
+def test_cosine_lr_matches_oracle(L):
+    for t in range(0, 51, 5):
+        assert abs(binding.slicegcn_cosine_lr(0.01, 1e-4, t, 50) - oracle.cosine_lr(0.01, 1e-4, t, 50)) < 1e-15
+    assert binding.slicegcn_cosine_lr(0.01, 0.0, 3, 0) == 0.01
 
 
 def test_null_and_size_errors_return_codes(L):

@@ -1,0 +1,70 @@
+"""GPU parity of the Adam step against the fp64 oracle, and a short training run of the whole model
+(slice stack + classifier + loss + optimiser) that has to reduce the loss."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from synth import configs, model
+import paper_2408_11500_amd as sg
+from paper_2408_11500_amd import binding as B
+from paper_2408_11500_amd.stack import Classifier, Optimizer, SliceStack
+from gpu_util import assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("count", [1, 255, 4097, 100003])
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_adam_step_parity(count, wd):
+    rng = np.random.default_rng(count)
+    p = rng.normal(size=count); m = np.zeros(count); v = np.zeros(count)
+    pd, md, vd = dev(p), dev(m), dev(v)
+    for t in range(1, 6):
+        g = (rng.normal(size=count) * t).astype(np.float32)
+        lr = oracle.cosine_lr(1e-2, 1e-4, t - 1, 5)
+        oracle.adam_step(p, g.astype(np.float64), m, v, lr, t, weight_decay=wd)
+        B.slicegcn_adam_step(pd, dev(g), md, vd, lr, t, weight_decay=wd)
+        assert_close(pd.cpu().numpy(), p, f"param after step {t}", tol=1e-5)
+        assert_close(md.cpu().numpy(), m, "m", tol=1e-5)
+        assert_close(vd.cpu().numpy(), v, "v", tol=1e-5)
+
+
+def test_adam_rejects_bad_arguments():
+    t = torch.zeros(8, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.SliceGCNError):
+        B.slicegcn_adam_step(t, t.clone(), t.clone(), t.clone(), 1e-3, 0)          # step < 1
+    with pytest.raises(B.SliceGCNError):
+        B.slicegcn_adam_step(t, t.clone(), t.clone(), t.clone(), 1e-3, 1, beta1=1.0)
+
+
+def test_training_reduces_the_loss():
+    """The training algorithm end to end on the tiny workload with labels that depend on the features:
+    forward, loss, backward and an Adam step per epoch; the loss must at least halve."""
+    w = synth.WORKLOADS["cfg1"]
+    s_, d_ = configs.edges(w)
+    g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
+    k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
+    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
+    X = configs.features(w)
+    st = SliceStack(g, n, k, c, hs, L)
+    for i, (a, b_) in enumerate(sl):
+        sg.slicegcn_slice_feature(X.cuda(), a, b_, st.X[i])
+        for l, (wi, wo) in enumerate(st.widths):
+            st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo))
+    cl = Classifier(n, k * hs, w.hidden, w.classes)
+    cl.set_params(*model.classifier_params(w, k * hs))
+    y = (X[:, :w.classes].argmax(dim=1)).to(torch.int32).cuda()   # learnable: the largest of the first C features
+    opt = Optimizer([st, cl], lr_max=1e-2, lr_min=1e-4, t_max=60)
+    assert st.params[0][0]["W_agg"].data_ptr() >= opt.P.data_ptr()         # rebound to views of the flat buffer
+    dH = torch.empty((n, k * hs), dtype=torch.float32, device="cuda")
+    losses = []
+    for epoch in range(60):
+        H = st.forward()
+        losses.append(cl.forward_backward(H, y, dH).item())
+        st.backward(dH)
+        opt.step(epoch)
+    assert losses[-1] < 0.5 * losses[0], losses[::10]
+    assert np.isfinite(losses).all()
+    g.destroy()
