@@ -926,8 +926,17 @@ __global__ __launch_bounds__(1024) void reduce_final_kernel(const float *__restr
     const int64_t per = (n_blocks + 31) / 32;
     const int64_t b0 = part * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
     double acc = 0.0;
-    if (e < stride)
-        for (int64_t b = b0; b < b1; ++b) acc += (double)partial[b * row_stride + e];
+    if (e < stride) {
+        int64_t b = b0;
+        for (; b + 8 <= b1; b += 8) { // eight independent loads in flight; the additions stay in block order
+            float q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) q[i] = partial[(b + i) * row_stride + e];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc += (double)q[i];
+        }
+        for (; b < b1; ++b) acc += (double)partial[b * row_stride + e];
+    }
     red[part][el] = acc;
     __syncthreads();
     if (part == 0 && e < stride) {
