@@ -20,7 +20,8 @@ def padded_ld(width: int) -> int:
 class SliceStack:
     def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
                  device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU,
-                 shared_input: torch.Tensor | None = None, cache_first_aggregation: bool = False):
+                 shared_input: torch.Tensor | None = None, cache_first_aggregation: bool = False,
+                 fuse_encoding: bool = True):
         """``shared_input``: with feature fusion every slice model reads the same fused n x first_width
         matrix; the stack then also returns the gradient with respect to it (``dXin``)."""
         self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
@@ -50,6 +51,11 @@ class SliceStack:
         mw = (slice_hidden + 31) // 32
         self.mask = [[torch.zeros((n_nodes, mw), dtype=torch.int32, device=self.dev) for _ in range(layers)] for _ in range(k)]
         self.Hcat = torch.empty((n_nodes, k * slice_hidden), **f32)
+        # Slice encoding adds the row vector E[i] to every node row of slice i; the last layer's self-term bias does
+        # the same, so E[i] can ride on it: the last layer then stores the encoded output straight into its column
+        # block (no encoding pass) and dE[i] is that layer's db_self (no column-sum pass over dH).
+        self.fuse_encoding = fuse_encoding and slice_encoding
+        self.b_eff = torch.zeros((k, slice_hidden), **f32) if self.fuse_encoding else None
         # backward scratch
         self.dbuf = [torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
         ws = 0
@@ -98,11 +104,22 @@ class SliceStack:
         return self.act_last if l == self.L - 1 else B.ACT_RELU
 
     # ---------------------------------------------------------------------------------
+    def encoding_fused(self) -> bool:
+        last = self.L - 1
+        return self.fuse_encoding and all(self.params[i][last]["W_self"] is not None and
+                                          self.params[i][last]["b_self"] is not None for i in range(self.k))
+
     def forward_slice(self, i: int):
+        fused = self.encoding_fused()
         for l in range(self.L):
             p = self.params[i][l]
             wi = self.widths[l][0]
-            B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], p["b_self"], self.hout(i, l),
+            b_self = p["b_self"]
+            if fused and l == self.L - 1:  # b_self + E[i], two tiny launches
+                b_self = self.b_eff[i]
+                B.slicegcn_slice_feature(p["b_self"].view(1, -1), 0, self.hs, b_self.view(1, -1))
+                B.slicegcn_accumulate(b_self.view(1, -1), self.E[i].view(1, -1))
+            B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], b_self, self.hout(i, l),
                                  self.Z[i][l][:, :wi], self.mask[i][l], act=self.act(l),
                                  z_valid=l == 0 and self.cache_first and self.first_valid[i])
         self.first_valid[i] = True
@@ -110,12 +127,14 @@ class SliceStack:
     def forward(self) -> torch.Tensor:
         for i in range(self.k):
             self.forward_slice(i)
-        # the last layer of every slice already stored into its column block: encode in place
-        B.slicegcn_concat([self.hout(i, self.L - 1) for i in range(self.k)], self.E, self.Hcat)
+        # the last layer of every slice already stored into its column block: encode in place, unless that is done
+        if not self.encoding_fused():
+            B.slicegcn_concat([self.hout(i, self.L - 1) for i in range(self.k)], self.E, self.Hcat)
         return self.Hcat
 
     def backward(self, dH: torch.Tensor):
-        if self.E is not None:
+        fused = self.encoding_fused()
+        if self.E is not None and not fused:
             B.slicegcn_concat_bwd(dH, [self.hs] * self.k, dE=self.dE, ws=self.ws)
         for i in range(self.k):
             g_out = dH[:, i * self.hs:(i + 1) * self.hs]  # CONCAT backward is a column view
@@ -133,6 +152,8 @@ class SliceStack:
                                      act=self.act(l))
                 if l == 0 and self.shared and i > 0:
                     B.slicegcn_accumulate(self.dXin[:, :wi], g_in)
+                if fused and l == self.L - 1:  # dE[i] = column sums of dH^i = this layer's db_self
+                    B.slicegcn_slice_feature(gr["db_self"].view(1, -1), 0, self.hs, self.dE[i].view(1, -1))
                 g_out = g_in
 
 
