@@ -27,7 +27,8 @@
 //
 // Environment (diagnostics / tuning, read once): SLICEGCN_SPMM_SCHEDULE=rowsplit|xcd forces the
 // single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
-// are cut by column class when a graph is built; SLICEGCN_VERBOSE=1 prints schedule statistics.
+// are cut by column class when a graph is built; SLICEGCN_PASS_COLS=<c> narrows the column passes of
+// the 16-byte path (default 64); SLICEGCN_VERBOSE=1 prints schedule statistics.
 #include "common.h"
 
 #include <cstdlib>
@@ -198,7 +199,7 @@ __device__ inline void store_result(const Acc<V> &acc, const SpmmArgs &a, int ro
 
 constexpr int NO_UNIT = INT32_MIN;
 
-// One gather phase of the batched path: sub-round t hands unit (t * GROUPS + grp) of the wavefront
+// One gather phase of the tiny-row path: sub-round t hands unit (t * GROUPS + grp) of the wavefront
 // to lane group grp.  c_l / v_l hold, per lane, four (column, value) pairs of the unit that lane
 // owns (column -1 = no entry).  Two sub-rounds (eight gathers per lane) are in flight at a time.
 template <int LPR, int V, bool S32>
