@@ -453,6 +453,129 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
     }
 }
 
+// Variant for the narrowest layers (K <= 32, at most 32 output columns: every layer of the workload
+// with slices and hidden width 32).  These layers are HBM bound (about 10 flop per byte), so the kernel
+// is built around the memory accesses: a wavefront owns strips of 32 rows; it reads a strip with fully
+// coalesced 16-byte loads (eight lanes per 128-byte row), parks it in its own LDS tile, and reads it
+// back in the MFMA operand layout (lane = row, four consecutive k per 16-byte LDS read; the row
+// stride of 36 floats keeps those reads conflict free).  The next strip's loads are issued before
+// the current strip's MFMAs.  The weight operands never change, so every lane keeps its 16 values per
+// product in registers.  No workgroup barrier anywhere: a wavefront only touches its own tile, and
+// its LDS accesses execute in program order.
+template <bool BWD, bool TWO>
+__global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
+{
+    constexpr int ST = 36;
+    __shared__ __attribute__((aligned(16))) float T1[4][32][ST];
+    __shared__ __attribute__((aligned(16))) float T2[(TWO && !BWD) ? 4 : 1][32][ST];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int lr = lane >> 3, lc = (lane & 7) * 4; // coalesced layout: row lr + 8 * it, columns lc..lc+3
+    const bool vec1 = aligned16(a.A1) && (a.lda1 % 4 == 0);
+    const bool vec2 = TWO && !BWD && aligned16(a.A2) && (a.lda2 % 4 == 0);
+    float (*t1)[ST] = T1[wave];
+    float (*t2)[ST] = T2[(TWO && !BWD) ? wave : 0];
+
+    float b1[16], b2[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kk = 8 * q + 4 * h + i;
+            float w1 = 0.f, w2 = 0.f;
+            if (kk < a.K && m < a.Nout) {
+                const int64_t id = BWD ? (int64_t)m * a.ldw + kk : (int64_t)kk * a.ldw + m;
+                w1 = a.B1[id];
+                if (TWO) w2 = a.B2[id];
+            }
+            b1[q * 4 + i] = w1;
+            b2[q * 4 + i] = w2;
+        }
+    const bool col_ok = m < a.Nout;
+    const float bias1 = (!BWD && a.bias1 && col_ok) ? a.bias1[m] : 0.f;
+    const float bias2 = (!BWD && TWO && a.bias2 && col_ok) ? a.bias2[m] : 0.f;
+
+    const int64_t n_strips = (a.n + 31) / 32;
+    const int64_t first = (int64_t)blockIdx.x * 4 + wave, step = (int64_t)gridDim.x * 4;
+    float4 p1[4], p2[4];
+    uint32_t pw = ~0u; // backward: activation word of strip row m (the row this lane feeds to the MFMAs)
+    auto fetch = [&](int64_t strip) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int64_t row = strip * 32 + lr + 8 * it;
+            float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
+            if (row < a.n && lc < a.K) {
+                v1 = load_k4(a.A1, a.lda1, row, lc, a.K, vec1);
+                if (!BWD && TWO) v2 = load_k4(a.A2, a.lda2, row, lc, a.K, vec2);
+            }
+            p1[it] = v1;
+            p2[it] = v2;
+        }
+        if (BWD && a.mask) pw = strip * 32 + m < a.n ? a.mask[(strip * 32 + m) * a.mask_words] : 0u;
+    };
+    if (first < n_strips) fetch(first);
+    for (int64_t strip = first; strip < n_strips; strip += step) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            *reinterpret_cast<float4 *>(&t1[lr + 8 * it][lc]) = p1[it];
+            if (TWO && !BWD) *reinterpret_cast<float4 *>(&t2[lr + 8 * it][lc]) = p2[it];
+        }
+        __builtin_amdgcn_wave_barrier();
+        float4 a1[4], a2[4];
+        const uint32_t word = pw;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            a1[q] = *reinterpret_cast<const float4 *>(&t1[m][8 * q + 4 * h]);
+            if (TWO && !BWD) a2[q] = *reinterpret_cast<const float4 *>(&t2[m][8 * q + 4 * h]);
+            if (BWD) { // second product: dHout as it is; first product: dP = dHout * mask
+                a2[q] = a1[q];
+                const uint32_t bits = word >> (8 * q + 4 * h);
+                if (!(bits & 1u)) a1[q].x = 0.f;
+                if (!(bits & 2u)) a1[q].y = 0.f;
+                if (!(bits & 4u)) a1[q].z = 0.f;
+                if (!(bits & 8u)) a1[q].w = 0.f;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (strip + step < n_strips) fetch(strip + step); // flies during the MFMAs and the stores below
+        floatx16 acc1, acc2;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1[q], i), b1[q * 4 + i], acc1, 0, 0, 0);
+                if (TWO) acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2[q], i), b2[q * 4 + i], acc2, 0, 0, 0);
+            }
+        const int64_t row0 = strip * 32;
+        uint32_t my_word = 0u; // lane L < 32 collects the activation word of strip row L
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (!BWD) {
+                const float p = acc1[r] + bias1;
+                const bool pos = p > 0.f && col_ok;
+                if (a.act == SLICEGCN_ACT_RELU) {
+                    const unsigned long long bal = __ballot(pos);
+                    if (lane < 32 && r == 4 * (lane >> 3) + (lane & 3))
+                        my_word = ((lane >> 2) & 1) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+                }
+                const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
+                const float o = rl + (TWO ? acc2[r] + bias2 : 0.f);
+                if (orow < a.n && col_ok) a.O1[orow * a.ldo1 + m] = o;
+            } else {
+                if (orow < a.n && col_ok) {
+                    a.O1[orow * a.ldo1 + m] = acc1[r];
+                    if (TWO && a.O2) a.O2[orow * a.ldo2 + m] = acc2[r];
+                }
+            }
+        }
+        if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && row0 + lane < a.n)
+            a.mask[(row0 + lane) * a.mask_words] = my_word;
+    }
+}
+
 template <int NT, bool BWD>
 void launch_direct(const PairArgs &a, dim3 grid, hipStream_t stream)
 {
@@ -475,6 +598,15 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
     const int nt = a.Nout <= 32 ? 1 : a.Nout <= 64 ? 2 : a.Nout <= 96 ? 3 : 4;
     dim3 grid((unsigned)((a.n + 127) / 128), (unsigned)((a.Nout + nt * 32 - 1) / (nt * 32)));
     static const bool no_direct = getenv("SLICEGCN_DENSE_STAGED") != nullptr;
+    if (a.K <= 32 && a.Nout <= 32 && !no_direct) { // narrowest layers: per-wavefront strips, no barriers
+        const int64_t strips = (a.n + 31) / 32;
+        const unsigned gb = (unsigned)((strips + 3) / 4 < 2048 ? (strips + 3) / 4 : 2048);
+        const bool two = a.A2 != nullptr && a.B2 != nullptr;
+        if (two) pair_strip32_kernel<BWD, true><<<gb, 256, 0, stream>>>(a);
+        else pair_strip32_kernel<BWD, false><<<gb, 256, 0, stream>>>(a);
+        SG_LAUNCH_CHECK();
+        return SLICEGCN_OK;
+    }
     if (a.K <= 64 && nt == 1 && !no_direct) { // short reduction, one output tile: weights resident in LDS, workgroups walk over row tiles
         const unsigned tiles = grid.x;
         grid.x = tiles < 2048u ? tiles : 2048u;
