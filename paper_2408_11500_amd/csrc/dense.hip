@@ -550,9 +550,9 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
             }
         const int64_t row0 = strip * 32;
         uint32_t my_word = 0u; // lane L < 32 collects the activation word of strip row L
+        float o1[16], o2[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
             if (!BWD) {
                 const float p = acc1[r] + bias1;
                 const bool pos = p > 0.f && col_ok;
@@ -562,15 +562,39 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
                         my_word = ((lane >> 2) & 1) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
                 }
                 const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
-                const float o = rl + (TWO ? acc2[r] + bias2 : 0.f);
-                if (orow < a.n && col_ok) a.O1[orow * a.ldo1 + m] = o;
+                o1[r] = rl + (TWO ? acc2[r] + bias2 : 0.f);
             } else {
-                if (orow < a.n && col_ok) {
-                    a.O1[orow * a.ldo1 + m] = acc1[r];
-                    if (TWO && a.O2) a.O2[orow * a.ldo2 + m] = acc2[r];
-                }
+                o1[r] = acc1[r];
+                o2[r] = acc2[r];
             }
         }
+        // Outputs leave through the wavefront's tile so that a row goes out as eight 16-byte stores
+        // (register r of lane (m, h) is strip row 8*(r/4) + 4*h + r%4, column m); layouts that do not
+        // allow 16-byte stores write the registers directly.
+        auto store_tile = [&](const float (&o)[16], float *O, int64_t ldo, bool vec_ok) {
+            if (vec_ok) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int r = 0; r < 16; ++r) t1[8 * (r / 4) + 4 * h + (r % 4)][m] = o[r];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int64_t row = row0 + lr + 8 * it;
+                    const float4 v = *reinterpret_cast<const float4 *>(&t1[lr + 8 * it][lc]);
+                    if (row < a.n && lc < a.Nout) *reinterpret_cast<float4 *>(O + row * ldo + lc) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
+                    if (orow < a.n && col_ok) O[orow * ldo + m] = o[r];
+                }
+            }
+        };
+        const bool nout4 = a.Nout % 4 == 0;
+        store_tile(o1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0);
+        if (BWD && TWO && a.O2) store_tile(o2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0);
         if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && row0 + lane < a.n)
             a.mask[(row0 + lane) * a.mask_words] = my_word;
     }
