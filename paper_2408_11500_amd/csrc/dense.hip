@@ -893,6 +893,97 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
     }
 }
 
+// Partial weight gradients of the narrowest layers (w_in, w_out <= 32, large n): every wavefront owns
+// a contiguous range of rows and its own accumulators, walks the range in strips of 32 rows read
+// with coalesced 16-byte loads into wave-private LDS tiles (the next strip's loads in flight during
+// the MFMAs), and writes one partial result.  The node axis is the MFMA's k axis (lane (m, h) feeds
+// column m of node row 2s + h).  No workgroup barrier; same output layout as grad_partial_kernel,
+// one partial per wavefront.
+__global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, int64_t rows_per_wave)
+{
+    __shared__ __attribute__((aligned(16))) float Zs[4][32][32];
+    __shared__ __attribute__((aligned(16))) float Hs[4][32][32];
+    __shared__ __attribute__((aligned(16))) float Gs[4][32][32];
+    __shared__ uint32_t Ms[4][32];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int lr = lane >> 3, lc = (lane & 7) * 4;
+    const int64_t w_id = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t r_begin = w_id * rows_per_wave;
+    const int64_t r_end = r_begin + rows_per_wave < a.n ? r_begin + rows_per_wave : a.n;
+    if (r_begin >= a.n) return; // uniform per wavefront; no barriers below
+    const bool self = a.Hin != nullptr;
+    const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
+    const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
+    float (*zs)[32] = Zs[wave];
+    float (*hs)[32] = Hs[wave];
+    float (*gs)[32] = Gs[wave];
+    uint32_t *ms = Ms[wave];
+
+    floatx16 accA, accS;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { accA[r] = 0.f; accS[r] = 0.f; }
+    float sum_p = 0.f, sum_g = 0.f; // column m of dP and of dHout over the node rows 2s + h
+
+    float4 pz[4], ph[4], pg[4];
+    uint32_t pw = ~0u;
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int64_t row = r0 + lr + 8 * it;
+            float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z, g = z;
+            if (row < r_end) {
+                if (lc < a.w_in) {
+                    z = load_k4(a.Z, a.ldz, row, lc, a.w_in, vz);
+                    if (self) hh = load_k4(a.Hin, a.ldi, row, lc, a.w_in, vh);
+                }
+                if (lc < a.w_out) g = load_k4(a.dHout, a.ldo, row, lc, a.w_out, vg);
+            }
+            pz[it] = z; ph[it] = hh; pg[it] = g;
+        }
+        if (a.mask && lane < 32) pw = r0 + lane < r_end ? a.mask[(r0 + lane) * a.mask_words] : 0u;
+    };
+    fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            *reinterpret_cast<float4 *>(&zs[lr + 8 * it][lc]) = pz[it];
+            *reinterpret_cast<float4 *>(&hs[lr + 8 * it][lc]) = ph[it];
+            *reinterpret_cast<float4 *>(&gs[lr + 8 * it][lc]) = pg[it];
+        }
+        if (lane < 32) ms[lane] = pw;
+        __builtin_amdgcn_wave_barrier();
+        if (r0 + 32 < r_end) fetch(r0 + 32);
+#pragma unroll
+        for (int s2 = 0; s2 < 16; ++s2) {
+            const int k = 2 * s2 + h;
+            const float g = gs[k][m];
+            const float p = ((ms[k] >> m) & 1u) ? g : 0.f;
+            accA = __builtin_amdgcn_mfma_f32_32x32x2f32(zs[k][m], p, accA, 0, 0, 0);
+            if (self) accS = __builtin_amdgcn_mfma_f32_32x32x2f32(hs[k][m], g, accS, 0, 0, 0);
+            sum_p += p;
+            sum_g += g;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    sum_p += __shfl_xor(sum_p, 32, 64);
+    sum_g += __shfl_xor(sum_g, 32, 64);
+    float *out = a.partial + w_id * a.stride;
+    const int ww = a.w_in * a.w_out;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = 8 * (r / 4) + 4 * h + (r % 4);
+        if (i < a.w_in && m < a.w_out) {
+            out[i * a.w_out + m] = accA[r];
+            if (!a.compact) out[ww + i * a.w_out + m] = accS[r];
+        }
+    }
+    if (lane < 32 && m < a.w_out) {
+        out[(a.compact ? ww : 2 * ww) + m] = sum_p;
+        if (!a.compact) out[2 * ww + a.w_out + m] = sum_g;
+    }
+}
+
 // Partial weight gradient of a single product (compact layout: [X^T dP | colsum dP]) for wide
 // layers: one workgroup per 128 x 128 output tile and block of RED_ROWS rows, each wavefront owning a
 // 64 x 64 quarter (four MFMA accumulators).  Per step 32 rows of the X tile and of the dP tile are
@@ -1224,8 +1315,18 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.mask = mask; r.mask_words = saved->mask_words;
         r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 0;
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
-        if (use_mfma()) grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
-        else grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        int64_t n_partials = nb;
+        if (use_mfma() && w_in <= 32 && w_out <= 32 && g->n >= 65536) {
+            // one partial per wavefront, at most as many as the workspace has rows (nb) and as fill the chip
+            const int64_t waves = nb < 8192 ? nb : 8192;
+            const int64_t rows_per_wave = round_up((g->n + waves - 1) / waves, 32);
+            n_partials = (g->n + rows_per_wave - 1) / rows_per_wave;
+            grad_strip32_kernel<<<(unsigned)((n_partials + 3) / 4), 256, 0, stream>>>(r, rows_per_wave);
+        } else if (use_mfma()) {
+            grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
+        } else {
+            grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+        }
         SG_LAUNCH_CHECK();
         FinalDst dst;
         const int ww = w_in * w_out;
@@ -1234,7 +1335,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         dst.ptr[2] = grads->db;
         dst.ptr[3] = params->W_self ? grads->db_self : nullptr;
         dst.begin[0] = 0; dst.begin[1] = ww; dst.begin[2] = 2 * ww; dst.begin[3] = 2 * ww + w_out; dst.begin[4] = stride;
-        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(partial, nb, stride, stride, dst);
+        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(partial, n_partials, stride, stride, dst);
         SG_LAUNCH_CHECK();
     }
 

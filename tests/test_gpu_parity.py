@@ -555,3 +555,44 @@ def test_cached_first_aggregation_equals_recomputed():
                                             plain.X[0].data_ptr(), plain.X[0].stride(0), plain.Hcat.data_ptr(), plain.Hcat.stride(0),
                                             __import__("ctypes").byref(B._saved_struct(plain.Z[0][0], plain.mask[0][0])), 0))
     g.destroy()
+
+
+@pytest.mark.parametrize("shape", [(32, 32), (25, 32), (32, 17), (7, 5)])
+@pytest.mark.parametrize("act,has_self", [(1, True), (0, True), (1, False)])
+def test_narrow_layer_many_rows(shape, act, has_self):
+    """Layers of width <= 32 on a graph with more than 65536 rows (not a multiple of 32): the
+    per-wavefront strip kernels of the dense products and of the weight gradients, forward and backward."""
+    n = 70001
+    rng = np.random.default_rng(shape[0] * 100 + shape[1] + act)
+    src = rng.integers(0, n, 3 * n); dst = rng.integers(0, n, 3 * n)
+    o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n)
+    w_in, w_out = shape
+    Hin, W_agg, b, W_self, b_self = layer_inputs(n, w_in, w_out, 5 * w_in + w_out, has_self)
+    want, Zo, Po = oracle.layer_fwd(o, Hin, W_agg, b, W_self, b_self, act=act)
+    Hd = padded(Hin, padded_ld(w_in))
+    Hout = torch.empty((n, w_out + 4), dtype=torch.float32, device="cuda")[:, :w_out]
+    Zd = torch.empty((n, padded_ld(w_in)), dtype=torch.float32, device="cuda")[:, :w_in]
+    maskd = torch.zeros((n, 1), dtype=torch.int32, device="cuda") if act else None
+    sg.slicegcn_layer_fwd(g, Hd, dev(W_agg), dev(b), dev(W_self) if has_self else None, dev(b_self) if has_self else None,
+                          Hout, Zd, maskd, act=act)
+    assert_close(Hout.cpu().numpy(), want, "Hout")
+    mask_bits = (Po > 0).astype(np.uint8) if act else np.ones_like(Po, dtype=np.uint8)
+    if act:
+        differ = unpack_mask(maskd.cpu().numpy(), w_out) != mask_bits
+        assert np.all(np.abs(Po[differ]) <= 1e-5 * np.sqrt(np.mean(Po * Po)))
+        maskd.copy_(torch.as_tensor(pack_mask(mask_bits)))
+    dHout = rng.standard_normal((n, w_out)).astype(np.float32)
+    Z32 = Zo.astype(np.float32)
+    ref = oracle.layer_bwd(o, Hin, Z32, mask_bits, W_agg, W_self, dHout, need_dHin=True)
+    f = dict(dtype=torch.float32, device="cuda")
+    dHin = torch.empty((n, padded_ld(w_in)), **f)[:, :w_in]
+    dW_agg = torch.empty((w_in, w_out), **f); db = torch.empty(w_out, **f)
+    dW_self = torch.empty((w_in, w_out), **f) if has_self else None
+    db_self = torch.empty(w_out, **f) if has_self else None
+    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(n, w_in, w_out, True), dtype=torch.uint8, device="cuda")
+    sg.slicegcn_layer_bwd(g, Hd, dev(W_agg), dev(W_self) if has_self else None, padded(Z32, padded_ld(w_in)), maskd,
+                          padded(dHout, padded_ld(w_out)), dHin, dW_agg, db, dW_self, db_self, ws, act=act)
+    names = [("dW_agg", dW_agg), ("db", db), ("dHin", dHin)] + ([("dW_self", dW_self), ("db_self", db_self)] if has_self else [])
+    for name, t in names:
+        assert_close(t.cpu().numpy(), ref[name], name)
+    g.destroy()
