@@ -73,6 +73,27 @@ def test_null_and_size_errors_return_codes(L):
     assert L.slicegcn_strerror(-99) == b"unknown status"
 
 
+def test_widened_entry_points_validate_before_device_work(L):
+    vp = ctypes.c_void_p
+    one = vp(256)  # a non-NULL dummy pointer: validation must fail before anything dereferences it
+    assert L.slicegcn_linear_fwd(None, 4, 4, 4, 4, None, None, 0, None, 4, None, 0, None) == binding.EINVAL
+    assert L.slicegcn_linear_fwd(one, 3, 4, 4, 4, one, None, 0, one, 4, None, 0, None) == binding.EINVAL      # ldx < w_in
+    assert L.slicegcn_linear_fwd(one, 4, 4, 4, 4, one, None, 1, one, 4, None, 0, None) == binding.EINVAL      # ReLU, no mask
+    assert L.slicegcn_linear_fwd(one, 4, 4, 4, 4, one, None, 7, one, 4, None, 0, None) == binding.EINVAL      # unknown act
+    assert L.slicegcn_linear_bwd(one, 4, 4, 4, 4, one, 0, None, 0, one, 4, None, 0, one, None, None, 0, None) == binding.EWORKSPACE
+    assert L.slicegcn_linear_bwd_workspace_bytes(0, 4, 4) == 0
+    assert L.slicegcn_linear_bwd_workspace_bytes(5000, 25, 64) == -(-(5 * (25 * 64 + 64) * 4) // 256) * 256
+    assert L.slicegcn_softmax_ce(None, 4, 4, 4, None, None, None, 0, None, 0, None) == binding.EINVAL
+    assert L.slicegcn_softmax_ce(one, 3, 4, 4, one, one, None, 0, one, 4096, None) == binding.EINVAL          # ld < classes
+    assert L.slicegcn_softmax_ce(one, 4, 4, 4, one, one, None, 0, None, 0, None) == binding.EWORKSPACE
+    assert L.slicegcn_softmax_ce_workspace_bytes(0) == 0 and L.slicegcn_softmax_ce_workspace_bytes(1000) == 256
+    assert L.slicegcn_accumulate(None, 4, None, 4, 4, 4, None) == binding.EINVAL
+    assert L.slicegcn_accumulate(one, 3, one, 4, 4, 4, None) == binding.EINVAL
+    assert L.slicegcn_adam_step(None, None, None, None, 4, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == binding.EINVAL
+    assert L.slicegcn_adam_step(one, one, one, one, 4, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, None) == binding.EINVAL  # step < 1
+    assert L.slicegcn_adam_step(one, one, one, one, 4, 1e-3, 1.0, 0.999, 1e-8, 0.0, 1, None) == binding.EINVAL  # beta1 = 1
+
+
 def test_workspace_formula(L):
     # partial sums: ceil(n / 1024) row blocks x (2*w_in*w_out + 2*w_out) floats, 256-byte rounded,
     # plus an n x roundup4(w_in) fp32 staging matrix when the input gradient is wanted
