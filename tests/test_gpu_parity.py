@@ -596,3 +596,36 @@ def test_narrow_layer_many_rows(shape, act, has_self):
     for name, t in names:
         assert_close(t.cpu().numpy(), ref[name], name)
     g.destroy()
+
+
+def test_spmm_seeded_fuzz():
+    """Forty seeded random cases: graph size, density, planted long rows, symmetrisation flags, operand
+    width, leading dimensions (aligned and not) and transposition all vary; every output element is
+    compared with the oracle and the columns beyond the width must stay untouched."""
+    rng = np.random.default_rng(20240811)
+    for case in range(40):
+        n = int(rng.choice([1, 2, 33, 64, 65, 500, 3000, 9000]))
+        m = int(rng.integers(0, 12 * n + 1))
+        src = rng.integers(0, n, m); dst = rng.integers(0, n, m)
+        if n >= 500 and case % 3 == 0:  # a few rows far longer than one segment or one class piece
+            hubs = rng.integers(0, n, 3)
+            for hnode in hubs:
+                nb = rng.choice(n, size=min(n - 1, int(rng.integers(300, 5000))), replace=False)
+                src = np.concatenate([src, np.full(nb.size, hnode)]); dst = np.concatenate([dst, nb])
+        flags = int(rng.choice([3, 3, 2, 1, 0]))
+        o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n, flags)
+        check_csr(o, g)
+        for _ in range(2):
+            w = int(rng.choice([1, 2, 5, 25, 31, 32, 33, 64, 100, 130]))
+            tr = bool(rng.integers(0, 2))
+            X = rng.standard_normal((n, w)).astype(np.float32)
+            ldx = w + int(rng.choice([0, 1, 3, 4])) if rng.integers(0, 2) else padded_ld(w)
+            ldy = w + int(rng.integers(0, 6))
+            Xd = padded(X, ldx)
+            Yfull = torch.full((n, ldy), -7.0, dtype=torch.float32, device="cuda")
+            sg.slicegcn_spmm_slice(g, Xd, Yfull[:, :w], transpose=tr)
+            want = oracle.spmm(o, X.astype(np.float64), transpose=tr)
+            what = f"case {case}: n={n} m={m} flags={flags} w={w} ldx={ldx} ldy={ldy} transpose={tr}"
+            assert_close(Yfull[:, :w].cpu().numpy(), want, what)
+            assert torch.all(Yfull[:, w:] == -7.0), what
+        g.destroy()
