@@ -54,9 +54,9 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 // with several items gets one partial-sum slot per item and is finished by a fix-up pass that adds
 // the slots in order.
 constexpr int TINY_ROW = 4;
-constexpr int LONG_ROW = 32;
+constexpr int LONG_ROW = 64;
 constexpr int PART_ROW = 256;
-constexpr int SMALL_ITEM = 32;   // class pieces up to this many entries: one lane group; longer: wavefronts
+constexpr int SMALL_ITEM = 64;   // class pieces up to this many entries: one lane group; longer: wavefronts
 constexpr int SEG_NNZ = 2048;
 constexpr int MAX_CLASSES = 8;
 constexpr int WIDE_SLOT_COLS = 256; // floats per slot, single-class schedule (256 columns per pass)

@@ -304,8 +304,8 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
     if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
 }
 
-// Lane-group items (whole rows of 5..LONG_ROW entries, class pieces of at most SMALL_ITEM entries;
-// never more than 32 entries): workgroup b serves class b mod n_classes.  Lane i of a wavefront
+// Lane-group items (whole rows of 5..LONG_ROW entries, class pieces of at most SMALL_ITEM entries):
+// workgroup b serves class b mod n_classes.  Lane i of a wavefront
 // reads the descriptor of item i; round r hands item r * G + grp to lane group grp.  The group
 // reads the item's (column, value) pairs with one read per LPR entries (lane `sub` holds entries
 // sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
@@ -315,7 +315,8 @@ __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
 {
     constexpr int G = 64 / LPR;                 // items in flight per wavefront
     constexpr int UNITS = 8 * G;                // items per wavefront
-    constexpr int K = LPR >= 32 ? 1 : 32 / LPR; // index registers per lane (K * LPR >= 32 entries)
+    constexpr int GI_MAX = LONG_ROW > SMALL_ITEM ? LONG_ROW : SMALL_ITEM; // longest lane-group item
+    constexpr int K = LPR >= GI_MAX ? 1 : GI_MAX / LPR; // index registers per lane (K * LPR >= GI_MAX entries)
     constexpr int U = 8;
     using L = Ld<V>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
         }
         Acc<V> acc;
 #pragma unroll
-        for (int j0 = 0; j0 < 32; j0 += U) {
+        for (int j0 = 0; j0 < GI_MAX; j0 += U) {
             if (!__any(j0 < len)) break; // wavefront-uniform
             int c[U];
             float v[U];
