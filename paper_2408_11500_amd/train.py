@@ -1,0 +1,98 @@
+"""The paper's training algorithm (its "Training" algorithm: slice strategy, feature slicing or feature
+fusion, k slice models of L layers, slice encoding + CONCAT, classifier, cross-entropy, backpropagation,
+Adam with cosine-annealed learning rate) as a call sequence over ``libslicegcn.so``.
+
+This module orders library calls and owns buffers; every arithmetic step of an epoch is a kernel of
+the library.  Run ``python -m paper_2408_11500_amd.train --workload cfg1 --epochs 60`` for a seeded
+synthetic run (labels are a function of the features so that there is something to learn).
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+import time
+
+import torch
+
+from . import binding as B
+from .stack import Classifier, FeatureFusion, Optimizer, SliceStack
+
+
+class SliceGCNTrainer:
+    def __init__(self, graph: B.Graph, X: torch.Tensor, labels: torch.Tensor, k: int, slice_hidden: int, layers: int,
+                 hidden: int, classes: int, use_ff: bool = False, slice_size_scale: float = 1.0,
+                 cache_first_aggregation: bool = False):
+        n, feat = X.shape
+        self.X, self.labels, self.use_ff = X, labels.to(torch.int32), use_ff
+        slices, _ = B.slicegcn_slice_strategy(feat, k, slice_size_scale)        # slice strategy generation
+        width = slices[0][1] - slices[0][0]
+        self.ff = FeatureFusion(n, feat, width, device=X.device) if use_ff else None
+        self.stack = SliceStack(graph, n, k, width, slice_hidden, layers, device=X.device,
+                                shared_input=self.ff.Xff if use_ff else None,
+                                cache_first_aggregation=cache_first_aggregation)
+        if not use_ff:                                                           # feature slicing
+            for i, (a, b) in enumerate(slices):
+                B.slicegcn_slice_feature(X, a, b, self.stack.X[i])
+        self.cls = Classifier(n, k * slice_hidden, hidden, classes, device=X.device)
+        self.dH = torch.empty((n, k * slice_hidden), dtype=torch.float32, device=X.device)
+        self.opt = None
+
+    def models(self):
+        return [m for m in (self.ff, self.stack, self.cls) if m is not None]
+
+    def start(self, lr_max: float, lr_min: float, epochs: int, weight_decay: float = 0.0):
+        """Call once after the parameters of all models are set."""
+        self.opt = Optimizer(self.models(), lr_max=lr_max, lr_min=lr_min, t_max=epochs, weight_decay=weight_decay)
+
+    def epoch(self, t: int) -> torch.Tensor:
+        """One epoch: forward, loss, backward, update.  Returns the loss (device scalar, before the update)."""
+        if self.ff is not None:
+            self.ff.forward(self.X)
+        H = self.stack.forward()
+        loss = self.cls.forward_backward(H, self.labels, self.dH)
+        self.stack.backward(self.dH)
+        if self.ff is not None:
+            self.ff.backward(self.X, self.stack.dXin[:, :self.ff.s])
+        self.opt.step(t)
+        return loss
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--epochs", type=int, default=60)
+    ap.add_argument("--lr", type=float, default=1e-2)
+    ap.add_argument("--ff", action="store_true", help="feature-fusion variant")
+    args = ap.parse_args(argv)
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import synth
+    from synth import configs, model
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    src, dst = configs.edges(w, device=dev)
+    g = B.slicegcn_build_norm_csr(src, dst, w.n_nodes)
+    X = configs.features(w, device=dev)
+    y = X[:, :w.classes].argmax(dim=1)  # synthetic target: the largest of the first C features
+    tr = SliceGCNTrainer(g, X, y, w.k, w.slice_hidden, w.layers, w.hidden, w.classes, use_ff=args.ff)
+    for i in range(w.k):
+        for l, (wi, wo) in enumerate(tr.stack.widths):
+            tr.stack.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, device=dev))
+    tr.stack.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, w.k, w.slice_hidden, device=dev, std=0.1))
+    tr.cls.set_params(*model.classifier_params(w, w.k * w.slice_hidden, device=dev))
+    if tr.ff is not None:
+        tr.ff.set_params(*model.fusion_params(w, tr.ff.s, device=dev))
+    tr.start(args.lr, args.lr * 1e-2, args.epochs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.epochs):
+        loss = tr.epoch(t)
+        if t % max(1, args.epochs // 10) == 0 or t == args.epochs - 1:
+            print(f"epoch {t:4d}  loss {loss.item():.4f}", flush=True)
+    torch.cuda.synchronize()
+    print(f"{args.epochs / (time.perf_counter() - t0):.2f} epochs/s")
+    g.destroy()
+
+
+if __name__ == "__main__":
+    main()

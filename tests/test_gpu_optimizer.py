@@ -39,32 +39,27 @@ def test_adam_rejects_bad_arguments():
         B.slicegcn_adam_step(t, t.clone(), t.clone(), t.clone(), 1e-3, 1, beta1=1.0)
 
 
-def test_training_reduces_the_loss():
-    """The training algorithm end to end on the tiny workload with labels that depend on the features:
-    forward, loss, backward and an Adam step per epoch; the loss must at least halve."""
+@pytest.mark.parametrize("use_ff", [False, True])
+def test_training_reduces_the_loss(use_ff):
+    """The training algorithm end to end on the tiny workload (direct slicing and feature fusion) with
+    labels that depend on the features: forward, loss, backward and an Adam step per epoch; the loss must
+    at least halve."""
+    from paper_2408_11500_amd.train import SliceGCNTrainer
     w = synth.WORKLOADS["cfg1"]
     s_, d_ = configs.edges(w)
     g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
-    k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
-    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
-    X = configs.features(w)
-    st = SliceStack(g, n, k, c, hs, L)
-    for i, (a, b_) in enumerate(sl):
-        sg.slicegcn_slice_feature(X.cuda(), a, b_, st.X[i])
-        for l, (wi, wo) in enumerate(st.widths):
-            st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo))
-    cl = Classifier(n, k * hs, w.hidden, w.classes)
-    cl.set_params(*model.classifier_params(w, k * hs))
-    y = (X[:, :w.classes].argmax(dim=1)).to(torch.int32).cuda()   # learnable: the largest of the first C features
-    opt = Optimizer([st, cl], lr_max=1e-2, lr_min=1e-4, t_max=60)
-    assert st.params[0][0]["W_agg"].data_ptr() >= opt.P.data_ptr()         # rebound to views of the flat buffer
-    dH = torch.empty((n, k * hs), dtype=torch.float32, device="cuda")
-    losses = []
-    for epoch in range(60):
-        H = st.forward()
-        losses.append(cl.forward_backward(H, y, dH).item())
-        st.backward(dH)
-        opt.step(epoch)
-    assert losses[-1] < 0.5 * losses[0], losses[::10]
+    X = configs.features(w).cuda()
+    y = X[:, :w.classes].argmax(dim=1)   # learnable: the largest of the first C features
+    tr = SliceGCNTrainer(g, X, y, w.k, w.slice_hidden, w.layers, w.hidden, w.classes, use_ff=use_ff)
+    for i in range(w.k):
+        for l, (wi, wo) in enumerate(tr.stack.widths):
+            tr.stack.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo))
+    tr.cls.set_params(*model.classifier_params(w, w.k * w.slice_hidden))
+    if use_ff:
+        tr.ff.set_params(*model.fusion_params(w, tr.ff.s))
+    tr.start(1e-2, 1e-4, 60)
+    assert tr.stack.params[0][0]["W_agg"].data_ptr() >= tr.opt.P.data_ptr()   # rebound to views of the flat buffer
+    losses = [tr.epoch(t).item() for t in range(60)]
     assert np.isfinite(losses).all()
+    assert losses[-1] < 0.5 * losses[0], losses[::10]
     g.destroy()
