@@ -25,6 +25,8 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict
     __shared__ double row_loss[CE_ROWS_PER_BLOCK];
     const int grp = threadIdx.x / CE_LPR, sub = threadIdx.x % CE_LPR;
     const float inv_n = 1.0f / (float)n;
+    const bool vec = c <= 64 && c % 4 == 0 && ld % 4 == 0 && aligned16(logits) &&
+                     (dlogits == nullptr || (ldd % 4 == 0 && aligned16(dlogits)));
     for (int q = 0; q < 4; ++q) {
         const int local = q * CE_ROWS + grp;
         const int64_t v = (int64_t)blockIdx.x * CE_ROWS_PER_BLOCK + local;
@@ -34,19 +36,44 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict
             int y = labels[v];
             const bool bad = y < 0 || y >= c;
             if (bad) y = 0;
-            float m = -INFINITY;
-            for (int j = sub; j < c; j += CE_LPR) m = fmaxf(m, x[j]);
+            if (vec) { // at most 64 classes, 16-byte accesses: the row lives in one float4 per lane, one exp per element
+                const int j = 4 * sub;
+                float4 q = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (j < c) q = *reinterpret_cast<const float4 *>(x + j);
+                float m = fmaxf(fmaxf(q.x, q.y), fmaxf(q.z, q.w));
 #pragma unroll
-            for (int s = 1; s < CE_LPR; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
-            float sum = 0.f;
-            for (int j = sub; j < c; j += CE_LPR) sum += expf(x[j] - m);
+                for (int s = 1; s < CE_LPR; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+                float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j < c) e = make_float4(expf(q.x - m), expf(q.y - m), expf(q.z - m), expf(q.w - m));
+                float sum = (e.x + e.y) + (e.z + e.w);
 #pragma unroll
-            for (int s = 1; s < CE_LPR; s <<= 1) sum += __shfl_xor(sum, s, 64);
-            loss = bad ? (double)NAN : (double)(m + logf(sum)) - (double)x[y];
-            if (dlogits) {
-                float *g = dlogits + v * ldd;
-                const float inv_sum = 1.0f / sum;
-                for (int j = sub; j < c; j += CE_LPR) g[j] = (expf(x[j] - m) * inv_sum - (j == y ? 1.f : 0.f)) * inv_n;
+                for (int s = 1; s < CE_LPR; s <<= 1) sum += __shfl_xor(sum, s, 64);
+                loss = bad ? (double)NAN : (double)(m + logf(sum)) - (double)x[y];
+                if (dlogits && j < c) {
+                    const float inv_sum = 1.0f / sum;
+                    float4 g4 = make_float4(e.x * inv_sum, e.y * inv_sum, e.z * inv_sum, e.w * inv_sum);
+                    if (y == j) g4.x -= 1.f;
+                    if (y == j + 1) g4.y -= 1.f;
+                    if (y == j + 2) g4.z -= 1.f;
+                    if (y == j + 3) g4.w -= 1.f;
+                    g4.x *= inv_n; g4.y *= inv_n; g4.z *= inv_n; g4.w *= inv_n;
+                    *reinterpret_cast<float4 *>(dlogits + v * ldd + j) = g4;
+                }
+            } else {
+                float m = -INFINITY;
+                for (int j = sub; j < c; j += CE_LPR) m = fmaxf(m, x[j]);
+#pragma unroll
+                for (int s = 1; s < CE_LPR; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+                float sum = 0.f;
+                for (int j = sub; j < c; j += CE_LPR) sum += expf(x[j] - m);
+#pragma unroll
+                for (int s = 1; s < CE_LPR; s <<= 1) sum += __shfl_xor(sum, s, 64);
+                loss = bad ? (double)NAN : (double)(m + logf(sum)) - (double)x[y];
+                if (dlogits) {
+                    float *g = dlogits + v * ldd;
+                    const float inv_sum = 1.0f / sum;
+                    for (int j = sub; j < c; j += CE_LPR) g[j] = (expf(x[j] - m) * inv_sum - (j == y ? 1.f : 0.f)) * inv_n;
+                }
             }
         }
         if (sub == 0) row_loss[local] = loss;
