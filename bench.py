@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--classifier", action="store_true",
                     help="widen the step by the classifier MLP and the cross-entropy loss: the upstream gradient of the "
                          "slice stack then comes from the loss instead of a seeded random matrix")
+    ap.add_argument("--vertex-order", choices=("permuted", "generator"), default="permuted",
+                    help="'generator' keeps the R-MAT generator's own vertex numbering (low numbers are the hubs) instead "
+                         "of the seeded random relabelling: a secondary data point on how much the numbering matters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all k slices execute sequentially on it); "
@@ -120,7 +123,7 @@ def main():
 
     log(f"generating {w.name}: N={w.n_nodes} M_und={w.m_und}")
     t0 = time.perf_counter()
-    src, dst = configs.edges(w, device=dev)
+    src, dst = configs.edges(w, device=dev, permute=args.vertex_order == "permuted")
     torch.cuda.synchronize()
     log(f"edges in {time.perf_counter() - t0:.1f} s")
     t0 = time.perf_counter()
@@ -220,7 +223,7 @@ def main():
     traffic = None
     # HBM-side bytes per aggregation call from the committed rocprofv3 counter summary of this workload
     tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_rocprofv3.md")
-    if os.path.exists(tfile):
+    if os.path.exists(tfile) and args.vertex_order == "permuted":
         import re
         m = re.search(r"^hbm_bytes_per_launch = (\d+)", open(tfile).read(), flags=re.M)
         traffic = int(m.group(1)) if m else None
@@ -230,6 +233,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={n}, nnz={view.nnz} (R-MAT, symmetrised + self loops), F={w.feat} in k={k} "
                                f"slices of {width}, {L} layers, per-slice hidden {hs}, full-batch fwd+bwd"
+                               + (" [generator's vertex numbering, hubs first]" if args.vertex_order != "permuted" else "")
                                + (" [aggregation only]" if args.spmm_only else "")
                                + (" [first-layer aggregation cached across steps]" if args.cache_first_agg and ff is None else "")
                                + (f" + feature fusion {w.feat}->{w.feat}->{width}" if ff is not None else "")

@@ -106,24 +106,45 @@ __global__ void swap_keys_kernel(const uint64_t *__restrict__ in, int64_t nnz, u
 }
 
 // ---- schedule ---------------------------------------------------------------------------
-// Per long row: the entries of column class c are [lower_bound(c * cw), lower_bound((c+1) * cw)).
-// counts layout: cnt[(KINDS*c + kind) * (n+1) + row]; kind 0 = wavefront items of rows cut by column
-// class, 1 = wavefront items of rows kept whole, 2 = lane-group items of rows cut by column class,
-// 3 = lane-group items that are whole rows.  A class's wavefront list is its kind-0 items followed
-// by its kind-1 items (and likewise kinds 2, 3 for the lane-group list), so the class-cut pieces
-// (whose gathers stay inside the class's column range) run before the whole rows (whose gathers
-// span every column and would otherwise keep evicting the class's hot rows from the XCD's L2).
-constexpr int KINDS = 4;
+// Column class c holds the columns [first[c], first[c+1]); the boundaries are the 1/n_classes
+// quantiles of the stored entries per column, so that the classes carry equal numbers of entries
+// whatever the vertex numbering (with hubs numbered first, equal column ranges would put almost
+// half of the entries into the first class).
+struct ClassBounds {
+    int32_t first[MAX_CLASSES + 1];
+};
+
+// colptr: row pointer of the transposed pattern (entries per column, scanned)
+__global__ void class_bounds_kernel(const int32_t *__restrict__ colptr, int64_t n, int n_classes, int32_t *__restrict__ first)
+{
+    const int c = threadIdx.x;
+    if (c > MAX_CLASSES) return;
+    if (c == 0) { first[0] = 0; return; }
+    if (c >= n_classes) { first[c] = (int32_t)n; return; }
+    const int64_t target = (int64_t)colptr[n] * c / n_classes;
+    int64_t lo = 0, hi = n; // smallest column j with colptr[j] >= target
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (colptr[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    first[c] = (int32_t)lo;
+}
+
+// Item tables: 2c = wavefront items of class c (pieces of rows cut by column class), 2c + 1 =
+// lane-group items of class c, 2 * n_classes = wavefront items of rows kept whole, 2 * n_classes + 1
+// = lane-group items that are whole rows.  counts layout: cnt[table * (n+1) + row].
+constexpr int MAX_TABLES = 2 * MAX_CLASSES + 2;
 struct RowCut {
     int32_t lo[MAX_CLASSES + 1];
 };
 
-__device__ inline RowCut cut_row(const int32_t *__restrict__ colidx, int32_t beg, int32_t end, int n_classes, int32_t cw)
+// Per long row: the entries of column class c are [lower_bound(first[c]), lower_bound(first[c+1])).
+__device__ inline RowCut cut_row(const int32_t *__restrict__ colidx, int32_t beg, int32_t end, int n_classes, const ClassBounds &cb)
 {
     RowCut rc;
     rc.lo[0] = beg;
     for (int c = 1; c < n_classes; ++c) {
-        const int32_t target = c * cw; // first column of class c (cw * n_classes >= n, so no overflow past n + cw)
+        const int32_t target = cb.first[c];
         int32_t lo = rc.lo[c - 1], hi = end;
         while (lo < hi) {
             const int32_t mid = lo + ((hi - lo) >> 1);
@@ -137,36 +158,35 @@ __device__ inline RowCut cut_row(const int32_t *__restrict__ colidx, int32_t beg
 
 __device__ inline int pieces_of(int32_t len) { return (len + SEG_NNZ - 1) / SEG_NNZ; }
 
-// The items of one row, in (class, piece) order.  F is called as f(cls, kind, beg, end).
+// The items of one row, in (class, piece) order.  F is called as f(table, beg, end).
 template <class F>
-__device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t r, int32_t beg, int32_t end,
-                                    int n_classes, int32_t cw, int32_t part_row, F f)
+__device__ inline int for_each_item(const int32_t *__restrict__ colidx, int32_t beg, int32_t end,
+                                    int n_classes, const ClassBounds &cb, int32_t part_row, F f)
 {
     const int32_t d = end - beg;
     int total = 0;
     if (d <= TINY_ROW) return 0;
-    const int own = (int)(r % n_classes);
     if (d <= LONG_ROW) {
-        f(own, 3, beg, end);
+        f(2 * n_classes + 1, beg, end);
         return 1;
     }
     if (n_classes == 1 || d <= part_row) {
         const int s = pieces_of(d);
         const int32_t piece = (d + s - 1) / s; // equal cuts, the last one takes the remainder
-        for (int j = 0; j < s; ++j) f(own, 1, beg + j * piece, min(end, beg + (j + 1) * piece));
+        for (int j = 0; j < s; ++j) f(2 * n_classes, beg + j * piece, min(end, beg + (j + 1) * piece));
         return s;
     }
-    const RowCut rc = cut_row(colidx, beg, end, n_classes, cw);
+    const RowCut rc = cut_row(colidx, beg, end, n_classes, cb);
     for (int c = 0; c < n_classes; ++c) {
         const int32_t b = rc.lo[c], e = rc.lo[c + 1], len = e - b;
         if (len <= 0) continue;
         if (len <= SMALL_ITEM) {
-            f(c, 2, b, e);
+            f(2 * c + 1, b, e);
             ++total;
         } else {
             const int s = pieces_of(len);
             const int32_t piece = (len + s - 1) / s;
-            for (int j = 0; j < s; ++j) f(c, 0, b + j * piece, min(e, b + (j + 1) * piece));
+            for (int j = 0; j < s; ++j) f(2 * c, b + j * piece, min(e, b + (j + 1) * piece));
             total += s;
         }
     }
@@ -174,25 +194,25 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int64_t 
 }
 
 __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
-                                   int n_classes, int32_t cw, int32_t part_row, int32_t *__restrict__ cnt,
+                                   int n_classes, const ClassBounds cb, int32_t part_row, int32_t *__restrict__ cnt,
                                    int32_t *__restrict__ c_slot, int32_t *__restrict__ c_fix)
 {
     const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (r > n) return;
     const int64_t stride = n + 1;
-    int32_t per[KINDS * MAX_CLASSES];
-    for (int t = 0; t < KINDS * MAX_CLASSES; ++t) per[t] = 0;
+    int32_t per[MAX_TABLES];
+    for (int t = 0; t < MAX_TABLES; ++t) per[t] = 0;
     int total = 0;
     if (r < n)
-        total = for_each_item(colidx, r, rowptr[r], rowptr[r + 1], n_classes, cw, part_row,
-                              [&](int c, int kind, int32_t, int32_t) { per[KINDS * c + kind] += 1; });
-    for (int t = 0; t < KINDS * n_classes; ++t) cnt[t * stride + r] = per[t];
+        total = for_each_item(colidx, rowptr[r], rowptr[r + 1], n_classes, cb, part_row,
+                              [&](int t, int32_t, int32_t) { per[t] += 1; });
+    for (int t = 0; t < 2 * n_classes + 2; ++t) cnt[t * stride + r] = per[t];
     c_slot[r] = total > 1 ? total : 0;
     c_fix[r] = total > 1 ? 1 : 0;
 }
 
 __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
-                                  int n_classes, int32_t cw, int32_t part_row, const int32_t *__restrict__ off,
+                                  int n_classes, const ClassBounds cb, int32_t part_row, const int32_t *__restrict__ off,
                                   const int32_t *__restrict__ o_slot, const int32_t *__restrict__ o_fix,
                                   Segment *__restrict__ items, FixRow *__restrict__ fix)
 {
@@ -202,17 +222,16 @@ __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int3
     const int32_t beg = rowptr[r], end = rowptr[r + 1];
     if (end - beg <= TINY_ROW) return;
     // first pass: how many items (decides whether they write the row or partial slots)
-    const int total = for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [](int, int, int32_t, int32_t) {});
-    int32_t used[KINDS * MAX_CLASSES];
-    for (int t = 0; t < KINDS * MAX_CLASSES; ++t) used[t] = 0;
+    const int total = for_each_item(colidx, beg, end, n_classes, cb, part_row, [](int, int32_t, int32_t) {});
+    int32_t used[MAX_TABLES];
+    for (int t = 0; t < MAX_TABLES; ++t) used[t] = 0;
     int slot = o_slot[r]; // slots are handed out in (class, piece) order
-    for_each_item(colidx, r, beg, end, n_classes, cw, part_row, [&](int c, int kind, int32_t b, int32_t e) {
+    for_each_item(colidx, beg, end, n_classes, cb, part_row, [&](int t, int32_t b, int32_t e) {
         Segment sg;
         sg.row = (int32_t)r;
         sg.beg = b;
         sg.end = e;
         sg.dst = total == 1 ? (int32_t)r : -(slot + 1);
-        const int t = KINDS * c + kind;
         items[off[t * stride + r] + used[t]] = sg;
         used[t] += 1;
         ++slot;
@@ -285,67 +304,78 @@ void free_csr(Csr &m, bool owns_pattern)
     m = Csr();
 }
 
-int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStream_t stream)
+int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream)
 {
     out = Schedule();
     out.n_classes = n_classes;
+    const int n_tables = 2 * n_classes + 2;
     const size_t stride = (size_t)(n + 1);
-    const size_t n_cnt = KINDS * (size_t)n_classes * stride;
+    const size_t n_cnt = (size_t)n_tables * stride;
     SG_REQUIRE(n_cnt <= (size_t)INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: schedule tables exceed int32 indexing");
-    const int32_t cw = (int32_t)((n + n_classes - 1) / n_classes); // columns per class
     DevBuf cnt, off, aux;
     if (int rc = cnt.alloc(n_cnt * sizeof(int32_t))) return rc;
     if (int rc = off.alloc(n_cnt * sizeof(int32_t))) return rc;
-    if (int rc = aux.alloc(4 * stride * sizeof(int32_t))) return rc; // slot counts, fix counts and their scans
+    if (int rc = aux.alloc((4 * stride + 16) * sizeof(int32_t))) return rc; // slot counts, fix counts, their scans, class bounds
     int32_t *c = cnt.as<int32_t>(), *o = off.as<int32_t>(), *x = aux.as<int32_t>();
+    ClassBounds cb;
+    class_bounds_kernel<<<1, 64, 0, stream>>>(colptr, n, n_classes, x + 4 * stride);
+    SG_LAUNCH_CHECK();
+    SG_HIP(hipMemcpyAsync(cb.first, x + 4 * stride, sizeof(cb.first), hipMemcpyDeviceToHost, stream));
+    SG_HIP(hipStreamSynchronize(stream));
     const int32_t part_row = getenv("SLICEGCN_PART_ROW") ? atoi(getenv("SLICEGCN_PART_ROW")) : PART_ROW;
-    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cw, part_row, c, x, x + stride);
+    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, c, x, x + stride);
     SG_LAUNCH_CHECK();
     if (int rc = scan_i32(c, o, (int64_t)n_cnt, stream)) return rc;
     if (int rc = scan_i32(x, x + 2 * stride, n + 1, stream)) return rc;
     if (int rc = scan_i32(x + stride, x + 3 * stride, n + 1, stream)) return rc;
-    // the scan runs over all (class, kind) tables back to back: table t starts at o[t * stride]
-    std::vector<int32_t> starts(KINDS * n_classes + 1);
-    for (int t = 0; t < KINDS * n_classes; ++t)
+    // the scan runs over all tables back to back: table t starts at o[t * stride]
+    std::vector<int32_t> starts(n_tables + 1);
+    for (int t = 0; t < n_tables; ++t)
         SG_HIP(hipMemcpy(&starts[t], o + (size_t)t * stride, sizeof(int32_t), hipMemcpyDeviceToHost));
     int32_t last_off = 0, last_cnt = 0, n_slots = 0, n_fix = 0;
     SG_HIP(hipMemcpy(&last_off, o + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&last_cnt, c + n_cnt - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&n_slots, x + 2 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
     SG_HIP(hipMemcpy(&n_fix, x + 3 * stride + n, sizeof(int32_t), hipMemcpyDeviceToHost));
-    starts[KINDS * n_classes] = last_off + last_cnt;
+    starts[n_tables] = last_off + last_cnt;
     for (int cl = 0; cl < n_classes; ++cl) {
-        out.big_off[cl] = starts[KINDS * cl];
-        out.big_cnt[cl] = starts[KINDS * cl + 2] - starts[KINDS * cl];
-        out.small_off[cl] = starts[KINDS * cl + 2];
-        out.small_cnt[cl] = starts[KINDS * cl + 4] - starts[KINDS * cl + 2];
+        out.big_off[cl] = starts[2 * cl];
+        out.big_cnt[cl] = starts[2 * cl + 1] - starts[2 * cl];
+        out.small_off[cl] = starts[2 * cl + 1];
+        out.small_cnt[cl] = starts[2 * cl + 2] - starts[2 * cl + 1];
     }
-    out.n_items = starts[KINDS * n_classes];
+    out.wbig_off = starts[2 * n_classes];
+    out.wbig_cnt = starts[2 * n_classes + 1] - starts[2 * n_classes];
+    out.wsmall_off = starts[2 * n_classes + 1];
+    out.wsmall_cnt = starts[2 * n_classes + 2] - starts[2 * n_classes + 1];
+    out.n_items = starts[n_tables];
     out.n_slots = n_slots;
     out.n_fix = n_fix;
     DevBuf items, fix;
     if (int rc = items.alloc((size_t)out.n_items * sizeof(Segment))) return rc;
     if (int rc = fix.alloc((size_t)out.n_fix * sizeof(FixRow))) return rc;
-    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cw, part_row, o, x + 2 * stride,
+    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, o, x + 2 * stride,
                                                          x + 3 * stride, items.as<Segment>(), fix.as<FixRow>());
     SG_LAUNCH_CHECK();
     SG_HIP(hipStreamSynchronize(stream));
     out.items = items.release<Segment>();
     out.fix = fix.release<FixRow>();
     if (getenv("SLICEGCN_VERBOSE")) {
-        int64_t big = 0, small = 0;
-        for (int cl = 0; cl < n_classes; ++cl) { big += out.big_cnt[cl]; small += out.small_cnt[cl]; }
-        fprintf(stderr, "[slicegcn] schedule with %d class(es): %lld wavefront items, %lld lane-group items, %lld rows with "
-                        "several items, %lld partial-sum slots\n", n_classes, (long long)big, (long long)small,
+        fprintf(stderr, "[slicegcn] schedule with %d class(es): whole rows %d wavefront + %d lane-group items, %lld rows with "
+                        "several items, %lld partial-sum slots\n", n_classes, out.wbig_cnt, out.wsmall_cnt,
                 (long long)out.n_fix, (long long)out.n_slots);
+        for (int cl = 0; cl < n_classes && n_classes > 1; ++cl)
+            fprintf(stderr, "[slicegcn]   class %d: columns [%d, %d), %d wavefront + %d lane-group pieces\n", cl,
+                    cb.first[cl], cb.first[cl + 1], out.big_cnt[cl], out.small_cnt[cl]);
     }
     return SLICEGCN_OK;
 }
 
-static int build_schedules(int64_t n, Csr &m, hipStream_t stream)
+// colptr: row pointer of the transposed pattern
+static int build_schedules(int64_t n, Csr &m, const int32_t *colptr, hipStream_t stream)
 {
-    if (int rc = build_schedule(n, m, 1, m.wide, stream)) return rc;
-    return build_schedule(n, m, MAX_CLASSES, m.xcd, stream);
+    if (int rc = build_schedule(n, m, colptr, 1, m.wide, stream)) return rc;
+    return build_schedule(n, m, colptr, MAX_CLASSES, m.xcd, stream);
 }
 
 static int64_t scratch_need(const Csr &m)
@@ -446,9 +476,9 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         g->dinv = dinv.release<float>();
     }
     if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
-    if (int rc = build_schedules(n_nodes, g->fwd, stream)) return rc;
 
     if (sym) {
+        if (int rc = build_schedules(n_nodes, g->fwd, g->fwd.rowptr, stream)) return rc;
         g->tr = g->fwd; // A^ is symmetric: the same arrays serve the transposed product
     } else {
         uint64_t *swapped = keys_b.as<uint64_t>();
@@ -468,7 +498,8 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         SG_LAUNCH_CHECK();
         g->tr.rowptr = rowptr.release<int32_t>();
         if (int rc = pattern_from_keys(keys_c.as<uint64_t>(), nnz, n_nodes, g->dinv, g->tr, stream)) return rc;
-        if (int rc = build_schedules(n_nodes, g->tr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, g->fwd, g->tr.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, g->tr, g->fwd.rowptr, stream)) return rc;
         SG_HIP(hipStreamSynchronize(stream));
     }
 

@@ -44,15 +44,16 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 //   TINY_ROW < d <= LONG_ROW : one lane-group item (the whole row);
 //   d > LONG_ROW             : wavefront items of at most SEG_NNZ entries;
 //   d > PART_ROW (schedules with 8 classes only): the row is first cut by column class
-//       (8 contiguous column ranges; a row's entries of one class are contiguous because columns
-//       ascend); a class piece of at most SMALL_ITEM entries is a lane-group item, a longer one is
-//       cut into wavefront items.
-// Items of class c are executed by workgroups whose index is c modulo n_classes; with 8 classes
+//       (8 contiguous column ranges holding equal shares of the stored entries; a row's entries of
+//       one class are contiguous because columns ascend); a class piece of at most SMALL_ITEM
+//       entries is a lane-group item, a longer one is cut into wavefront items.
+// Pieces of class c are executed by workgroups whose index is c modulo n_classes; with 8 classes
 // and the round-robin placement of workgroups over the 8 XCDs, each XCD's L2 only ever sees its
-// own eighth of the columns of the gathered operand for the partitioned rows.  Whole-row items
-// take class (row mod n_classes) and sit behind the class pieces in their class's list.  A row
-// with several items gets one partial-sum slot per item and is finished by a fix-up pass that adds
-// the slots in order.
+// own class of columns of the gathered operand for the partitioned rows.  Whole-row items form
+// two lists of their own (wavefront and lane-group items, in row order) that are dealt to the
+// classes in fixed-size chunks, round-robin, and run behind the class's pieces.  A row with
+// several items gets one partial-sum slot per item and is finished by a fix-up pass that adds the
+// slots in order.
 constexpr int TINY_ROW = 4;
 constexpr int LONG_ROW = 64;
 constexpr int PART_ROW = 256;
@@ -78,10 +79,12 @@ struct FixRow { // a row whose items went to partial slots [slot_beg, slot_end)
 
 struct Schedule {
     int32_t n_classes = 0;
-    Segment *items = nullptr; // all items, ordered by (class, wavefront before lane-group items, class pieces before whole rows, row, piece)
+    Segment *items = nullptr; // per class its wavefront pieces, then its lane-group pieces; then the whole-row lists
     FixRow *fix = nullptr;
-    int32_t big_off[MAX_CLASSES] = {0}, big_cnt[MAX_CLASSES] = {0};
-    int32_t small_off[MAX_CLASSES] = {0}, small_cnt[MAX_CLASSES] = {0};
+    int32_t big_off[MAX_CLASSES] = {0}, big_cnt[MAX_CLASSES] = {0};     // wavefront pieces of class c
+    int32_t small_off[MAX_CLASSES] = {0}, small_cnt[MAX_CLASSES] = {0}; // lane-group pieces of class c
+    int32_t wbig_off = 0, wbig_cnt = 0;     // wavefront items of rows kept whole
+    int32_t wsmall_off = 0, wsmall_cnt = 0; // lane-group items that are whole rows
     int64_t n_items = 0;
     int64_t n_fix = 0;
     int64_t n_slots = 0;
@@ -133,7 +136,7 @@ struct ProfScope {
 };
 
 // build_csr.hip
-int build_schedule(int64_t n, const Csr &m, int n_classes, Schedule &out, hipStream_t stream);
+int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream);
 void free_csr(Csr &m, bool owns_pattern);
 
 } // namespace slicegcn

@@ -57,8 +57,10 @@ struct SpmmArgs {
     int32_t col0;         // first column of this pass
     int32_t col_end;      // one past the last column of this pass (<= width)
     int32_t vec_store;    // Y (and Add) allow 16-byte accesses
-    int32_t big_off[MAX_CLASSES], big_cnt[MAX_CLASSES];
-    int32_t small_off[MAX_CLASSES], small_cnt[MAX_CLASSES];
+    int32_t big_off[MAX_CLASSES], big_cnt[MAX_CLASSES];     // wavefront pieces of class c
+    int32_t small_off[MAX_CLASSES], small_cnt[MAX_CLASSES]; // lane-group pieces of class c
+    int32_t wbig_off, wbig_cnt;     // wavefront items of rows kept whole (dealt to the classes four at a time)
+    int32_t wsmall_off, wsmall_cnt; // lane-group whole rows (dealt one wavefront's share at a time)
 };
 
 template <int V> struct Acc;
@@ -265,7 +267,8 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
     }
 }
 
-// Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup.  An item's
+// Wavefront items: workgroup b serves class b mod n_classes, four items per workgroup: first the
+// class's own pieces, then every n_classes-th group of four whole-row items.  An item's
 // entries are read 64 (column, value) pairs at a time with one coalesced load each, lane i holding
 // entry base + i, and the next 64 are requested before the current ones are consumed.  (Giving a
 // wavefront several items and prefetching across them was measured and changes nothing: the
@@ -275,9 +278,18 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cls = blockIdx.x % a.n_classes, j = blockIdx.x / a.n_classes;
-    const int item = j * 4 + wave;
-    if (item >= a.big_cnt[cls]) return; // uniform per wavefront
-    const int4 s = *reinterpret_cast<const int4 *>(a.items + a.big_off[cls] + item);
+    const int piece_blocks = (a.big_cnt[cls] + 3) >> 2;
+    int64_t item;
+    if (j < piece_blocks) { // uniform per workgroup
+        item = j * 4 + wave;
+        if (item >= a.big_cnt[cls]) return;
+        item += a.big_off[cls];
+    } else {
+        item = ((int64_t)(j - piece_blocks) * a.n_classes + cls) * 4 + wave;
+        if (item >= a.wbig_cnt) return;
+        item += a.wbig_off;
+    }
+    const int4 s = *reinterpret_cast<const int4 *>(a.items + item);
     const int grp = lane / LPR, sub = lane % LPR;
     const int col = a.col0 + sub * V;
     const bool active = col < a.col_end;
@@ -321,16 +333,27 @@ __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
     using L = Ld<V>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cls = blockIdx.x % a.n_classes, blk = blockIdx.x / a.n_classes;
-    const int first = (blk * 4 + wave) * UNITS;
-    const int count = a.small_cnt[cls] - first;
-    if (count <= 0) return; // uniform per wavefront
+    const int w_idx = blk * 4 + wave;                            // this wavefront among its class's
+    const int piece_waves = (a.small_cnt[cls] + UNITS - 1) / UNITS;
+    int64_t first, left;
+    if (w_idx < piece_waves) { // uniform per wavefront
+        first = (int64_t)w_idx * UNITS;
+        left = a.small_cnt[cls] - first;
+        first += a.small_off[cls];
+    } else {
+        first = ((int64_t)(w_idx - piece_waves) * a.n_classes + cls) * UNITS;
+        left = a.wsmall_cnt - first;
+        first += a.wsmall_off;
+    }
+    if (left <= 0) return;
+    const int count = left < UNITS ? (int)left : UNITS;
     int4 d = make_int4(0, 0, 0, NO_UNIT);
-    if (lane < UNITS && lane < count) d = *reinterpret_cast<const int4 *>(a.items + a.small_off[cls] + first + lane);
+    if (lane < count) d = *reinterpret_cast<const int4 *>(a.items + first + lane);
     const int grp = lane / LPR, sub = lane % LPR, gbase = lane - sub;
     const int col = a.col0 + sub * V;
     const bool col_ok = col < a.col_end;
     const int colc = col_ok ? col : a.col0;
-    const int rounds = ((count < UNITS ? count : UNITS) + G - 1) / G;
+    const int rounds = (count + G - 1) / G;
     int beg = __shfl(d.y, grp, 64), end = __shfl(d.z, grp, 64);
     int c_k[K];
     float v_k[K];
@@ -505,14 +528,20 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     a.n_classes = sc.n_classes;
     a.slot_cols = slot_cols; // narrowed below to the pass width
     a.vec_store = aligned16(Y) && (ldy % 4 == 0) && (!Add || (aligned16(Add) && ldadd % 4 == 0));
-    int max_big = 0, max_small = 0;
+    a.wbig_off = sc.wbig_off; a.wbig_cnt = sc.wbig_cnt;
+    a.wsmall_off = sc.wsmall_off; a.wsmall_cnt = sc.wsmall_cnt;
+    // workgroups per class: the class's own pieces, then its share of the whole-row chunks
+    const int64_t wbig_chunks = ((int64_t)sc.wbig_cnt + 3) / 4;
+    int64_t big_blocks = 0;
     for (int c = 0; c < MAX_CLASSES; ++c) {
         a.big_off[c] = sc.big_off[c]; a.big_cnt[c] = sc.big_cnt[c];
         a.small_off[c] = sc.small_off[c]; a.small_cnt[c] = sc.small_cnt[c];
-        max_big = sc.big_cnt[c] > max_big ? sc.big_cnt[c] : max_big;
-        max_small = sc.small_cnt[c] > max_small ? sc.small_cnt[c] : max_small;
+        if (c >= sc.n_classes) continue;
+        const int64_t b = (sc.big_cnt[c] + 3) / 4 + (wbig_chunks + sc.n_classes - 1 - c) / sc.n_classes;
+        big_blocks = b > big_blocks ? b : big_blocks;
     }
-    a.big_blocks = (max_big + 3) / 4;
+    SG_REQUIRE(big_blocks * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+    a.big_blocks = (int32_t)big_blocks;
     ProfScope prof(Add ? SLICEGCN_PROF_SPMM_ADD : SLICEGCN_PROF_SPMM, width, stream);
     int pass_cols = vec_load ? slot_cols : 64;
     if (pass_cols > 256) pass_cols = 256;
@@ -524,8 +553,15 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
         const int lanes_needed = (a.col_end - c0 + V - 1) / V;
         int lpr = 8;
         while (lpr < lanes_needed) lpr <<= 1; // 8, 16, 32 or 64
-        const int units_per_block = 4 * 8 * (64 / lpr);
-        a.small_blocks = (max_small + units_per_block - 1) / units_per_block;
+        const int units = 8 * (64 / lpr); // lane-group items per wavefront
+        const int64_t wsmall_chunks = ((int64_t)sc.wsmall_cnt + units - 1) / units;
+        int64_t small_waves = 0;
+        for (int c = 0; c < sc.n_classes; ++c) {
+            const int64_t wv = (sc.small_cnt[c] + units - 1) / units + (wsmall_chunks + sc.n_classes - 1 - c) / sc.n_classes;
+            small_waves = wv > small_waves ? wv : small_waves;
+        }
+        SG_REQUIRE((small_waves + 3) / 4 * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+        a.small_blocks = (int32_t)((small_waves + 3) / 4);
         if (int rc = vec_load ? launch_pass<4>(a, lpr, stream) : launch_pass<1>(a, lpr, stream)) return rc;
         if (sc.n_fix > 0) {
             const int64_t threads = sc.n_fix * (int64_t)(a.col_end - c0);

@@ -637,3 +637,35 @@ def test_spmm_seeded_fuzz():
             assert_close(Yfull[:, :w].cpu().numpy(), want, what)
             assert torch.all(Yfull[:, w:] == -7.0), what
         g.destroy()
+
+
+@pytest.mark.parametrize("directed", [False, True])
+@pytest.mark.parametrize("graph", ["rmat_hubs_first", "star"])
+def test_spmm_skewed_vertex_numbering(graph, directed):
+    """Hubs numbered first (the generator's own R-MAT numbering), and a star whose centre column holds
+    a third of all stored entries: the column classes are then very unequal in width (some empty), and
+    the result must still match the oracle entry for entry, in both directions."""
+    if graph == "star":
+        n = 5000
+        src = np.zeros(n - 1, dtype=np.int64); dst = np.arange(1, n, dtype=np.int64)
+        if directed:   # spokes in both directions, plus a one-way ring so that the pattern is not symmetric
+            src, dst = np.concatenate([src, dst, dst]), np.concatenate([dst, src, np.roll(dst, 1)])
+    else:
+        from synth import graphs as sgraphs
+        n = 30000
+        lo, hi = sgraphs.rmat(n, 600000, seed=77, device="cpu", permute=False)
+        src = lo.numpy().astype(np.int64); dst = hi.numpy().astype(np.int64)
+    o, g = build_both(src, dst, n, flags=2 if directed else 3)
+    check_csr(o, g)
+    assert int(o.deg.max()) > 256                     # rows cut by column class exist
+    rng = np.random.default_rng(5)
+    for w, tr in ((32, False), (32, True), (25, False), (100, True)):
+        X = rng.standard_normal((n, w)).astype(np.float32)
+        Y = torch.empty((n, w), dtype=torch.float32, device="cuda")
+        sg.slicegcn_spmm_slice(g, padded(X, padded_ld(w)), Y, transpose=tr)
+        want = oracle.spmm(o, X.astype(np.float64), transpose=tr)
+        assert_close(Y.cpu().numpy(), want, f"{graph} w={w} transpose={tr} directed={directed}")
+        Y2 = torch.empty_like(Y)
+        sg.slicegcn_spmm_slice(g, padded(X, padded_ld(w)), Y2, transpose=tr)
+        assert torch.equal(Y, Y2)
+    g.destroy()
