@@ -600,6 +600,216 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
     }
 }
 
+// The same idea for layers up to 64 wide (K <= 32 * KC, at most 32 * NC output columns).  The weights no
+// longer fit in registers next to the accumulators, so the workgroup keeps them (zero padded, already
+// transposed for the backward products) in LDS and every MFMA reads its B operand from there; the
+// two operand strips of the forward pass go through the wavefront's one tile in turn.  Compiled for
+// two wavefronts per SIMD: one computes while the other moves its strip.
+template <int KC, int NC, bool BWD, bool TWO>
+__global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
+{
+    constexpr int KW = 32 * KC, NW = 32 * NC;
+    constexpr int ST = (KW > NW ? KW : NW) + 4; // tile row stride: 16-byte reads with lane = row stay conflict free
+    constexpr int LK = KW / 4, LN = NW / 4;     // lanes per row, operand strips / output strips
+    constexpr int PK = 32 * LK / 64, PN = 32 * LN / 64; // 16-byte accesses per lane and strip
+    constexpr int QN = 4 * KC;                  // float4 of the reduction axis per row
+    __shared__ __attribute__((aligned(16))) float Tl[4][32][ST];
+    __shared__ float W1s[KW][NW];
+    __shared__ float W2s[TWO ? KW : 1][NW];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int rk = lane / LK, ck = (lane % LK) * 4; // coalesced layout of an operand strip
+    const int rn = lane / LN, cn = (lane % LN) * 4; // and of an output strip
+    const bool vec1 = aligned16(a.A1) && (a.lda1 % 4 == 0);
+    const bool vec2 = TWO && !BWD && aligned16(a.A2) && (a.lda2 % 4 == 0);
+    float (*tl)[ST] = Tl[wave];
+
+    for (int idx = threadIdx.x; idx < KW * NW; idx += 256) {
+        // consecutive threads walk the contiguous axis of W: columns forward, k backward (W^T)
+        const int kk = BWD ? idx % KW : idx / NW, j = BWD ? idx / KW : idx % NW;
+        float w1 = 0.f, w2 = 0.f;
+        if (kk < a.K && j < a.Nout) {
+            const int64_t id = BWD ? (int64_t)j * a.ldw + kk : (int64_t)kk * a.ldw + j;
+            w1 = a.B1[id];
+            if (TWO) w2 = a.B2[id];
+        }
+        W1s[kk][j] = w1;
+        if (TWO) W2s[kk][j] = w2;
+    }
+    __syncthreads(); // the only workgroup barrier: from here on a wavefront touches its own tile only
+
+    float bias1[NC], bias2[NC];
+#pragma unroll
+    for (int t = 0; t < NC; ++t) {
+        const bool ok = 32 * t + m < a.Nout;
+        bias1[t] = (!BWD && a.bias1 && ok) ? a.bias1[32 * t + m] : 0.f;
+        bias2[t] = (!BWD && TWO && a.bias2 && ok) ? a.bias2[32 * t + m] : 0.f;
+    }
+
+    const int64_t n_strips = (a.n + 31) / 32;
+    const int64_t first = (int64_t)blockIdx.x * 4 + wave, step = (int64_t)gridDim.x * 4;
+    float4 p1[PK], p2[(TWO && !BWD) ? PK : 1];
+    uint32_t pw[KC]; // backward: activation words of strip row m
+#pragma unroll
+    for (int w = 0; w < KC; ++w) pw[w] = ~0u;
+    auto fetch = [&](int64_t strip) {
+#pragma unroll
+        for (int it = 0; it < PK; ++it) {
+            const int64_t row = strip * 32 + rk + (64 / LK) * it;
+            float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
+            if (row < a.n && ck < a.K) {
+                v1 = load_k4(a.A1, a.lda1, row, ck, a.K, vec1);
+                if (!BWD && TWO) v2 = load_k4(a.A2, a.lda2, row, ck, a.K, vec2);
+            }
+            p1[it] = v1;
+            if (!BWD && TWO) p2[it] = v2;
+        }
+        if (BWD && a.mask) {
+#pragma unroll
+            for (int w = 0; w < KC; ++w)
+                pw[w] = (strip * 32 + m < a.n && 32 * w < a.K) ? a.mask[(strip * 32 + m) * a.mask_words + w] : 0u;
+        }
+    };
+    if (first < n_strips) fetch(first);
+    for (int64_t strip = first; strip < n_strips; strip += step) {
+#pragma unroll
+        for (int it = 0; it < PK; ++it) *reinterpret_cast<float4 *>(&tl[rk + (64 / LK) * it][ck]) = p1[it];
+        __builtin_amdgcn_wave_barrier();
+        float4 a1[QN];
+#pragma unroll
+        for (int q = 0; q < QN; ++q) a1[q] = *reinterpret_cast<const float4 *>(&tl[m][8 * q + 4 * h]);
+        __builtin_amdgcn_wave_barrier();
+        if (TWO && !BWD) { // the second operand strip takes the tile while the first product runs from registers
+#pragma unroll
+            for (int it = 0; it < PK; ++it) *reinterpret_cast<float4 *>(&tl[rk + (64 / LK) * it][ck]) = p2[it];
+            __builtin_amdgcn_wave_barrier();
+        }
+        const bool more = strip + step < n_strips;
+        uint32_t word[KC];
+#pragma unroll
+        for (int w = 0; w < KC; ++w) word[w] = pw[w];
+        if (more) fetch(strip + step); // flies during the MFMAs and the stores below
+        floatx16 acc1[NC], acc2[NC];
+#pragma unroll
+        for (int t = 0; t < NC; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; acc2[t][r] = 0.f; }
+        if (BWD) { // both products read dHout; the first one through the activation bits (dP = dHout * mask)
+#pragma unroll
+            for (int q = 0; q < QN; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int kk = 8 * q + 4 * h + i;
+                    const float g = pick(a1[q], i);
+                    const float gp = ((word[q >> 2] >> (8 * (q & 3) + 4 * h + i)) & 1u) ? g : 0.f;
+#pragma unroll
+                    for (int t = 0; t < NC; ++t)
+                        acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(gp, W1s[kk][32 * t + m], acc1[t], 0, 0, 0);
+                }
+            if (TWO) {
+#pragma unroll
+                for (int q = 0; q < QN; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int kk = 8 * q + 4 * h + i;
+#pragma unroll
+                        for (int t = 0; t < NC; ++t)
+                            acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1[q], i), W2s[kk][32 * t + m], acc2[t], 0, 0, 0);
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < QN; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int kk = 8 * q + 4 * h + i;
+#pragma unroll
+                    for (int t = 0; t < NC; ++t)
+                        acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1[q], i), W1s[kk][32 * t + m], acc1[t], 0, 0, 0);
+                }
+            if (TWO) {
+#pragma unroll
+                for (int q = 0; q < QN; ++q) a1[q] = *reinterpret_cast<const float4 *>(&tl[m][8 * q + 4 * h]);
+#pragma unroll
+                for (int q = 0; q < QN; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int kk = 8 * q + 4 * h + i;
+#pragma unroll
+                        for (int t = 0; t < NC; ++t)
+                            acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1[q], i), W2s[kk][32 * t + m], acc2[t], 0, 0, 0);
+                    }
+            }
+        }
+        const int64_t row0 = strip * 32;
+        uint32_t my_word[NC]; // lane L < 32 collects the activation words of strip row L
+        if (!BWD) { // the forward result replaces the first accumulator
+#pragma unroll
+            for (int t = 0; t < NC; ++t) {
+                my_word[t] = 0u;
+                const bool col_ok = 32 * t + m < a.Nout;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = acc1[t][r] + bias1[t];
+                    const bool pos = p > 0.f && col_ok;
+                    if (a.act == SLICEGCN_ACT_RELU) {
+                        const unsigned long long bal = __ballot(pos);
+                        if (lane < 32 && r == 4 * (lane >> 3) + (lane & 3))
+                            my_word[t] = ((lane >> 2) & 1) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+                    }
+                    const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
+                    acc1[t][r] = rl + (TWO ? acc2[t][r] + bias2[t] : 0.f);
+                }
+            }
+        }
+        // Outputs leave through the wavefront's tile so that a row goes out as 16-byte stores
+        // (register r of lane (m, h) is strip row 8*(r/4) + 4*h + r%4, column 32 t + m); layouts that
+        // do not allow 16-byte stores write the registers directly.
+        auto store_tile = [&](const floatx16 (&o)[NC], float *O, int64_t ldo, bool vec_ok) {
+            if (vec_ok) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int t = 0; t < NC; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) tl[8 * (r / 4) + 4 * h + (r % 4)][32 * t + m] = o[t][r];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < PN; ++it) {
+                    const int64_t row = row0 + rn + (64 / LN) * it;
+                    const float4 v = *reinterpret_cast<const float4 *>(&tl[rn + (64 / LN) * it][cn]);
+                    if (row < a.n && cn < a.Nout) *reinterpret_cast<float4 *>(O + row * ldo + cn) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int t = 0; t < NC; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
+                        if (orow < a.n && 32 * t + m < a.Nout) O[orow * ldo + 32 * t + m] = o[t][r];
+                    }
+            }
+        };
+        const bool nout4 = a.Nout % 4 == 0;
+        store_tile(acc1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0);
+        if constexpr (BWD && TWO) {
+            if (a.O2) store_tile(acc2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0);
+        }
+        if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && row0 + lane < a.n) {
+#pragma unroll
+            for (int t = 0; t < NC; ++t)
+                if (32 * t < a.Nout) a.mask[(row0 + lane) * a.mask_words + t] = my_word[t];
+        }
+    }
+}
+
+template <int KC, int NC, bool BWD>
+void launch_strip64(const PairArgs &a, unsigned gb, hipStream_t stream)
+{
+    if (a.A2 != nullptr && a.B2 != nullptr) pair_strip64_kernel<KC, NC, BWD, true><<<gb, 256, 0, stream>>>(a);
+    else pair_strip64_kernel<KC, NC, BWD, false><<<gb, 256, 0, stream>>>(a);
+}
+
 template <int NT, bool BWD>
 void launch_direct(const PairArgs &a, dim3 grid, hipStream_t stream)
 {
@@ -628,6 +838,16 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
         const bool two = a.A2 != nullptr && a.B2 != nullptr;
         if (two) pair_strip32_kernel<BWD, true><<<gb, 256, 0, stream>>>(a);
         else pair_strip32_kernel<BWD, false><<<gb, 256, 0, stream>>>(a);
+        SG_LAUNCH_CHECK();
+        return SLICEGCN_OK;
+    }
+    static const bool no_strip64 = getenv("SLICEGCN_NO_STRIP64") != nullptr;
+    if (a.K <= 64 && a.Nout <= 64 && a.n >= 262144 && !no_direct && !no_strip64) { // up to 64 wide: strips, weights in LDS
+        const int64_t strips = (a.n + 31) / 32;
+        const unsigned gb = (unsigned)((strips + 3) / 4 < 1024 ? (strips + 3) / 4 : 1024);
+        if (a.K <= 32) launch_strip64<1, 2, BWD>(a, gb, stream);
+        else if (a.Nout <= 32) launch_strip64<2, 1, BWD>(a, gb, stream);
+        else launch_strip64<2, 2, BWD>(a, gb, stream);
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
     }
@@ -984,6 +1204,138 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
     }
 }
 
+// The same for layers up to 64 wide (w_in <= 32 * MI, w_out <= 32 * NJ, large n): a wavefront owns the
+// whole w_in x w_out gradient pair (2 * MI * NJ accumulators), so every operand row is read from
+// memory exactly once.  Short strips (8 node rows; 16 and 32 are slower) keep the staging registers and
+// the wave-private LDS tiles small enough for two wavefronts per SIMD: while one waits for its tile,
+// the other runs MFMAs.
+template <int MI, int NJ, int SR, int WPS> // SR: node rows per strip; WPS: wavefronts per SIMD to compile for
+__global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs a, int64_t rows_per_wave)
+{
+    constexpr int WI = 32 * MI, WJ = 32 * NJ; // padded widths
+    constexpr int LI = WI / 4, LJ = WJ / 4;   // lanes per row (16-byte accesses)
+    constexpr int PI = SR * LI / 64, PJ = SR * LJ / 64; // passes over a strip
+    __shared__ __attribute__((aligned(16))) float Zs[4][SR][WI];
+    __shared__ __attribute__((aligned(16))) float Hs[4][SR][WI];
+    __shared__ __attribute__((aligned(16))) float Gs[4][SR][WJ];
+    __shared__ uint32_t Ms[4][SR][NJ];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int ri = lane / LI, ci = (lane % LI) * 4; // coalesced layout of the w_in-wide operands
+    const int rj = lane / LJ, cj = (lane % LJ) * 4; // and of dHout
+    const int64_t w_id = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t r_begin = w_id * rows_per_wave;
+    const int64_t r_end = r_begin + rows_per_wave < a.n ? r_begin + rows_per_wave : a.n;
+    if (r_begin >= a.n) return; // uniform per wavefront; no workgroup barriers below
+    const bool self = a.Hin != nullptr;
+    const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
+    const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
+    float (*zs)[WI] = Zs[wave];
+    float (*hs)[WI] = Hs[wave];
+    float (*gs)[WJ] = Gs[wave];
+    uint32_t (*ms)[NJ] = Ms[wave];
+
+    floatx16 accA[MI][NJ], accS[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { accA[i][j][r] = 0.f; accS[i][j][r] = 0.f; }
+    float sum_p[NJ], sum_g[NJ]; // column 32 j + m of dP and of dHout over the node rows 2 s + h
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) { sum_p[j] = 0.f; sum_g[j] = 0.f; }
+
+    float4 pz[PI], ph[PI], pg[PJ];
+    uint32_t pw = ~0u; // lane l < SR * NJ: word l % NJ of strip row l / NJ
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int it = 0; it < PI; ++it) {
+            const int64_t row = r0 + ri + (64 / LI) * it;
+            float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z;
+            if (row < r_end && ci < a.w_in) {
+                z = load_k4(a.Z, a.ldz, row, ci, a.w_in, vz);
+                if (self) hh = load_k4(a.Hin, a.ldi, row, ci, a.w_in, vh);
+            }
+            pz[it] = z; ph[it] = hh;
+        }
+#pragma unroll
+        for (int it = 0; it < PJ; ++it) {
+            const int64_t row = r0 + rj + (64 / LJ) * it;
+            float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < r_end && cj < a.w_out) g = load_k4(a.dHout, a.ldo, row, cj, a.w_out, vg);
+            pg[it] = g;
+        }
+        if (a.mask && lane < SR * NJ) {
+            const int64_t row = r0 + lane / NJ;
+            const int word = lane % NJ;
+            pw = (row < r_end && 32 * word < a.w_out) ? a.mask[row * a.mask_words + word] : 0u;
+        }
+    };
+    fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += SR) {
+#pragma unroll
+        for (int it = 0; it < PI; ++it) {
+            *reinterpret_cast<float4 *>(&zs[ri + (64 / LI) * it][ci]) = pz[it];
+            *reinterpret_cast<float4 *>(&hs[ri + (64 / LI) * it][ci]) = ph[it];
+        }
+#pragma unroll
+        for (int it = 0; it < PJ; ++it) *reinterpret_cast<float4 *>(&gs[rj + (64 / LJ) * it][cj]) = pg[it];
+        if (lane < SR * NJ) ms[lane / NJ][lane % NJ] = pw;
+        __builtin_amdgcn_wave_barrier();
+        if (r0 + SR < r_end) fetch(r0 + SR);
+#pragma unroll
+        for (int s2 = 0; s2 < SR / 2; ++s2) {
+            const int k = 2 * s2 + h;
+            float g[NJ], pp[NJ], z[MI], hh[MI];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                g[j] = gs[k][32 * j + m];
+                pp[j] = ((ms[k][j] >> m) & 1u) ? g[j] : 0.f;
+                sum_p[j] += pp[j];
+                sum_g[j] += g[j];
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                z[i] = zs[k][32 * i + m];
+                hh[i] = hs[k][32 * i + m];
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    accA[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(z[i], pp[j], accA[i][j], 0, 0, 0);
+                    if (self) accS[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(hh[i], g[j], accS[i][j], 0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    float *out = a.partial + w_id * a.stride;
+    const int ww = a.w_in * a.w_out;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 32 * i + 8 * (r / 4) + 4 * h + (r % 4), col = 32 * j + m;
+                if (row < a.w_in && col < a.w_out) {
+                    out[row * a.w_out + col] = accA[i][j][r];
+                    if (!a.compact) out[ww + row * a.w_out + col] = accS[i][j][r];
+                }
+            }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const float sp = sum_p[j] + __shfl_xor(sum_p[j], 32, 64);
+        const float sg = sum_g[j] + __shfl_xor(sum_g[j], 32, 64);
+        const int col = 32 * j + m;
+        if (lane < 32 && col < a.w_out) {
+            out[(a.compact ? ww : 2 * ww) + col] = sp;
+            if (!a.compact) out[2 * ww + a.w_out + col] = sg;
+        }
+    }
+}
+
 // Partial weight gradient of a single product (compact layout: [X^T dP | colsum dP]) for wide
 // layers: one workgroup per 128 x 128 output tile and block of RED_ROWS rows, each wavefront owning a
 // 64 x 64 quarter (four MFMA accumulators).  Per step 32 rows of the X tile and of the dP tile are
@@ -1322,6 +1674,16 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
             const int64_t rows_per_wave = round_up((g->n + waves - 1) / waves, 32);
             n_partials = (g->n + rows_per_wave - 1) / rows_per_wave;
             grad_strip32_kernel<<<(unsigned)((n_partials + 3) / 4), 256, 0, stream>>>(r, rows_per_wave);
+        } else if (use_mfma() && w_in <= 64 && w_out <= 64 && nb >= 2048 && !getenv("SLICEGCN_NO_STRIP64")) {
+            // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
+            const int64_t resident = 3072;
+            const int64_t waves = nb >= resident ? nb / resident * resident : nb >= 2048 ? 2048 : nb;
+            const int64_t rows_per_wave = round_up((g->n + waves - 1) / waves, 32);
+            n_partials = (g->n + rows_per_wave - 1) / rows_per_wave;
+            const unsigned gb = (unsigned)((n_partials + 3) / 4);
+            if (w_in <= 32) grad_strip64_kernel<1, 2, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
+            else if (w_out <= 32) grad_strip64_kernel<2, 1, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
+            else grad_strip64_kernel<2, 2, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
         } else if (use_mfma()) {
             grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
         } else {

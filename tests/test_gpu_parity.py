@@ -562,7 +562,23 @@ def test_cached_first_aggregation_equals_recomputed():
 def test_narrow_layer_many_rows(shape, act, has_self):
     """Layers of width <= 32 on a graph with more than 65536 rows (not a multiple of 32): the
     per-wavefront strip kernels of the dense products and of the weight gradients, forward and backward."""
-    n = 70001
+    layer_many_rows(70001, shape, act, has_self)
+
+
+@pytest.mark.parametrize("shape,act,has_self", [((64, 64), 1, True), ((25, 64), 1, True), ((64, 25), 1, False)])
+def test_mid_layer_many_rows(shape, act, has_self):
+    """Layers up to 64 wide on more than 2^21 rows (not a multiple of 32): the strip kernels that keep
+    the weights in LDS, and the weight-gradient kernel with one 64 x 64 pair of accumulators per wavefront."""
+    layer_many_rows(2100001, shape, act, has_self)
+
+
+@pytest.mark.parametrize("shape,act,has_self", [((40, 50), 1, False), ((64, 64), 0, True), ((33, 64), 1, True), ((64, 7), 1, True)])
+def test_mid_layer_ragged_widths(shape, act, has_self):
+    """The same dense kernels at widths that fill neither their 32-column tiles nor 16-byte accesses."""
+    layer_many_rows(270001, shape, act, has_self)
+
+
+def layer_many_rows(n, shape, act, has_self):
     rng = np.random.default_rng(shape[0] * 100 + shape[1] + act)
     src = rng.integers(0, n, 3 * n); dst = rng.integers(0, n, 3 * n)
     o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n)
@@ -572,7 +588,7 @@ def test_narrow_layer_many_rows(shape, act, has_self):
     Hd = padded(Hin, padded_ld(w_in))
     Hout = torch.empty((n, w_out + 4), dtype=torch.float32, device="cuda")[:, :w_out]
     Zd = torch.empty((n, padded_ld(w_in)), dtype=torch.float32, device="cuda")[:, :w_in]
-    maskd = torch.zeros((n, 1), dtype=torch.int32, device="cuda") if act else None
+    maskd = torch.zeros((n, (w_out + 31) // 32), dtype=torch.int32, device="cuda") if act else None
     sg.slicegcn_layer_fwd(g, Hd, dev(W_agg), dev(b), dev(W_self) if has_self else None, dev(b_self) if has_self else None,
                           Hout, Zd, maskd, act=act)
     assert_close(Hout.cpu().numpy(), want, "Hout")
