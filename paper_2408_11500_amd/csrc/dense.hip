@@ -1206,11 +1206,13 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
 
 // The same for layers up to 64 wide (w_in <= 32 * MI, w_out <= 32 * NJ, large n): a wavefront owns the
 // whole w_in x w_out gradient pair (2 * MI * NJ accumulators), so every operand row is read from
-// memory exactly once.  Short strips (8 node rows; 16 and 32 are slower) keep the staging registers and
-// the wave-private LDS tiles small enough for two wavefronts per SIMD: while one waits for its tile,
-// the other runs MFMAs.
+// memory exactly once.  Strips are dealt to the wavefronts round-robin, so at any moment the chip
+// reads one contiguous window of the operands.  Short strips (8 node rows; 4, 16 and 32 are no
+// faster, nor is keeping two or three strips in flight) keep the staging registers and the
+// wave-private LDS tiles small enough for two wavefronts per SIMD beside the 128 accumulator
+// registers of the full-width variant, three for the half-width ones.
 template <int MI, int NJ, int SR, int WPS> // SR: node rows per strip; WPS: wavefronts per SIMD to compile for
-__global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs a, int64_t rows_per_wave)
+__global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs a, int64_t n_waves)
 {
     constexpr int WI = 32 * MI, WJ = 32 * NJ; // padded widths
     constexpr int LI = WI / 4, LJ = WJ / 4;   // lanes per row (16-byte accesses)
@@ -1224,9 +1226,8 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
     const int ri = lane / LI, ci = (lane % LI) * 4; // coalesced layout of the w_in-wide operands
     const int rj = lane / LJ, cj = (lane % LJ) * 4; // and of dHout
     const int64_t w_id = (int64_t)blockIdx.x * 4 + wave;
-    const int64_t r_begin = w_id * rows_per_wave;
-    const int64_t r_end = r_begin + rows_per_wave < a.n ? r_begin + rows_per_wave : a.n;
-    if (r_begin >= a.n) return; // uniform per wavefront; no workgroup barriers below
+    const int64_t n_strips = (a.n + SR - 1) / SR;
+    if (w_id >= n_waves) return; // uniform per wavefront; no workgroup barriers below (n_waves <= n_strips)
     const bool self = a.Hin != nullptr;
     const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
     const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
@@ -1253,7 +1254,7 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
         for (int it = 0; it < PI; ++it) {
             const int64_t row = r0 + ri + (64 / LI) * it;
             float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z;
-            if (row < r_end && ci < a.w_in) {
+            if (row < a.n && ci < a.w_in) {
                 z = load_k4(a.Z, a.ldz, row, ci, a.w_in, vz);
                 if (self) hh = load_k4(a.Hin, a.ldi, row, ci, a.w_in, vh);
             }
@@ -1263,17 +1264,17 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
         for (int it = 0; it < PJ; ++it) {
             const int64_t row = r0 + rj + (64 / LJ) * it;
             float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < r_end && cj < a.w_out) g = load_k4(a.dHout, a.ldo, row, cj, a.w_out, vg);
+            if (row < a.n && cj < a.w_out) g = load_k4(a.dHout, a.ldo, row, cj, a.w_out, vg);
             pg[it] = g;
         }
         if (a.mask && lane < SR * NJ) {
             const int64_t row = r0 + lane / NJ;
             const int word = lane % NJ;
-            pw = (row < r_end && 32 * word < a.w_out) ? a.mask[row * a.mask_words + word] : 0u;
+            pw = (row < a.n && 32 * word < a.w_out) ? a.mask[row * a.mask_words + word] : 0u;
         }
     };
-    fetch(r_begin);
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += SR) {
+    fetch(w_id * SR);
+    for (int64_t strip = w_id; strip < n_strips; strip += n_waves) { // wavefront w takes strips w, w + n_waves, ...
 #pragma unroll
         for (int it = 0; it < PI; ++it) {
             *reinterpret_cast<float4 *>(&zs[ri + (64 / LI) * it][ci]) = pz[it];
@@ -1283,7 +1284,7 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
         for (int it = 0; it < PJ; ++it) *reinterpret_cast<float4 *>(&gs[rj + (64 / LJ) * it][cj]) = pg[it];
         if (lane < SR * NJ) ms[lane / NJ][lane % NJ] = pw;
         __builtin_amdgcn_wave_barrier();
-        if (r0 + SR < r_end) fetch(r0 + SR);
+        if (strip + n_waves < n_strips) fetch((strip + n_waves) * SR);
 #pragma unroll
         for (int s2 = 0; s2 < SR / 2; ++s2) {
             const int k = 2 * s2 + h;
@@ -1677,13 +1678,14 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         } else if (use_mfma() && w_in <= 64 && w_out <= 64 && nb >= 2048 && !getenv("SLICEGCN_NO_STRIP64")) {
             // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
             const int64_t resident = 3072;
-            const int64_t waves = nb >= resident ? nb / resident * resident : nb >= 2048 ? 2048 : nb;
-            const int64_t rows_per_wave = round_up((g->n + waves - 1) / waves, 32);
-            n_partials = (g->n + rows_per_wave - 1) / rows_per_wave;
-            const unsigned gb = (unsigned)((n_partials + 3) / 4);
-            if (w_in <= 32) grad_strip64_kernel<1, 2, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
-            else if (w_out <= 32) grad_strip64_kernel<2, 1, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
-            else grad_strip64_kernel<2, 2, 8, 2><<<gb, 256, 0, stream>>>(r, rows_per_wave);
+            int64_t waves = nb >= resident ? nb / resident * resident : nb >= 2048 ? 2048 : nb;
+            const int64_t n_strips = (g->n + 7) / 8; // strips of 8 rows in every variant launched here
+            if (waves > n_strips) waves = n_strips;
+            n_partials = waves;
+            const unsigned gb = (unsigned)((waves + 3) / 4);
+            if (w_in <= 32) grad_strip64_kernel<1, 2, 8, 3><<<gb, 256, 0, stream>>>(r, waves);
+            else if (w_out <= 32) grad_strip64_kernel<2, 1, 8, 3><<<gb, 256, 0, stream>>>(r, waves);
+            else grad_strip64_kernel<2, 2, 8, 2><<<gb, 256, 0, stream>>>(r, waves);
         } else if (use_mfma()) {
             grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
         } else {
