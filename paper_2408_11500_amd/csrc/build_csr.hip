@@ -161,12 +161,12 @@ __device__ inline int pieces_of(int32_t len) { return (len + SEG_NNZ - 1) / SEG_
 // The items of one row, in (class, piece) order.  F is called as f(table, beg, end).
 template <class F>
 __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int32_t beg, int32_t end,
-                                    int n_classes, const ClassBounds &cb, int32_t part_row, F f)
+                                    int n_classes, const ClassBounds &cb, int32_t part_row, int32_t item_max, F f)
 {
     const int32_t d = end - beg;
     int total = 0;
     if (d <= TINY_ROW) return 0;
-    if (d <= LONG_ROW) {
+    if (d <= item_max) {
         f(2 * n_classes + 1, beg, end);
         return 1;
     }
@@ -180,7 +180,7 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int32_t 
     for (int c = 0; c < n_classes; ++c) {
         const int32_t b = rc.lo[c], e = rc.lo[c + 1], len = e - b;
         if (len <= 0) continue;
-        if (len <= SMALL_ITEM) {
+        if (len <= item_max) {
             f(2 * c + 1, b, e);
             ++total;
         } else {
@@ -194,7 +194,7 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int32_t 
 }
 
 __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
-                                   int n_classes, const ClassBounds cb, int32_t part_row, int32_t *__restrict__ cnt,
+                                   int n_classes, const ClassBounds cb, int32_t part_row, int32_t item_max, int32_t *__restrict__ cnt,
                                    int32_t *__restrict__ c_slot, int32_t *__restrict__ c_fix)
 {
     const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
@@ -204,7 +204,7 @@ __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int
     for (int t = 0; t < MAX_TABLES; ++t) per[t] = 0;
     int total = 0;
     if (r < n)
-        total = for_each_item(colidx, rowptr[r], rowptr[r + 1], n_classes, cb, part_row,
+        total = for_each_item(colidx, rowptr[r], rowptr[r + 1], n_classes, cb, part_row, item_max,
                               [&](int t, int32_t, int32_t) { per[t] += 1; });
     for (int t = 0; t < 2 * n_classes + 2; ++t) cnt[t * stride + r] = per[t];
     c_slot[r] = total > 1 ? total : 0;
@@ -212,7 +212,7 @@ __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int
 }
 
 __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
-                                  int n_classes, const ClassBounds cb, int32_t part_row, const int32_t *__restrict__ off,
+                                  int n_classes, const ClassBounds cb, int32_t part_row, int32_t item_max, const int32_t *__restrict__ off,
                                   const int32_t *__restrict__ o_slot, const int32_t *__restrict__ o_fix,
                                   Segment *__restrict__ items, FixRow *__restrict__ fix)
 {
@@ -222,11 +222,11 @@ __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int3
     const int32_t beg = rowptr[r], end = rowptr[r + 1];
     if (end - beg <= TINY_ROW) return;
     // first pass: how many items (decides whether they write the row or partial slots)
-    const int total = for_each_item(colidx, beg, end, n_classes, cb, part_row, [](int, int32_t, int32_t) {});
+    const int total = for_each_item(colidx, beg, end, n_classes, cb, part_row, item_max, [](int, int32_t, int32_t) {});
     int32_t used[MAX_TABLES];
     for (int t = 0; t < MAX_TABLES; ++t) used[t] = 0;
     int slot = o_slot[r]; // slots are handed out in (class, piece) order
-    for_each_item(colidx, beg, end, n_classes, cb, part_row, [&](int t, int32_t b, int32_t e) {
+    for_each_item(colidx, beg, end, n_classes, cb, part_row, item_max, [&](int t, int32_t b, int32_t e) {
         Segment sg;
         sg.row = (int32_t)r;
         sg.beg = b;
@@ -304,10 +304,15 @@ void free_csr(Csr &m, bool owns_pattern)
     m = Csr();
 }
 
-int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream)
+int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream)
 {
     out = Schedule();
     out.n_classes = n_classes;
+    // entries (8 bytes each) plus one 128-byte operand row per node against the 256 MB last-level cache
+    const bool resident = nnz * 8 + n * 128 <= ((int64_t)256 << 20);
+    int32_t item_max = resident ? ITEM_SHORT : ITEM_LONG;
+    if (const char *e = getenv("SLICEGCN_ITEM_MAX")) item_max = atoi(e) == ITEM_SHORT ? ITEM_SHORT : ITEM_LONG;
+    out.item_max = item_max;
     const int n_tables = 2 * n_classes + 2;
     const size_t stride = (size_t)(n + 1);
     const size_t n_cnt = (size_t)n_tables * stride;
@@ -323,7 +328,7 @@ int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes
     SG_HIP(hipMemcpyAsync(cb.first, x + 4 * stride, sizeof(cb.first), hipMemcpyDeviceToHost, stream));
     SG_HIP(hipStreamSynchronize(stream));
     const int32_t part_row = getenv("SLICEGCN_PART_ROW") ? atoi(getenv("SLICEGCN_PART_ROW")) : PART_ROW;
-    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, c, x, x + stride);
+    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, item_max, c, x, x + stride);
     SG_LAUNCH_CHECK();
     if (int rc = scan_i32(c, o, (int64_t)n_cnt, stream)) return rc;
     if (int rc = scan_i32(x, x + 2 * stride, n + 1, stream)) return rc;
@@ -354,7 +359,7 @@ int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes
     DevBuf items, fix;
     if (int rc = items.alloc((size_t)out.n_items * sizeof(Segment))) return rc;
     if (int rc = fix.alloc((size_t)out.n_fix * sizeof(FixRow))) return rc;
-    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, o, x + 2 * stride,
+    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, item_max, o, x + 2 * stride,
                                                          x + 3 * stride, items.as<Segment>(), fix.as<FixRow>());
     SG_LAUNCH_CHECK();
     SG_HIP(hipStreamSynchronize(stream));
@@ -372,10 +377,10 @@ int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes
 }
 
 // colptr: row pointer of the transposed pattern
-static int build_schedules(int64_t n, Csr &m, const int32_t *colptr, hipStream_t stream)
+static int build_schedules(int64_t n, int64_t nnz, Csr &m, const int32_t *colptr, hipStream_t stream)
 {
-    if (int rc = build_schedule(n, m, colptr, 1, m.wide, stream)) return rc;
-    return build_schedule(n, m, colptr, MAX_CLASSES, m.xcd, stream);
+    if (int rc = build_schedule(n, nnz, m, colptr, 1, m.wide, stream)) return rc;
+    return build_schedule(n, nnz, m, colptr, MAX_CLASSES, m.xcd, stream);
 }
 
 static int64_t scratch_need(const Csr &m)
@@ -478,7 +483,7 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
     if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
 
     if (sym) {
-        if (int rc = build_schedules(n_nodes, g->fwd, g->fwd.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->fwd.rowptr, stream)) return rc;
         g->tr = g->fwd; // A^ is symmetric: the same arrays serve the transposed product
     } else {
         uint64_t *swapped = keys_b.as<uint64_t>();
@@ -498,8 +503,8 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         SG_LAUNCH_CHECK();
         g->tr.rowptr = rowptr.release<int32_t>();
         if (int rc = pattern_from_keys(keys_c.as<uint64_t>(), nnz, n_nodes, g->dinv, g->tr, stream)) return rc;
-        if (int rc = build_schedules(n_nodes, g->fwd, g->tr.rowptr, stream)) return rc;
-        if (int rc = build_schedules(n_nodes, g->tr, g->fwd.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->tr.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->tr, g->fwd.rowptr, stream)) return rc;
         SG_HIP(hipStreamSynchronize(stream));
     }
 

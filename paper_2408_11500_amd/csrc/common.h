@@ -41,12 +41,15 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 // ---- aggregation schedule -------------------------------------------------------------
 // Rows are split by their number of stored entries d:
 //   d <= TINY_ROW            : handled whole, 64 consecutive rows per wavefront, in natural order;
-//   TINY_ROW < d <= LONG_ROW : one lane-group item (the whole row);
-//   d > LONG_ROW             : wavefront items of at most SEG_NNZ entries;
+//   TINY_ROW < d <= item_max : one lane-group item (the whole row);
+//   d > item_max             : wavefront items of at most SEG_NNZ entries;
 //   d > PART_ROW (schedules with 8 classes only): the row is first cut by column class
 //       (8 contiguous column ranges holding equal shares of the stored entries; a row's entries of
-//       one class are contiguous because columns ascend); a class piece of at most SMALL_ITEM
+//       one class are contiguous because columns ascend); a class piece of at most item_max
 //       entries is a lane-group item, a longer one is cut into wavefront items.
+// item_max is fixed per graph: ITEM_SHORT when the whole working set stays in the last-level cache
+// (the kernels are then bound by instruction issue, and shorter lane-group items win), ITEM_LONG when
+// the gathers go to memory (fewer, longer items keep more gathers in flight).
 // Pieces of class c are executed by workgroups whose index is c modulo n_classes; with 8 classes
 // and the round-robin placement of workgroups over the 8 XCDs, each XCD's L2 only ever sees its
 // own class of columns of the gathered operand for the partitioned rows.  Whole-row items form
@@ -55,9 +58,9 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 // several items gets one partial-sum slot per item and is finished by a fix-up pass that adds the
 // slots in order.
 constexpr int TINY_ROW = 4;
-constexpr int LONG_ROW = 64;
+constexpr int ITEM_SHORT = 32;
+constexpr int ITEM_LONG = 64;
 constexpr int PART_ROW = 256;
-constexpr int SMALL_ITEM = 64;   // class pieces up to this many entries: one lane group; longer: wavefronts
 constexpr int SEG_NNZ = 2048;
 constexpr int MAX_CLASSES = 8;
 constexpr int WIDE_SLOT_COLS = 256; // floats per slot, single-class schedule (256 columns per pass)
@@ -79,6 +82,7 @@ struct FixRow { // a row whose items went to partial slots [slot_beg, slot_end)
 
 struct Schedule {
     int32_t n_classes = 0;
+    int32_t item_max = ITEM_LONG; // longest lane-group item (whole row or class piece)
     Segment *items = nullptr; // per class its wavefront pieces, then its lane-group pieces; then the whole-row lists
     FixRow *fix = nullptr;
     int32_t big_off[MAX_CLASSES] = {0}, big_cnt[MAX_CLASSES] = {0};     // wavefront pieces of class c
@@ -136,7 +140,7 @@ struct ProfScope {
 };
 
 // build_csr.hip
-int build_schedule(int64_t n, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream);
+int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream);
 void free_csr(Csr &m, bool owns_pattern);
 
 } // namespace slicegcn

@@ -6,7 +6,7 @@
 //     then hands row (t * GROUPS + grp) to lane group grp in sub-round t through cross-lane reads,
 //     so one wavefront keeps many independent row gathers in flight and the output stream stays
 //     contiguous;
-//   * lane-group items (whole rows of up to LONG_ROW entries, short class pieces of partitioned
+//   * lane-group items (whole rows of up to item_max entries, short class pieces of partitioned
 //     rows): one item per lane group at a time, its (column, value) pairs read LPR at a time by the
 //     group's lanes and handed out by cross-lane reads, the next item's pairs requested before the
 //     current item's gathers;
@@ -28,7 +28,8 @@
 // Environment (diagnostics / tuning, read once): SLICEGCN_SPMM_SCHEDULE=rowsplit|xcd forces the
 // single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
 // are cut by column class when a graph is built; SLICEGCN_PASS_COLS=<c> narrows the column passes of
-// the 16-byte path (default 64); SLICEGCN_VERBOSE=1 prints schedule statistics.
+// the 16-byte path (default 64); SLICEGCN_ITEM_MAX=32|64 fixes the longest lane-group item when a graph
+// is built (default: by working-set size); SLICEGCN_VERBOSE=1 prints schedule statistics.
 #include "common.h"
 
 #include <cstdlib>
@@ -51,6 +52,7 @@ struct SpmmArgs {
     uint32_t ldx_bytes;   // S32 kernels: byte stride of X rows (n * ldx * 4 < 2^32, n and ldx * 4 < 2^24)
     int32_t n;
     int32_t n_classes;
+    int32_t item_max;     // longest lane-group item of the schedule (ITEM_SHORT or ITEM_LONG)
     int32_t big_blocks;   // workgroups per class in the wavefront-item section
     int32_t small_blocks; // workgroups per class in the lane-group-item section
     int32_t slot_cols;    // floats per partial-sum slot
@@ -316,18 +318,17 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
     if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
 }
 
-// Lane-group items (whole rows of 5..LONG_ROW entries, class pieces of at most SMALL_ITEM entries):
+// Lane-group items (whole rows and class pieces of 5..GI_MAX entries, GI_MAX = the schedule's item_max):
 // workgroup b serves class b mod n_classes.  Lane i of a wavefront
 // reads the descriptor of item i; round r hands item r * G + grp to lane group grp.  The group
 // reads the item's (column, value) pairs with one read per LPR entries (lane `sub` holds entries
 // sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
 // gather takes its pair from the holding lane by a cross-lane read, eight gathers in flight.
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, int GI_MAX>
 __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
 {
     constexpr int G = 64 / LPR;                 // items in flight per wavefront
     constexpr int UNITS = 8 * G;                // items per wavefront
-    constexpr int GI_MAX = LONG_ROW > SMALL_ITEM ? LONG_ROW : SMALL_ITEM; // longest lane-group item
     constexpr int K = LPR >= GI_MAX ? 1 : GI_MAX / LPR; // index registers per lane (K * LPR >= GI_MAX entries)
     constexpr int U = 8;
     using L = Ld<V>;
@@ -462,7 +463,8 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
         SG_LAUNCH_CHECK();
     }
     if (g2 > 0) {
-        spmm_group_items_kernel<LPR, V, S32><<<(unsigned)g2, 256, 0, stream>>>(a);
+        if (a.item_max <= ITEM_SHORT) spmm_group_items_kernel<LPR, V, S32, ITEM_SHORT><<<(unsigned)g2, 256, 0, stream>>>(a);
+        else spmm_group_items_kernel<LPR, V, S32, ITEM_LONG><<<(unsigned)g2, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
     spmm_tiny_rows_kernel<LPR, V, S32><<<(unsigned)g3, 256, 0, stream>>>(a);
@@ -526,6 +528,7 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     a.ldx_bytes = s32 ? (uint32_t)(ldx * 4) : 0u;
     a.n = (int32_t)g->n;
     a.n_classes = sc.n_classes;
+    a.item_max = sc.item_max;
     a.slot_cols = slot_cols; // narrowed below to the pass width
     a.vec_store = aligned16(Y) && (ldy % 4 == 0) && (!Add || (aligned16(Add) && ldadd % 4 == 0));
     a.wbig_off = sc.wbig_off; a.wbig_cnt = sc.wbig_cnt;

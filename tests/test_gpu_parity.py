@@ -3,6 +3,8 @@
 Integer outputs (rowptr, colidx, degrees, slice bounds) must be bit-exact; fp32 outputs and
 gradients must be within a max relative error of 1e-4 (max|got - want| / max|want|).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -637,7 +639,12 @@ def test_spmm_seeded_fuzz():
                 nb = rng.choice(n, size=min(n - 1, int(rng.integers(300, 5000))), replace=False)
                 src = np.concatenate([src, np.full(nb.size, hnode)]); dst = np.concatenate([dst, nb])
         flags = int(rng.choice([3, 3, 2, 1, 0]))
-        o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n, flags)
+        # both lane-group item limits (graphs this small would all get the short one)
+        os.environ["SLICEGCN_ITEM_MAX"] = "64" if case % 2 else "32"
+        try:
+            o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n, flags)
+        finally:
+            del os.environ["SLICEGCN_ITEM_MAX"]
         check_csr(o, g)
         for _ in range(2):
             w = int(rng.choice([1, 2, 5, 25, 31, 32, 33, 64, 100, 130]))
@@ -671,7 +678,11 @@ def test_spmm_skewed_vertex_numbering(graph, directed):
         n = 30000
         lo, hi = sgraphs.rmat(n, 600000, seed=77, device="cpu", permute=False)
         src = lo.numpy().astype(np.int64); dst = hi.numpy().astype(np.int64)
-    o, g = build_both(src, dst, n, flags=2 if directed else 3)
+    os.environ["SLICEGCN_ITEM_MAX"] = "64"            # the limit large graphs get; the other tests run the short one
+    try:
+        o, g = build_both(src, dst, n, flags=2 if directed else 3)
+    finally:
+        del os.environ["SLICEGCN_ITEM_MAX"]
     check_csr(o, g)
     assert int(o.deg.max()) > 256                     # rows cut by column class exist
     rng = np.random.default_rng(5)
