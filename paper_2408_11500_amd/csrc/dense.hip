@@ -1632,7 +1632,7 @@ extern "C" size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slic
     if (!desc || n_nodes < 1 || desc->w_in < 1 || desc->w_out < 1) return 0;
     const size_t stride = 2 * (size_t)desc->w_in * desc->w_out + 2 * (size_t)desc->w_out;
     size_t bytes = (size_t)round_up((int64_t)(red_blocks(n_nodes) * stride * sizeof(float)), 256);
-    if (need_dHin) bytes += (size_t)round_up(n_nodes * round_up(desc->w_in, 4) * (int64_t)sizeof(float), 256);
+    if (need_dHin) bytes += (size_t)round_up(n_nodes * round_up(desc->w_in, 32) * (int64_t)sizeof(float), 256);
     return bytes;
 }
 
@@ -1705,7 +1705,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
 
     // ---- input gradient: dHin = A^^T (dP W_agg^T) + dHout W_self^T ----
     if (dHin) {
-        const int64_t ldz = round_up(w_in, 4);
+        const int64_t ldz = round_up(w_in, 32); // rows of the gathered operand start on 128-byte boundaries
         float *dZ = reinterpret_cast<float *>(static_cast<char *>(ws) +
                                               round_up((int64_t)(nb * stride * sizeof(float)), 256));
         PairArgs a;
