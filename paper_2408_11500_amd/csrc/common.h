@@ -64,7 +64,7 @@ constexpr int PART_ROW = 256;
 constexpr int SEG_NNZ = 2048;
 constexpr int MAX_CLASSES = 8;
 constexpr int WIDE_SLOT_COLS = 256; // floats per slot, single-class schedule (256 columns per pass)
-constexpr int XCD_SLOT_COLS = 64;   // floats per slot, 8-class schedule (64 columns per pass)
+constexpr int XCD_SLOT_COLS = 128;  // floats per slot, 8-class schedule (128 columns per pass)
 
 struct Segment { // 16 bytes, read as one int4
     int32_t row;

@@ -28,7 +28,7 @@
 // Environment (diagnostics / tuning, read once): SLICEGCN_SPMM_SCHEDULE=rowsplit|xcd forces the
 // single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
 // are cut by column class when a graph is built; SLICEGCN_PASS_COLS=<c> narrows the column passes of
-// the 16-byte path (default 64); SLICEGCN_ITEM_MAX=32|64 fixes the longest lane-group item when a graph
+// the 16-byte path (default 128); SLICEGCN_ITEM_MAX=32|64 fixes the longest lane-group item when a graph
 // is built (default: by working-set size); SLICEGCN_VERBOSE=1 prints schedule statistics.
 #include "common.h"
 
@@ -511,9 +511,10 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
     const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
     const int V = vec_load ? 4 : 1;
-    // 16-byte gathers use the 8-class schedule in passes of at most 64 columns: a narrow pass keeps
-    // the set of hot rows of the operand small enough for the L2s (a wider operand costs more index
-    // reads, which are small next to the gathers); the scalar path keeps the single-class schedule
+    // 16-byte gathers use the 8-class schedule in passes of at most 128 columns (32 lanes per row):
+    // narrower passes re-read the index streams more often, wider ones make the set of hot rows of
+    // the operand too large for the L2s (301 columns: 7.8 / 7.4 / 7.7 ms for passes of 64 / 128 / 256);
+    // the scalar path keeps the single-class schedule
     const int forced = forced_schedule();
     const bool use_xcd = forced ? forced == 2 : vec_load;
     const Schedule &sc = use_xcd ? m.xcd : m.wide;

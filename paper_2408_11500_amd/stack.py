@@ -12,7 +12,7 @@ from . import binding as B
 
 def padded_ld(width: int) -> int:
     """Leading dimension for a slice operand: every row starts on a 128-byte boundary, so a gathered
-    row (or a 64-column pass over it) touches the fewest cache lines (a 301-wide slice at ld 304 has
+    row (or a column pass over it) touches the fewest cache lines (a 301-wide slice at ld 304 has
     every other row straddle one line more: 8.7 vs 7.8 ms per aggregation)."""
     return (width + 31) // 32 * 32
 
