@@ -1114,12 +1114,12 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
 }
 
 // Partial weight gradients of the narrowest layers (w_in, w_out <= 32, large n): every wavefront owns
-// a contiguous range of rows and its own accumulators, walks the range in strips of 32 rows read
-// with coalesced 16-byte loads into wave-private LDS tiles (the next strip's loads in flight during
-// the MFMAs), and writes one partial result.  The node axis is the MFMA's k axis (lane (m, h) feeds
+// its own accumulators and every n_waves-th strip of 32 rows (so that the chip reads one contiguous
+// window at a time), reads a strip with coalesced 16-byte loads into wave-private LDS tiles (the
+// next strip's loads in flight during the MFMAs), and writes one partial result.  The node axis is the MFMA's k axis (lane (m, h) feeds
 // column m of node row 2s + h).  No workgroup barrier; same output layout as grad_partial_kernel,
 // one partial per wavefront.
-__global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, int64_t rows_per_wave)
+__global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, int64_t n_waves)
 {
     __shared__ __attribute__((aligned(16))) float Zs[4][32][32];
     __shared__ __attribute__((aligned(16))) float Hs[4][32][32];
@@ -1129,9 +1129,8 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
     const int m = lane & 31, h = lane >> 5;
     const int lr = lane >> 3, lc = (lane & 7) * 4;
     const int64_t w_id = (int64_t)blockIdx.x * 4 + wave;
-    const int64_t r_begin = w_id * rows_per_wave;
-    const int64_t r_end = r_begin + rows_per_wave < a.n ? r_begin + rows_per_wave : a.n;
-    if (r_begin >= a.n) return; // uniform per wavefront; no barriers below
+    const int64_t n_strips = (a.n + 31) / 32, r_end = a.n;
+    if (w_id >= n_waves) return; // uniform per wavefront; no barriers below (n_waves <= n_strips)
     const bool self = a.Hin != nullptr;
     const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
     const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
@@ -1163,8 +1162,8 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
         }
         if (a.mask && lane < 32) pw = r0 + lane < r_end ? a.mask[(r0 + lane) * a.mask_words] : 0u;
     };
-    fetch(r_begin);
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
+    fetch(w_id * 32);
+    for (int64_t strip = w_id; strip < n_strips; strip += n_waves) { // wavefront w takes strips w, w + n_waves, ...
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             *reinterpret_cast<float4 *>(&zs[lr + 8 * it][lc]) = pz[it];
@@ -1173,7 +1172,7 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
         }
         if (lane < 32) ms[lane] = pw;
         __builtin_amdgcn_wave_barrier();
-        if (r0 + 32 < r_end) fetch(r0 + 32);
+        if (strip + n_waves < n_strips) fetch((strip + n_waves) * 32);
 #pragma unroll
         for (int s2 = 0; s2 < 16; ++s2) {
             const int k = 2 * s2 + h;
@@ -1671,10 +1670,11 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         int64_t n_partials = nb;
         if (use_mfma() && w_in <= 32 && w_out <= 32 && g->n >= 65536) {
             // one partial per wavefront, at most as many as the workspace has rows (nb) and as fill the chip
-            const int64_t waves = nb < 8192 ? nb : 8192;
-            const int64_t rows_per_wave = round_up((g->n + waves - 1) / waves, 32);
-            n_partials = (g->n + rows_per_wave - 1) / rows_per_wave;
-            grad_strip32_kernel<<<(unsigned)((n_partials + 3) / 4), 256, 0, stream>>>(r, rows_per_wave);
+            int64_t waves = nb < 8192 ? nb : 8192;
+            const int64_t n_strips = (g->n + 31) / 32;
+            if (waves > n_strips) waves = n_strips;
+            n_partials = waves;
+            grad_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, waves);
         } else if (use_mfma() && w_in <= 64 && w_out <= 64 && nb >= 2048 && !getenv("SLICEGCN_NO_STRIP64")) {
             // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
             const int64_t resident = 3072;
