@@ -105,7 +105,8 @@ def main():
     torch.cuda.set_device(dev)
     w = synth.WORKLOADS[args.workload]
 
-    if args.copy_calibration:
+    def stream_copy():
+        """A plain 4 GiB device copy with the library's copy kernel: the HBM rate this box attains."""
         rows, ld = 1 << 22, 256   # 2^30 floats = 4 GiB read + 4 GiB written by one plain copy kernel
         a = torch.ones((rows, ld), dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -117,8 +118,11 @@ def main():
             sg.slicegcn_slice_feature(a, 0, ld, b)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / 5
-        print(json.dumps({"copy_bytes_read": rows * ld * 4, "copy_bytes_written": rows * ld * 4, "ms": dt * 1e3,
-                          "GBps": 2 * rows * ld * 4 / dt / 1e9}))
+        return {"copy_bytes_read": rows * ld * 4, "copy_bytes_written": rows * ld * 4, "ms": dt * 1e3,
+                "GBps": 2 * rows * ld * 4 / dt / 1e9}
+
+    if args.copy_calibration:
+        print(json.dumps(stream_copy()))
         return
 
     log(f"generating {w.name}: N={w.n_nodes} M_und={w.m_und}")
@@ -248,6 +252,7 @@ def main():
                      "algorithmic_bytes_per_launch": nbytes},
         "kernels": kernels,
     }
+    out["roofline"]["stream_copy_GBps"] = stream_copy()["GBps"]   # what a plain copy reaches on this machine, for scale
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         out["cpu_baseline"] = cpu_baseline(w, src, dst, lambda i: st.X[i][:, :width].cpu().numpy(), slices, width,
