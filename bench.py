@@ -191,7 +191,8 @@ def main():
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = sg.slicegcn_profile_end()
+    prof_full = sg.slicegcn_profile_end(with_range=True)
+    prof = [e[:4] for e in prof_full]
     ms_per_step = elapsed * 1e3 / args.steps
     log(f"{args.steps} steps, {ms_per_step:.2f} ms/step")
 
@@ -208,7 +209,8 @@ def main():
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         log(f"HIP graph replay: {graph_ms:.2f} ms/step")
 
-    kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt} for kind, wd, cnt, tot in prof}
+    kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt, "min_ms": lo, "max_ms": hi}
+               for kind, wd, cnt, tot, lo, hi in prof_full}
     dom = next(((cnt, tot) for kind, wd, cnt, tot in prof if kind == "spmm" and wd == width), None)
     if dom is None and args.cache_first_agg:
         # the cached variant ran no aggregation at the slice width inside the steps: time it on its own

@@ -311,6 +311,8 @@ typedef struct {
     int32_t width;
     int64_t launches;
     double total_ms;
+    double min_ms; /* shortest and longest single launch group of this (kind, width) */
+    double max_ms;
 } slicegcn_profile_entry;
 int slicegcn_profile_begin(void);
 int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t capacity, int32_t *count);

@@ -65,7 +65,7 @@ class _LayerSaved(ctypes.Structure):
 
 class _ProfileEntry(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("width", ctypes.c_int32), ("launches", ctypes.c_int64),
-                ("total_ms", ctypes.c_double)]
+                ("total_ms", ctypes.c_double), ("min_ms", ctypes.c_double), ("max_ms", ctypes.c_double)]
 
 
 class _LayerGrads(ctypes.Structure):
@@ -431,10 +431,12 @@ def slicegcn_profile_begin():
     _check(lib().slicegcn_profile_begin())
 
 
-def slicegcn_profile_end(capacity: int = 64):
-    """[(kind name, width, launches, total_ms)] of the kernels launched since profile_begin."""
+def slicegcn_profile_end(capacity: int = 64, with_range: bool = False):
+    """[(kind name, width, launches, total_ms)] of the kernels launched since profile_begin;
+    with_range appends (min_ms, max_ms) of a single launch group."""
     arr = (_ProfileEntry * capacity)()
     count = ctypes.c_int32(0)
     _check(lib().slicegcn_profile_end(arr, capacity, ctypes.byref(count)))
     return [(PROF_KINDS.get(e.kind, str(e.kind)), int(e.width), int(e.launches), float(e.total_ms))
+            + ((float(e.min_ms), float(e.max_ms)) if with_range else ())
             for e in arr[:min(count.value, capacity)]]

@@ -324,13 +324,16 @@ extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t cap
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_prof_on = false;
     SG_HIP(hipDeviceSynchronize());
-    std::map<std::pair<int, int>, std::pair<int64_t, double>> sum;
+    struct Acc { int64_t launches = 0; double total = 0.0, lo = 0.0, hi = 0.0; };
+    std::map<std::pair<int, int>, Acc> sum;
     for (auto &r : g_prof) {
         float ms = 0.f;
         if (r.closed && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
             auto &e = sum[{r.kind, r.width}];
-            e.first += 1;
-            e.second += (double)ms;
+            if (e.launches == 0 || ms < e.lo) e.lo = ms;
+            if (e.launches == 0 || ms > e.hi) e.hi = ms;
+            e.launches += 1;
+            e.total += (double)ms;
         }
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -341,8 +344,10 @@ extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t cap
         if (i < capacity) {
             entries[i].kind = kv.first.first;
             entries[i].width = kv.first.second;
-            entries[i].launches = kv.second.first;
-            entries[i].total_ms = kv.second.second;
+            entries[i].launches = kv.second.launches;
+            entries[i].total_ms = kv.second.total;
+            entries[i].min_ms = kv.second.lo;
+            entries[i].max_ms = kv.second.hi;
         }
         ++i;
     }
