@@ -16,13 +16,18 @@ import time
 import torch
 
 from . import binding as B
-from .stack import Classifier, FeatureFusion, Optimizer, SliceStack
+from .stack import Classifier, FeatureFusion, GraphedStep, Optimizer, SliceStack
 
 
 class SliceGCNTrainer:
     def __init__(self, graph: B.Graph, X: torch.Tensor, labels: torch.Tensor, k: int, slice_hidden: int, layers: int,
                  hidden: int, classes: int, use_ff: bool = False, slice_size_scale: float = 1.0,
-                 cache_first_aggregation: bool = False):
+                 cache_first_aggregation: bool = False, graph_replay: bool = False):
+        """``graph_replay``: forward, loss and backward of an epoch are captured into a HIP graph at the first
+        epoch and replayed afterwards (the update stays an eager launch: its learning rate and step count
+        are launch arguments).  The features and labels must then stay in the tensors given here."""
+        if graph_replay and cache_first_aggregation:
+            raise ValueError("graph_replay captures one fixed call sequence; the cached first aggregation changes it")
         n, feat = X.shape
         self.X, self.labels, self.use_ff = X, labels.to(torch.int32), use_ff
         slices, _ = B.slicegcn_slice_strategy(feat, k, slice_size_scale)        # slice strategy generation
@@ -37,6 +42,7 @@ class SliceGCNTrainer:
         self.cls = Classifier(n, k * slice_hidden, hidden, classes, device=X.device)
         self.dH = torch.empty((n, k * slice_hidden), dtype=torch.float32, device=X.device)
         self.opt = None
+        self.graph_replay, self._graph = graph_replay, None
 
     def models(self):
         return [m for m in (self.ff, self.stack, self.cls) if m is not None]
@@ -45,17 +51,26 @@ class SliceGCNTrainer:
         """Call once after the parameters of all models are set."""
         self.opt = Optimizer(self.models(), lr_max=lr_max, lr_min=lr_min, t_max=epochs, weight_decay=weight_decay)
 
-    def epoch(self, t: int) -> torch.Tensor:
-        """One epoch: forward, loss, backward, update.  Returns the loss (device scalar, before the update)."""
+    def forward_backward(self):
+        """Forward, loss and backward of one epoch (no update)."""
         if self.ff is not None:
             self.ff.forward(self.X)
         H = self.stack.forward()
-        loss = self.cls.forward_backward(H, self.labels, self.dH)
+        self.cls.forward_backward(H, self.labels, self.dH)
         self.stack.backward(self.dH)
         if self.ff is not None:
             self.ff.backward(self.X, self.stack.dXin[:, :self.ff.s])
+
+    def epoch(self, t: int) -> torch.Tensor:
+        """One epoch: forward, loss, backward, update.  Returns the loss (device scalar, before the update)."""
+        if self.graph_replay:
+            if self._graph is None:
+                self._graph = GraphedStep(self.forward_backward)
+            self._graph.replay()
+        else:
+            self.forward_backward()
         self.opt.step(t)
-        return loss
+        return self.cls.loss
 
 
 def main(argv=None):
@@ -64,6 +79,7 @@ def main(argv=None):
     ap.add_argument("--epochs", type=int, default=60)
     ap.add_argument("--lr", type=float, default=1e-2)
     ap.add_argument("--ff", action="store_true", help="feature-fusion variant")
+    ap.add_argument("--graph", action="store_true", help="replay forward + loss + backward as one HIP graph")
     args = ap.parse_args(argv)
     sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     import synth
@@ -74,7 +90,8 @@ def main(argv=None):
     g = B.slicegcn_build_norm_csr(src, dst, w.n_nodes)
     X = configs.features(w, device=dev)
     y = X[:, :w.classes].argmax(dim=1)  # synthetic target: the largest of the first C features
-    tr = SliceGCNTrainer(g, X, y, w.k, w.slice_hidden, w.layers, w.hidden, w.classes, use_ff=args.ff)
+    tr = SliceGCNTrainer(g, X, y, w.k, w.slice_hidden, w.layers, w.hidden, w.classes, use_ff=args.ff,
+                         graph_replay=args.graph)
     for i in range(w.k):
         for l, (wi, wo) in enumerate(tr.stack.widths):
             tr.stack.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, device=dev))

@@ -39,6 +39,39 @@ def test_adam_rejects_bad_arguments():
         B.slicegcn_adam_step(t, t.clone(), t.clone(), t.clone(), 1e-3, 1, beta1=1.0)
 
 
+def make_trainer(w, g, X, y, use_ff, graph_replay=False):
+    from paper_2408_11500_amd.train import SliceGCNTrainer
+    tr = SliceGCNTrainer(g, X, y, w.k, w.slice_hidden, w.layers, w.hidden, w.classes, use_ff=use_ff,
+                         graph_replay=graph_replay)
+    for i in range(w.k):
+        for l, (wi, wo) in enumerate(tr.stack.widths):
+            tr.stack.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo))
+    tr.cls.set_params(*model.classifier_params(w, w.k * w.slice_hidden))
+    if use_ff:
+        tr.ff.set_params(*model.fusion_params(w, tr.ff.s))
+    tr.start(1e-2, 1e-4, 60)
+    return tr
+
+
+@pytest.mark.parametrize("use_ff", [False, True])
+def test_training_with_graph_replay_equals_eager(use_ff):
+    """Replaying forward + loss + backward as one HIP graph gives, epoch after epoch, the same bits as the
+    eager call sequence (the parameter update runs eagerly between the replays in both)."""
+    w = synth.WORKLOADS["cfg1"]
+    s_, d_ = configs.edges(w)
+    g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
+    X = configs.features(w).cuda()
+    y = X[:, :w.classes].argmax(dim=1)
+    eager = make_trainer(w, g, X, y, use_ff)
+    replay = make_trainer(w, g, X, y, use_ff, graph_replay=True)
+    for t in range(6):
+        le, lr_ = eager.epoch(t), replay.epoch(t)
+        torch.cuda.synchronize()
+        assert torch.equal(le, lr_), t
+        assert torch.equal(eager.opt.P, replay.opt.P), t
+    g.destroy()
+
+
 @pytest.mark.parametrize("use_ff", [False, True])
 def test_training_reduces_the_loss(use_ff):
     """The training algorithm end to end on the tiny workload (direct slicing and feature fusion) with
