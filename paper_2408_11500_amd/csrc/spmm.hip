@@ -29,7 +29,8 @@
 // single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
 // are cut by column class when a graph is built; SLICEGCN_PASS_COLS=<c> narrows the column passes of
 // the 16-byte path (default 128); SLICEGCN_ITEM_MAX=32|64 fixes the longest lane-group item when a graph
-// is built (default: by working-set size); SLICEGCN_VERBOSE=1 prints schedule statistics.
+// is built (default: by working-set size); SLICEGCN_SPMM_SEPARATE=1 keeps the three item kernels as
+// separate launches for small graphs too; SLICEGCN_VERBOSE=1 prints schedule statistics.
 #include "common.h"
 
 #include <cstdlib>
@@ -276,10 +277,10 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
 // wavefront several items and prefetching across them was measured and changes nothing: the
 // kernel is bound by the traffic of the gathers, not by the latency of its index loads.)
 template <int LPR, int V, bool S32>
-__global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
+__device__ __forceinline__ void wave_items_body(const SpmmArgs &a, int block)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int cls = blockIdx.x % a.n_classes, j = blockIdx.x / a.n_classes;
+    const int cls = block % a.n_classes, j = block / a.n_classes;
     const int piece_blocks = (a.big_cnt[cls] + 3) >> 2;
     int64_t item;
     if (j < piece_blocks) { // uniform per workgroup
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a)
 // sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
 // gather takes its pair from the holding lane by a cross-lane read, eight gathers in flight.
 template <int LPR, int V, bool S32, int GI_MAX>
-__global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
+__device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
 {
     constexpr int G = 64 / LPR;                 // items in flight per wavefront
     constexpr int UNITS = 8 * G;                // items per wavefront
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
     constexpr int U = 8;
     using L = Ld<V>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int cls = blockIdx.x % a.n_classes, blk = blockIdx.x / a.n_classes;
+    const int cls = block % a.n_classes, blk = block / a.n_classes;
     const int w_idx = blk * 4 + wave;                            // this wavefront among its class's
     const int piece_waves = (a.small_cnt[cls] + UNITS - 1) / UNITS;
     int64_t first, left;
@@ -409,11 +410,11 @@ __global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a)
 
 // Rows of at most TINY_ROW entries, 64 consecutive rows per wavefront in natural order.
 template <int LPR, int V, bool S32>
-__global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a)
+__device__ __forceinline__ void tiny_rows_body(const SpmmArgs &a, int block)
 {
     constexpr int UNITS = 8 * (64 / LPR); // rows per wavefront
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int first = (blockIdx.x * 4 + wave) * UNITS;
+    const int first = (block * 4 + wave) * UNITS;
     if (first >= a.n) return; // uniform per wavefront
     int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
     if (lane < UNITS && first + lane < a.n) {
@@ -422,6 +423,30 @@ __global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a)
         if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
     }
     batch_units<LPR, V, S32>(a, beg_l, end_l, row_l, dst_l, lane);
+}
+
+template <int LPR, int V, bool S32>
+__global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a) { wave_items_body<LPR, V, S32>(a, blockIdx.x); }
+
+template <int LPR, int V, bool S32, int GI_MAX>
+__global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a) { group_items_body<LPR, V, S32, GI_MAX>(a, blockIdx.x); }
+
+template <int LPR, int V, bool S32>
+__global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a) { tiny_rows_body<LPR, V, S32>(a, blockIdx.x); }
+
+// All three item kinds in one launch: workgroups [0, g1) take wavefront items, [g1, g1 + g2)
+// lane-group items, the rest tiny rows (g1 and g2 are multiples of n_classes, so workgroup b still
+// serves class b mod n_classes).  For graphs that stay in cache a call takes tens of microseconds and
+// each of three launches would pay its own ramp-up and its own chain of dependent loads; in one launch
+// they overlap (cfg2: 0.075 -> 0.056 ms per call).  Large graphs keep the three launches: there the
+// class pieces must have the L2s to themselves before the whole rows start (merged: cfg5 4.09 -> 4.30 ms).
+template <int LPR, int V, bool S32>
+__global__ __launch_bounds__(256) void spmm_merged_kernel(const SpmmArgs a, int g1, int g2)
+{
+    const int b = blockIdx.x; // uniform per workgroup
+    if (b < g1) wave_items_body<LPR, V, S32>(a, b);
+    else if (b < g1 + g2) group_items_body<LPR, V, S32, ITEM_SHORT>(a, b - g1);
+    else tiny_rows_body<LPR, V, S32>(a, b - g1 - g2);
 }
 
 // Rows with several items: add the partial slots in order.  One thread per (row, column); eight
@@ -458,6 +483,12 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
     const int64_t g2 = (int64_t)a.n_classes * a.small_blocks;
     const int64_t g3 = (a.n + units_per_block - 1) / units_per_block;
     SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX && g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+    static const bool no_merge = getenv("SLICEGCN_SPMM_SEPARATE") != nullptr;
+    if (a.item_max <= ITEM_SHORT && g1 + g2 + g3 <= INT32_MAX && !no_merge) { // cache-resident graph: one launch
+        spmm_merged_kernel<LPR, V, S32><<<(unsigned)(g1 + g2 + g3), 256, 0, stream>>>(a, (int)g1, (int)g2);
+        SG_LAUNCH_CHECK();
+        return SLICEGCN_OK;
+    }
     if (g1 > 0) {
         spmm_wave_items_kernel<LPR, V, S32><<<(unsigned)g1, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
