@@ -924,6 +924,7 @@ struct ReduceArgs {
     int32_t w_in, w_out;
     int32_t stride;                     // 2*w_in*w_out + 2*w_out; compact: w_in*w_out + w_out
     int32_t compact;                    // 1: no self term and no slot for it: [Z^T dP | colsum dP]
+    int32_t rows_per_block = RED_ROWS;  // tiled kernels: node rows per workgroup (one partial each)
 };
 
 __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
@@ -935,8 +936,8 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
     const int tid = threadIdx.x;
     const int ty = tid / 16, tx = tid % 16;
     const int i_base = blockIdx.y * RED_TILE, j_base = blockIdx.z * RED_TILE;
-    const int64_t r_begin = (int64_t)blockIdx.x * RED_ROWS;
-    const int64_t r_end = r_begin + RED_ROWS < a.n ? r_begin + RED_ROWS : a.n;
+    const int64_t r_begin = (int64_t)blockIdx.x * a.rows_per_block;
+    const int64_t r_end = r_begin + a.rows_per_block < a.n ? r_begin + a.rows_per_block : a.n;
     const bool self = a.Hin != nullptr;
 
     float accA[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, accS[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
@@ -1022,8 +1023,8 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
     const int wave = tid >> 6, lane = tid & 63;
     const int m = lane & 31, h = lane >> 5;
     const int i_base = blockIdx.y * RED_TILE, j_base = blockIdx.z * RED_TILE;
-    const int64_t r_begin = (int64_t)blockIdx.x * RED_ROWS;
-    const int64_t r_end = r_begin + RED_ROWS < a.n ? r_begin + RED_ROWS : a.n;
+    const int64_t r_begin = (int64_t)blockIdx.x * a.rows_per_block;
+    const int64_t r_end = r_begin + a.rows_per_block < a.n ? r_begin + a.rows_per_block : a.n;
     const bool self = a.Hin != nullptr;
     const bool vz = aligned16(a.Z) && a.ldz % 4 == 0, vh = self && aligned16(a.Hin) && a.ldi % 4 == 0;
     const bool vg = aligned16(a.dHout) && a.ldo % 4 == 0;
@@ -1549,6 +1550,20 @@ __global__ __launch_bounds__(1024) void reduce_final_kernel(const float *__restr
 
 inline int64_t red_blocks(int64_t n) { return (n + RED_ROWS - 1) / RED_ROWS; }
 
+// Node rows per partial sum of a slice layer's weight gradients: RED_ROWS, or a quarter of it when that
+// would give the tiled kernel fewer than 2048 workgroups (a workgroup walks its rows in dependent steps
+// of 32, so on small graphs shorter walks in more workgroups finish sooner: cfg2 80 -> 35 us).
+inline int32_t layer_grad_rows(int64_t n, int32_t w_in, int32_t w_out)
+{
+    const int64_t tiles = (int64_t)((w_in + RED_TILE - 1) / RED_TILE) * ((w_out + RED_TILE - 1) / RED_TILE);
+    return red_blocks(n) * tiles < 2048 ? RED_ROWS / 4 : RED_ROWS;
+}
+inline int64_t layer_grad_blocks(int64_t n, int32_t w_in, int32_t w_out)
+{
+    const int32_t rows = layer_grad_rows(n, w_in, w_out);
+    return (n + rows - 1) / rows;
+}
+
 int check_layer(const slicegcn_graph *g, const slicegcn_layer_desc *d, const slicegcn_layer_params *p, const char *who)
 {
     SG_REQUIRE(g && d && p, SLICEGCN_EINVAL, "%s: NULL graph, desc or params", who);
@@ -1630,7 +1645,7 @@ extern "C" size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slic
 {
     if (!desc || n_nodes < 1 || desc->w_in < 1 || desc->w_out < 1) return 0;
     const size_t stride = 2 * (size_t)desc->w_in * desc->w_out + 2 * (size_t)desc->w_out;
-    size_t bytes = (size_t)round_up((int64_t)(red_blocks(n_nodes) * stride * sizeof(float)), 256);
+    size_t bytes = (size_t)round_up((int64_t)(layer_grad_blocks(n_nodes, desc->w_in, desc->w_out) * stride * sizeof(float)), 256);
     if (need_dHin) bytes += (size_t)round_up(n_nodes * round_up(desc->w_in, 32) * (int64_t)sizeof(float), 256);
     return bytes;
 }
@@ -1656,7 +1671,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
 
     // ---- parameter gradients: per-row-block partial sums, then an fp64 combination ----
     float *partial = static_cast<float *>(ws);
-    const int64_t nb = red_blocks(g->n);
+    const int64_t nb = layer_grad_blocks(g->n, w_in, w_out); // partial sums the workspace has room for
     const int32_t stride = 2 * w_in * w_out + 2 * w_out;
     {
         ProfScope prof(SLICEGCN_PROF_GRAD_REDUCE, w_out, stream);
@@ -1666,6 +1681,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.dHout = dHout; r.ldo = ldo;
         r.mask = mask; r.mask_words = saved->mask_words;
         r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 0;
+        r.rows_per_block = layer_grad_rows(g->n, w_in, w_out);
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
         int64_t n_partials = nb;
         if (use_mfma() && w_in <= 32 && w_out <= 32 && g->n >= 65536) {
@@ -1675,7 +1691,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
             if (waves > n_strips) waves = n_strips;
             n_partials = waves;
             grad_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, waves);
-        } else if (use_mfma() && w_in <= 64 && w_out <= 64 && nb >= 2048 && !getenv("SLICEGCN_NO_STRIP64")) {
+        } else if (use_mfma() && w_in <= 64 && w_out <= 64 && g->n >= ((int64_t)1 << 21) && !getenv("SLICEGCN_NO_STRIP64")) {
             // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
             const int64_t resident = 3072;
             int64_t waves = nb >= resident ? nb / resident * resident : nb >= 2048 ? 2048 : nb;
