@@ -844,7 +844,8 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
     static const bool no_strip64 = getenv("SLICEGCN_NO_STRIP64") != nullptr;
     if (a.K <= 64 && a.Nout <= 64 && a.n >= 262144 && !no_direct && !no_strip64) { // up to 64 wide: strips, weights in LDS
         const int64_t strips = (a.n + 31) / 32;
-        const unsigned gb = (unsigned)((strips + 3) / 4 < 1024 ? (strips + 3) / 4 : 1024);
+        // as many workgroups as the chip holds at once (two per CU): each stages the weights once
+        const unsigned gb = (unsigned)((strips + 3) / 4 < 512 ? (strips + 3) / 4 : 512);
         if (a.K <= 32) launch_strip64<1, 2, BWD>(a, gb, stream);
         else if (a.Nout <= 32) launch_strip64<2, 1, BWD>(a, gb, stream);
         else launch_strip64<2, 2, BWD>(a, gb, stream);
