@@ -248,7 +248,8 @@ def main():
         "epoch_ms": None if args.spmm_only else ms_per_step,
         "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,
         "graph_ms_per_step": graph_ms,
-        "spmm_avg_ms": avg_s * 1e3, "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
+        "spmm_avg_ms": avg_s * 1e3, "spmm_min_ms": kernels.get(f"spmm_w{width}", {}).get("min_ms"),
+        "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "slice aggregation (spmm_wave_items + spmm_group_items + spmm_tiny_rows + spmm_fix kernels of one call)",
                      "algorithmic_bytes_per_launch": nbytes},
