@@ -8,7 +8,8 @@ optimiser step).  Inputs are resident in HBM before the timed region starts.
 
 The headline value is the slice aggregation (SpMM) rate 2*nnz*F_s / t at the slice width
 F_s, with t the average duration of that kernel measured with HIP events inside the timed
-steps; ``ms_per_step`` is the whole fwd+bwd pass.  One JSON line is printed.
+steps (the events themselves are created before the timed region); ``ms_per_step`` is the
+whole fwd+bwd pass.  One JSON line is printed.
 """
 from __future__ import annotations
 
@@ -65,7 +66,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5")
+    ap.add_argument("--workload", default="cfg5",
+                    help="cfg1..cfg5 (the benchmark workloads); comm (planted communities, for --reorder); "
+                         "er:<n>:<m_und> (uniform random graph, one 32-wide slice: gather-rate probe)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frac", type=int, default=1, help="oracle leg uses edges incident to n/frac nodes")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -83,6 +86,12 @@ def main():
     ap.add_argument("--classifier", action="store_true",
                     help="widen the step by the classifier MLP and the cross-entropy loss: the upstream gradient of the "
                          "slice stack then comes from the loss instead of a seeded random matrix")
+    ap.add_argument("--order", choices=("aggregate", "transform", "auto"), default="aggregate",
+                    help="order of the two products of every layer (SLICEGCN_LAYER_*): aggregate first (the layer as stated, "
+                         "default), transform first, or transform first where the layer narrows (w_out < w_in)")
+    ap.add_argument("--reorder", choices=("none", "degree", "bfs"), default="none",
+                    help="row order of the aggregation schedule (SLICEGCN_REORDER_*): by degree, or breadth first "
+                         "(pays off on graphs with communities such as --workload comm, not on R-MAT)")
     ap.add_argument("--vertex-order", choices=("permuted", "generator"), default="permuted",
                     help="'generator' keeps the R-MAT generator's own vertex numbering (low numbers are the hubs) instead "
                          "of the seeded random relabelling: a secondary data point on how much the numbering matters")
@@ -103,7 +112,7 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    w = synth.WORKLOADS[args.workload]
+    w = synth.get_workload(args.workload)
 
     def stream_copy():
         """A plain 4 GiB device copy with the library's copy kernel: the HBM rate this box attains."""
@@ -131,11 +140,13 @@ def main():
     torch.cuda.synchronize()
     log(f"edges in {time.perf_counter() - t0:.1f} s")
     t0 = time.perf_counter()
-    g = sg.slicegcn_build_norm_csr(src, dst, w.n_nodes)
+    build_flags = sg.SYMMETRIZE | sg.ADD_SELF_LOOPS | {"none": 0, "degree": sg.binding.REORDER_DEGREE,
+                                                        "bfs": sg.binding.REORDER_BFS}[args.reorder]
+    g = sg.slicegcn_build_norm_csr(src, dst, w.n_nodes, build_flags)
     torch.cuda.synchronize()
     build_ms = (time.perf_counter() - t0) * 1e3
     view = g.view()
-    assert view.nnz == w.nnz, (view.nnz, w.nnz)
+    assert w.kind == "comm" or view.nnz == w.nnz, (view.nnz, w.nnz)
     log(f"build_norm_csr {build_ms:.1f} ms, nnz={view.nnz}")
 
     slices, width = sg.slicegcn_slice_strategy(w.feat, w.k)
@@ -147,7 +158,8 @@ def main():
         ff.set_params(*model.fusion_params(w, width, device=dev))
         ff.forward(X)
     st = SliceStack(g, n, k, width, hs, L, device=dev, shared_input=ff.Xff if ff is not None else None,
-                    cache_first_aggregation=args.cache_first_agg)
+                    cache_first_aggregation=args.cache_first_agg,
+                    order={"aggregate": 0, "transform": sg.binding.LAYER_TRANSFORM_FIRST, "auto": sg.binding.LAYER_ORDER_AUTO}[args.order])
     for i, (a, b) in enumerate(slices):
         if ff is None:
             sg.slicegcn_slice_feature(X, a, b, st.X[i])
@@ -165,7 +177,7 @@ def main():
     torch.cuda.synchronize()
     log("inputs resident")
 
-    Yspmm = torch.empty_like(st.Z[0][0]) if args.spmm_only else None
+    Yspmm = torch.empty_like(st.X[0]) if args.spmm_only else None
 
     def step():
         if args.spmm_only:
@@ -184,6 +196,11 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # count the kernel groups of one step, then create every event the timed steps will record beforehand
+    sg.slicegcn_profile_begin()
+    step()
+    groups_per_step = sum(e[2] for e in sg.slicegcn_profile_end())
+    sg.slicegcn_profile_reserve((args.steps + 1) * groups_per_step)
     sg.slicegcn_profile_begin()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -209,12 +226,12 @@ def main():
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         log(f"HIP graph replay: {graph_ms:.2f} ms/step")
 
-    kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt, "min_ms": lo, "max_ms": hi}
-               for kind, wd, cnt, tot, lo, hi in prof_full}
+    kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt, "median_ms": med, "min_ms": lo, "max_ms": hi}
+               for kind, wd, cnt, tot, lo, hi, med in prof_full}
     dom = next(((cnt, tot) for kind, wd, cnt, tot in prof if kind == "spmm" and wd == width), None)
     if dom is None and args.cache_first_agg:
         # the cached variant ran no aggregation at the slice width inside the steps: time it on its own
-        Y = torch.empty_like(st.Z[0][0])
+        Y = torch.empty_like(st.X[0])
         sg.slicegcn_profile_begin()
         for j in range(2 * k):
             sg.slicegcn_spmm_slice(g, st.X[j % k][:, :width], Y[:, :width])
@@ -226,13 +243,16 @@ def main():
     avg_s = dom[1] / dom[0] / 1e3
     nbytes = spmm_bytes(n, view.nnz, width)
     achieved = nbytes / avg_s / 1e9
-    traffic = None
-    # HBM-side bytes per aggregation call from the committed rocprofv3 counter summary of this workload
+    traffic = traffic_source = None
+    # HBM-side bytes per aggregation call: NOT measured in this run (counters need rocprofv3); the figure is read
+    # from the committed rocprofv3 --pmc summary of the same workload and launch configuration
     tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_rocprofv3.md")
-    if os.path.exists(tfile) and args.vertex_order == "permuted":
+    if os.path.exists(tfile) and args.vertex_order == "permuted" and args.reorder == "none":
         import re
         m = re.search(r"^hbm_bytes_per_launch = (\d+)", open(tfile).read(), flags=re.M)
         traffic = int(m.group(1)) if m else None
+        traffic_source = (f"profiles/spmm_{w.name}_rocprofv3.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                          "`bench.py --spmm-only`, scaled by a plain copy; a stored figure, not measured in this run)")
     out = {
         "metric": "slice_spmm_gflops", "value": 2.0 * view.nnz * width / avg_s / 1e9, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -240,6 +260,8 @@ def main():
         "config": {"workload": f"{w.name}: N={n}, nnz={view.nnz} (R-MAT, symmetrised + self loops), F={w.feat} in k={k} "
                                f"slices of {width}, {L} layers, per-slice hidden {hs}, full-batch fwd+bwd"
                                + (" [generator's vertex numbering, hubs first]" if args.vertex_order != "permuted" else "")
+                               + (f" [rows visited in {args.reorder} order]" if args.reorder != "none" else "")
+                               + (f" [layer order: {args.order}]" if args.order != "aggregate" else "")
                                + (" [aggregation only]" if args.spmm_only else "")
                                + (" [first-layer aggregation cached across steps]" if args.cache_first_agg and ff is None else "")
                                + (f" + feature fusion {w.feat}->{w.feat}->{width}" if ff is not None else "")
@@ -248,10 +270,11 @@ def main():
         "epoch_ms": None if args.spmm_only else ms_per_step,
         "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,
         "graph_ms_per_step": graph_ms,
-        "spmm_avg_ms": avg_s * 1e3, "spmm_min_ms": kernels.get(f"spmm_w{width}", {}).get("min_ms"),
+        "spmm_avg_ms": avg_s * 1e3, "spmm_median_ms": kernels.get(f"spmm_w{width}", {}).get("median_ms"),
+        "spmm_min_ms": kernels.get(f"spmm_w{width}", {}).get("min_ms"),
         "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "slice aggregation (spmm_wave_items + spmm_group_items + spmm_tiny_rows + spmm_fix kernels of one call)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source, "kernel": "slice aggregation (spmm_wave_items + spmm_group_items + spmm_tiny_rows + spmm_fix kernels of one call)",
                      "algorithmic_bytes_per_launch": nbytes},
         "kernels": kernels,
     }

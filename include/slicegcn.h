@@ -18,9 +18,15 @@
  *    are asynchronous with respect to the host and ordered on that stream, except
  *    slicegcn_build_norm_csr, which synchronises the stream before returning.
  *  - Ownership: the caller owns every tensor, workspace and edge-list buffer.  The library
- *    owns only what a slicegcn_graph handle holds (the CSR arrays), from
- *    slicegcn_build_norm_csr until slicegcn_graph_destroy.  Apart from building a graph,
- *    no call allocates or frees device memory.
+ *    owns only what a slicegcn_graph handle holds (the CSR arrays and the row schedule derived
+ *    from them), from slicegcn_build_norm_csr until slicegcn_graph_destroy.  Apart from
+ *    building a graph, no call allocates or frees device memory.
+ *  - A handle is read-only after it has been built: any number of calls may use one handle at
+ *    the same time from different streams or host threads, as long as each call has its own
+ *    workspace and output buffers.  Workspaces (`ws`, `ws_bytes`) are scratch: 256-byte aligned,
+ *    at least the size the matching *_workspace_bytes query returns, contents undefined before
+ *    and after a call; `ws` may be NULL when that size is 0.  Two calls that share a workspace
+ *    must be ordered on one stream.
  *  - Results are deterministic: kernels use no floating-point atomics, so two calls on the
  *    same inputs give bitwise equal outputs.
  */
@@ -45,6 +51,24 @@ extern "C" {
 /* flags of slicegcn_build_norm_csr */
 #define SLICEGCN_SYMMETRIZE 1u     /* store A | A^T (undirected graph)                      */
 #define SLICEGCN_ADD_SELF_LOOPS 2u /* add exactly one diagonal entry per row (A + I)        */
+/* Locality preprocessing (optional; the paper fixes no execution order): the aggregation visits the rows
+ * in the order below instead of by ascending id, so that rows visited together gather the same rows and
+ * find them in cache.  Inputs and outputs of every call stay in the caller's numbering, the CSR arrays of
+ * slicegcn_graph_view are unchanged, and results differ from the natural order by rounding at most (the
+ * sum of a row is formed in the same order).  The chosen order is slicegcn_csr_view.order.
+ *   REORDER_DEGREE: rows by descending number of stored entries, ties by ascending id.
+ *   REORDER_BFS   : at most 16 times, the not yet placed row that comes first in the degree order becomes a
+ *                   root, and the rows reachable from it (along stored entries of A^) are placed in the order a
+ *                   first-in-first-out queue visits them, the neighbours of a row in ascending id; rows
+ *                   still unplaced follow in degree order.  Graphs whose vertices were numbered without
+ *                   regard to their communities gain from this; a random graph does not. */
+#define SLICEGCN_REORDER_DEGREE 4u
+#define SLICEGCN_REORDER_BFS 8u
+/* schedule tuning (optional, results are unaffected): by default rows of up to 32 stored entries are
+ * served by 8-lane groups when the whole graph stays in the last-level cache and rows of up to 64
+ * otherwise; these two flags force one of the limits */
+#define SLICEGCN_SCHED_SHORT_ITEMS 16u
+#define SLICEGCN_SCHED_LONG_ITEMS 32u
 
 /* activation of slicegcn_layer_desc.act */
 #define SLICEGCN_ACT_NONE 0
@@ -62,10 +86,21 @@ typedef struct {
     const float *dinv;     /* [n_nodes] 1/sqrt(max(d~_v, 1))                  */
     const float *vals;     /* [nnz] dinv[row] * dinv[col]                     */
     int32_t symmetric;     /* 1 when the pattern was symmetrised              */
+    const int32_t *order;  /* [n_nodes] row visited at each position, or NULL (ascending id) */
 } slicegcn_csr_view;
 
 /* flags of slicegcn_layer_desc.flags */
 #define SLICEGCN_LAYER_Z_VALID 1u /* forward only: saved->Z already holds A^ Hin, skip the aggregation */
+/* Order of the two products of the layer equation's aggregation term.  (A^ Hin) W_agg and A^ (Hin W_agg) are equal
+ * in exact arithmetic (results differ by rounding only); the default aggregates first, as the layer is stated.
+ * TRANSFORM_FIRST multiplies by W_agg first, so the aggregation gathers rows of w_out instead of w_in columns, in
+ * the forward and in the backward pass; ORDER_AUTO picks it when w_out < w_in.  The transform-first order keeps
+ * nothing but the activation mask for the backward pass (saved->Z is neither written nor read and may be NULL),
+ * and its backward pass always runs one aggregation (of dP, w_out wide), where the default order runs one of
+ * w_in columns only when dHin is wanted.  Pass the same flags to slicegcn_layer_fwd, slicegcn_layer_bwd and the
+ * workspace queries of a layer. */
+#define SLICEGCN_LAYER_TRANSFORM_FIRST 2u
+#define SLICEGCN_LAYER_ORDER_AUTO 4u
 
 typedef struct {
     int32_t w_in;   /* width of the layer input  (columns of Hin, rows of W)    */
@@ -85,7 +120,9 @@ typedef struct {
 
 /* What the forward pass keeps for the backward pass (caller-owned buffers).
  * Z    : n x w_in aggregation result A^ Hin, leading dimension ldz (>= w_in, multiple of 4,
- *        16-byte aligned base).
+ *        16-byte aligned base).  It doubles as the staging buffer of the forward aggregation, so it is
+ *        required in the default (aggregate-first) order; there is no "recompute in backward" mode.  Unused
+ *        (may be NULL) in the transform-first order.
  * mask : n x mask_words uint32; bit (j % 32) of word (j / 32) of row v is 1 where the
  *        pre-activation P[v, j] > 0.  mask_words >= ceil(w_out / 32).  For ACT_NONE the
  *        mask is neither written nor read and may be NULL. */
@@ -123,8 +160,13 @@ int slicegcn_slice_strategy(int32_t in_d, int32_t p, double slice_size_scale,
  * d~_v the number of stored entries of row v.  Input self pairs are dropped and repeats
  * collapsed, so the diagonal is exactly 1 entry when ADD_SELF_LOOPS is set.
  * On success *out holds a new handle (free it with slicegcn_graph_destroy).  Allocates device
- * memory, synchronises `stream`.  rowptr/colidx/deg are exact integers; dinv/vals are fp32.
- * EINVAL: NULL out, n_nodes < 1, n_edges < 0, NULL src/dst with n_edges > 0, unknown flag.
+ * memory (the handle's arrays plus temporaries of a few times the edge list, freed before it
+ * returns) and synchronises `stream` several times: it runs once per graph, not per epoch.
+ * Sorting, duplicate removal and prefix sums are rocPRIM device primitives; the kernels around
+ * them are this library's.  rowptr/colidx/deg are exact integers; dinv/vals are fp32 and always
+ * kept (there is no flag to drop vals: every aggregation path reads them).
+ * EINVAL: NULL out, n_nodes < 1, n_edges < 0, NULL src/dst with n_edges > 0, unknown flag, both
+ *         REORDER flags or both SCHED flags.
  * ERANGE: n_nodes > 2^31-1, more than 2^31-1 stored entries, or a node id outside [0, n_nodes).
  * ------------------------------------------------------------------------------------- */
 int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, int64_t n_edges,
@@ -151,10 +193,15 @@ int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, int32_t start
  * to 4 (padding columns are read but never used); other layouts take a scalar path.  Only
  * columns [0, width) of Y are written.  A symmetrised graph serves transpose != 0 with the
  * same arrays; otherwise the handle holds the transposed pattern as well.
- * EINVAL: NULL pointer, width < 1, ldx < width, ldy < width.
+ * ws: rows cut into several work items (long rows, see the schedule notes of the library) keep
+ * per-item partial sums there; slicegcn_spmm_workspace_bytes gives the size for this graph,
+ * direction and width (0 for graphs without such rows).
+ * EINVAL: NULL pointer, width < 1, ldx < width, ldy < width, misaligned ws;
+ * EWORKSPACE: ws NULL or too small.
  * ------------------------------------------------------------------------------------- */
+size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int transpose, int32_t width);
 int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
-                        int32_t width, float *Y, int64_t ldy, void *stream);
+                        int32_t width, float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * One layer of one slice, forward (the SliceGCN layer equation as typeset, self term outside
@@ -167,17 +214,21 @@ int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, 
  * With SLICEGCN_LAYER_Z_VALID the caller vouches that saved->Z still holds A^ Hin from an earlier
  * call with the same graph and Hin (the first layer over raw, constant features is the same in
  * every epoch); the aggregation is then skipped.  The paper's own implementation recomputes it.
- * No workspace is needed.
+ * ws: at least slicegcn_layer_fwd_workspace_bytes(g, desc) bytes (the aggregation's workspace; in the
+ * transform-first order also the staged Hin W_agg and its aggregation).
  * EINVAL: NULL Hin/Hout/W_agg/saved->Z, widths < 1, ld too small, ldz not a multiple of 4,
- *         mask NULL or mask_words too small with ACT_RELU, unknown act or flag.
+ *         mask NULL or mask_words too small with ACT_RELU, unknown act or flag, misaligned ws;
+ * EWORKSPACE: ws NULL or too small.
  * ------------------------------------------------------------------------------------- */
+size_t slicegcn_layer_fwd_workspace_bytes(const slicegcn_graph *g, const slicegcn_layer_desc *desc);
 int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
                        const slicegcn_layer_params *params, const float *Hin, int64_t ldi,
-                       float *Hout, int64_t ldo, slicegcn_layer_saved *saved, void *stream);
+                       float *Hout, int64_t ldo, slicegcn_layer_saved *saved,
+                       void *ws, size_t ws_bytes, void *stream);
 
-/* Bytes of workspace slicegcn_layer_bwd needs for this graph size and layer (0 on bad input).
+/* Bytes of workspace slicegcn_layer_bwd needs for this graph and layer (0 on bad input).
  * need_dHin = 0 when the input gradient is not wanted (first layer over raw features). */
-size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slicegcn_layer_desc *desc, int need_dHin);
+size_t slicegcn_layer_bwd_workspace_bytes(const slicegcn_graph *g, const slicegcn_layer_desc *desc, int need_dHin);
 
 /* ---------------------------------------------------------------------------------------
  * One layer of one slice, backward (chain rule of the forward above; ReLU'(0) = 0):
@@ -186,8 +237,9 @@ size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slicegcn_layer_
  *   dHin = A^^T (dP W_agg^T) + dHout W_self^T         (skipped when dHin == NULL).
  * saved holds Z and mask exactly as slicegcn_layer_fwd wrote them (read only here).
  * Reductions over the nodes run in fp32 over short row blocks and are combined in fp64 in a
- * fixed order.  ws: workspace of at least slicegcn_layer_bwd_workspace_bytes bytes, 256-byte
- * aligned; its contents are scratch.
+ * fixed order.  ws: at least slicegcn_layer_bwd_workspace_bytes bytes (partial weight gradients,
+ * the staged dZ = dP W_agg^T and the aggregation's workspace).  In the transform-first order the pass reads
+ * G = A^^T dP instead of Z: dW_agg = Hin^T G, dHin = G W_agg^T + dHout W_self^T.
  * EINVAL as for the forward; EWORKSPACE when ws is NULL or ws_bytes too small.
  * ------------------------------------------------------------------------------------- */
 int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
@@ -313,7 +365,11 @@ typedef struct {
     double total_ms;
     double min_ms; /* shortest and longest single launch group of this (kind, width) */
     double max_ms;
+    double median_ms;
 } slicegcn_profile_entry;
+/* Creates the events of `scopes` kernel groups ahead of time, so that a profiled region that launches at
+ * most that many groups creates none itself (events are reused from one profiled region to the next). */
+int slicegcn_profile_reserve(int32_t scopes);
 int slicegcn_profile_begin(void);
 int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t capacity, int32_t *count);
 

@@ -15,7 +15,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "slicegcn_oracle.c")
-_LIB = os.path.join(_HERE, "libslicegcn_oracle.so")
+# SLICEGCN_SANITIZE=1 (with the AddressSanitizer runtime preloaded into the interpreter) runs the tests against
+# a build of the same source with -fsanitize=address,undefined
+_SANITIZE = os.environ.get("SLICEGCN_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libslicegcn_oracle_san.so" if _SANITIZE else "libslicegcn_oracle.so")
 
 SYMMETRIZE = 1
 ADD_SELF_LOOPS = 2
@@ -25,7 +28,8 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (idempotent unless ``force``)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *opt, "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                                "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -109,6 +113,19 @@ def build_norm_csr(src, dst, n_nodes: int, flags: int = SYMMETRIZE | ADD_SELF_LO
         L.oracle_free(ctypes.cast(col_p, ctypes.c_void_p))
         L.oracle_free(ctypes.cast(val_p, ctypes.c_void_p))
     return NormCSR(n_nodes, rowptr, colidx, deg[:n_nodes], dinv[:n_nodes], vals)
+
+
+ORDER_DEGREE, ORDER_BFS = 1, 2
+BFS_MAX_TREES = 16
+
+
+def row_order(g: NormCSR, mode: int, max_trees: int = BFS_MAX_TREES) -> np.ndarray:
+    """Processing order of the rows (ORDER_DEGREE or ORDER_BFS): order[p] = id of the row at position p."""
+    order = np.empty(g.n, dtype=np.int32)
+    rc = lib().oracle_row_order(ctypes.c_int64(g.n), _p(g.rowptr, ctypes.c_int64), _p(g.colidx, ctypes.c_int32),
+                                ctypes.c_int(mode), ctypes.c_int32(max_trees), _p(order, ctypes.c_int32))
+    _check(rc, "row_order")
+    return order
 
 
 def _csr_args(g: NormCSR):

@@ -15,7 +15,8 @@
  * Pins (see tests/test_oracle_*.py): dense brute force on tiny graphs, closed-form graphs
  * (empty, complete, ring, star), the fixed-point invariant of the normalised adjacency,
  * the slice/concat identity, adjoint identities, finite differences, and library
- * cross-checks (tests/test_oracle_classifier.py for the dense layer and the loss).  No function
+ * cross-checks (tests/test_oracle_classifier.py for the dense layer and the loss; tests/test_oracle_order.py
+ * for the row orders: hand examples, queue invariants, scipy's breadth-first order).  No function
  * here is "parity unpinned".
  */
 #include <math.h>
@@ -154,6 +155,64 @@ int oracle_build_norm_csr(const int64_t *src, const int64_t *dst, int64_t n_edge
 }
 
 void oracle_free(void *p) { free(p); }
+
+/* ------------------------------------------------------------------------------------
+ * Row processing order (the library's optional locality preprocessing; the paper fixes no
+ * execution order, so this is defined here, uniquely, and the library must reproduce it):
+ *   mode 1, by degree: rows by descending number of stored entries, ties by ascending id;
+ *   mode 2, breadth first: at most `max_trees` times, take the not yet placed row that comes
+ *     first in the degree order as a root and place the rows reachable from it in the order
+ *     a first-in-first-out queue visits them, the neighbours of a row in ascending id; rows
+ *     still unplaced after that follow in degree order.
+ * order[p] = id of the row at position p.
+ * ---------------------------------------------------------------------------------- */
+typedef struct { int32_t deg; int32_t id; } deg_id;
+
+static int cmp_deg_desc(const void *a, const void *b)
+{
+    const deg_id *x = (const deg_id *)a, *y = (const deg_id *)b;
+    if (x->deg != y->deg) return x->deg > y->deg ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+int oracle_row_order(int64_t n, const int64_t *rowptr, const int32_t *colidx, int mode, int32_t max_trees,
+                     int32_t *order)
+{
+    if (n < 1 || !rowptr || !order || (mode != 1 && mode != 2)) return ORACLE_EINVAL;
+    deg_id *by_deg = (deg_id *)malloc((size_t)n * sizeof(deg_id));
+    if (!by_deg) return ORACLE_ENOMEM;
+    for (int64_t v = 0; v < n; ++v) {
+        by_deg[v].deg = (int32_t)(rowptr[v + 1] - rowptr[v]);
+        by_deg[v].id = (int32_t)v;
+    }
+    qsort(by_deg, (size_t)n, sizeof(deg_id), cmp_deg_desc);
+    if (mode == 1) {
+        for (int64_t p = 0; p < n; ++p) order[p] = by_deg[p].id;
+        free(by_deg);
+        return ORACLE_OK;
+    }
+    unsigned char *placed = (unsigned char *)calloc((size_t)n, 1);
+    if (!placed) { free(by_deg); return ORACLE_ENOMEM; }
+    int64_t count = 0, cursor = 0;
+    for (int32_t tree = 0; tree < max_trees && count < n; ++tree) {
+        while (placed[by_deg[cursor].id]) ++cursor;
+        int64_t head = count;                 /* the queue is order[head .. count) */
+        order[count++] = by_deg[cursor].id;
+        placed[by_deg[cursor].id] = 1;
+        while (head < count) {
+            const int32_t v = order[head++];
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {   /* columns ascend within a row */
+                const int32_t u = colidx[e];
+                if (!placed[u]) { placed[u] = 1; order[count++] = u; }
+            }
+        }
+    }
+    for (int64_t p = 0; p < n && count < n; ++p)
+        if (!placed[by_deg[p].id]) order[count++] = by_deg[p].id;
+    free(placed);
+    free(by_deg);
+    return ORACLE_OK;
+}
 
 /* ------------------------------------------------------------------------------------
  * Sparse aggregation: the inner sum of the SliceGCN layer equation,

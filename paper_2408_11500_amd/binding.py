@@ -15,21 +15,29 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libslicegcn.so")
+# SLICEGCN_SANITIZE=1 selects the build whose host code carries sanitizer checks (CPU-only test runs)
+LIB_PATH = os.path.join(_PKG, "libslicegcn_hostsan.so" if os.environ.get("SLICEGCN_SANITIZE") == "1" else "libslicegcn.so")
 
 SYMMETRIZE = 1
 ADD_SELF_LOOPS = 2
+REORDER_DEGREE = 4
+REORDER_BFS = 8
+SCHED_SHORT_ITEMS = 16
+SCHED_LONG_ITEMS = 32
 ACT_NONE = 0
 ACT_RELU = 1
 LAYER_Z_VALID = 1
+LAYER_TRANSFORM_FIRST = 2
+LAYER_ORDER_AUTO = 4
 
 OK, EINVAL, ERANGE, ENOMEM, EHIP, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "slicegcn_slice_strategy", "slicegcn_build_norm_csr", "slicegcn_graph_view", "slicegcn_graph_destroy",
-    "slicegcn_slice_feature", "slicegcn_spmm_slice", "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
+    "slicegcn_slice_feature", "slicegcn_spmm_workspace_bytes", "slicegcn_spmm_slice", "slicegcn_layer_fwd_workspace_bytes",
+    "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
-    "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_begin", "slicegcn_profile_end",
+    "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_reserve", "slicegcn_profile_begin", "slicegcn_profile_end",
     "slicegcn_linear_fwd", "slicegcn_linear_bwd_workspace_bytes", "slicegcn_linear_bwd",
     "slicegcn_softmax_ce_workspace_bytes", "slicegcn_softmax_ce", "slicegcn_accumulate",
     "slicegcn_adam_step", "slicegcn_cosine_lr",
@@ -48,7 +56,7 @@ class SliceGCNError(RuntimeError):
 class _CsrView(ctypes.Structure):
     _fields_ = [("n_nodes", ctypes.c_int64), ("nnz", ctypes.c_int64), ("rowptr", ctypes.c_void_p),
                 ("colidx", ctypes.c_void_p), ("deg", ctypes.c_void_p), ("dinv", ctypes.c_void_p),
-                ("vals", ctypes.c_void_p), ("symmetric", ctypes.c_int32)]
+                ("vals", ctypes.c_void_p), ("symmetric", ctypes.c_int32), ("order", ctypes.c_void_p)]
 
 
 class _LayerDesc(ctypes.Structure):
@@ -65,7 +73,8 @@ class _LayerSaved(ctypes.Structure):
 
 class _ProfileEntry(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("width", ctypes.c_int32), ("launches", ctypes.c_int64),
-                ("total_ms", ctypes.c_double), ("min_ms", ctypes.c_double), ("max_ms", ctypes.c_double)]
+                ("total_ms", ctypes.c_double), ("min_ms", ctypes.c_double), ("max_ms", ctypes.c_double),
+                ("median_ms", ctypes.c_double)]
 
 
 class _LayerGrads(ctypes.Structure):
@@ -89,10 +98,14 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_graph_view.argtypes = [vp, ctypes.POINTER(_CsrView)]
         L.slicegcn_graph_destroy.argtypes = [vp]
         L.slicegcn_slice_feature.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp]
-        L.slicegcn_spmm_slice.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp]
+        L.slicegcn_spmm_workspace_bytes.argtypes = [vp, ctypes.c_int, i32]
+        L.slicegcn_spmm_workspace_bytes.restype = sz
+        L.slicegcn_spmm_slice.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp, sz, vp]
+        L.slicegcn_layer_fwd_workspace_bytes.argtypes = [vp, ctypes.POINTER(_LayerDesc)]
+        L.slicegcn_layer_fwd_workspace_bytes.restype = sz
         L.slicegcn_layer_fwd.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.POINTER(_LayerParams), vp, i64, vp, i64,
-                                         ctypes.POINTER(_LayerSaved), vp]
-        L.slicegcn_layer_bwd_workspace_bytes.argtypes = [i64, ctypes.POINTER(_LayerDesc), ctypes.c_int]
+                                         ctypes.POINTER(_LayerSaved), vp, sz, vp]
+        L.slicegcn_layer_bwd_workspace_bytes.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.c_int]
         L.slicegcn_layer_bwd_workspace_bytes.restype = sz
         L.slicegcn_layer_bwd.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.POINTER(_LayerParams), vp, i64,
                                          ctypes.POINTER(_LayerSaved), vp, i64, vp, i64, ctypes.POINTER(_LayerGrads),
@@ -147,6 +160,10 @@ def _vec(t, name: str, dtype=torch.float32):
     return t.data_ptr()
 
 
+def _ws(ws):
+    return (ws.data_ptr(), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
 # ---------------------------------------------------------------------------------------
 def slicegcn_slice_strategy(in_d: int, p: int, slice_size_scale: float = 1.0):
     """Host call: returns ([(start, end)] * p, slice_size)."""
@@ -169,13 +186,24 @@ class CsrView:
     dinv: int
     vals: int
     symmetric: int
+    order: int = 0
 
 
 class Graph:
-    """Owner of a ``slicegcn_graph`` handle."""
+    """Owner of a ``slicegcn_graph`` handle.  The handle itself is read-only; ``default_ws`` hands out one
+    cached device buffer for callers that pass no workspace of their own (such calls must then be ordered
+    on one stream; callers that overlap calls on several streams pass one workspace per stream)."""
 
     def __init__(self, handle: int):
         self._h = handle
+        self._ws = None
+
+    def default_ws(self, nbytes: int):
+        if nbytes == 0:
+            return None
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        return self._ws
 
     @property
     def handle(self) -> int:
@@ -186,7 +214,8 @@ class Graph:
     def view(self) -> CsrView:
         v = _CsrView()
         _check(lib().slicegcn_graph_view(self.handle, ctypes.byref(v)))
-        return CsrView(v.n_nodes, v.nnz, v.rowptr or 0, v.colidx or 0, v.deg or 0, v.dinv or 0, v.vals or 0, v.symmetric)
+        return CsrView(v.n_nodes, v.nnz, v.rowptr or 0, v.colidx or 0, v.deg or 0, v.dinv or 0, v.vals or 0, v.symmetric,
+                       v.order or 0)
 
     def to_host(self) -> dict:
         """Copies of the CSR arrays as numpy arrays (for checks)."""
@@ -194,12 +223,14 @@ class Graph:
         return dict(n=v.n_nodes, nnz=v.nnz,
                     rowptr=_to_host(v.rowptr, v.n_nodes + 1, np.int32), colidx=_to_host(v.colidx, v.nnz, np.int32),
                     deg=_to_host(v.deg, v.n_nodes, np.int32), dinv=_to_host(v.dinv, v.n_nodes, np.float32),
-                    vals=_to_host(v.vals, v.nnz, np.float32))
+                    vals=_to_host(v.vals, v.nnz, np.float32),
+                    order=_to_host(v.order, v.n_nodes, np.int32) if v.order else None)
 
     def destroy(self):
         if self._h:
             lib().slicegcn_graph_destroy(self._h)
             self._h = 0
+            self._ws = None
 
     def __del__(self):
         try:
@@ -247,13 +278,22 @@ def slicegcn_slice_feature(X: torch.Tensor, start: int, end: int, Xs: torch.Tens
     return Xs
 
 
-def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False):
+def slicegcn_spmm_workspace_bytes(g: Graph, width: int, transpose: bool = False) -> int:
+    return int(lib().slicegcn_spmm_workspace_bytes(g.handle, int(transpose), width))
+
+
+def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False,
+                        ws: torch.Tensor | None = None):
+    """``ws``: uint8 device tensor of slicegcn_spmm_workspace_bytes bytes; None = the graph object's cached buffer."""
     px, ldx = _mat(X, "X")
     py, ldy = _mat(Y, "Y")
     if X.shape[0] != Y.shape[0]:
         raise ValueError("X and Y differ in rows")
     w = int(X.shape[1] if width is None else width)
-    _check(lib().slicegcn_spmm_slice(g.handle, int(transpose), px, ldx, w, py, ldy, _stream()))
+    if ws is None and w >= 1:
+        ws = g.default_ws(slicegcn_spmm_workspace_bytes(g, w, transpose))
+    pws, nws = _ws(ws)
+    _check(lib().slicegcn_spmm_slice(g.handle, int(transpose), px, ldx, w, py, ldy, pws, nws, _stream()))
     return Y
 
 
@@ -266,39 +306,51 @@ def _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, flags=0):
     return desc, params
 
 
-def _saved_struct(Z: torch.Tensor, mask):
-    pz, ldz = _mat(Z, "Z")
+def _saved_struct(Z, mask):
+    pz, ldz = _mat(Z, "Z") if Z is not None else (None, 0)
     if mask is None:
         return _LayerSaved(pz, ldz, None, 0)
     pm, ldm = _mat(mask, "mask", torch.int32)
     return _LayerSaved(pz, ldz, pm, ldm)
 
 
+def slicegcn_layer_fwd_workspace_bytes(g: Graph, w_in: int, w_out: int, flags: int = 0) -> int:
+    desc = _LayerDesc(w_in, w_out, ACT_RELU, flags)
+    return int(lib().slicegcn_layer_fwd_workspace_bytes(g.handle, ctypes.byref(desc)))
+
+
 def slicegcn_layer_fwd(g: Graph, Hin, W_agg, b, W_self, b_self, Hout, Z, mask, act: int = ACT_RELU,
-                       w_in: int | None = None, w_out: int | None = None, z_valid: bool = False):
+                       w_in: int | None = None, w_out: int | None = None, z_valid: bool = False,
+                       ws: torch.Tensor | None = None, order: int = 0):
     """Hout = act(A^ Hin W_agg + b) + Hin W_self + b_self; fills Z (and mask for ReLU).
-    ``z_valid``: Z already holds A^ Hin (same graph and Hin as an earlier call): skip the aggregation."""
+    ``z_valid``: Z already holds A^ Hin (same graph and Hin as an earlier call): skip the aggregation.
+    ``ws``: uint8 device tensor of slicegcn_layer_fwd_workspace_bytes bytes; None = the graph object's cached buffer.
+    ``order``: 0, LAYER_TRANSFORM_FIRST or LAYER_ORDER_AUTO (then Z may be None when the transform-first order runs)."""
     w_in = int(W_agg.shape[0] if w_in is None else w_in)
     w_out = int(W_agg.shape[1] if w_out is None else w_out)
-    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, LAYER_Z_VALID if z_valid else 0)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, (LAYER_Z_VALID if z_valid else 0) | order)
     pi, ldi = _mat(Hin, "Hin")
     po, ldo = _mat(Hout, "Hout")
     saved = _saved_struct(Z, mask)
+    if ws is None:
+        ws = g.default_ws(int(lib().slicegcn_layer_fwd_workspace_bytes(g.handle, ctypes.byref(desc))))
+    pws, nws = _ws(ws)
     _check(lib().slicegcn_layer_fwd(g.handle, ctypes.byref(desc), ctypes.byref(params), pi, ldi, po, ldo,
-                                    ctypes.byref(saved), _stream()))
+                                    ctypes.byref(saved), pws, nws, _stream()))
     return Hout
 
 
-def slicegcn_layer_bwd_workspace_bytes(n_nodes: int, w_in: int, w_out: int, need_dHin: bool) -> int:
-    desc = _LayerDesc(w_in, w_out, ACT_RELU, 0)
-    return int(lib().slicegcn_layer_bwd_workspace_bytes(n_nodes, ctypes.byref(desc), int(need_dHin)))
+def slicegcn_layer_bwd_workspace_bytes(g: Graph, w_in: int, w_out: int, need_dHin: bool, flags: int = 0) -> int:
+    desc = _LayerDesc(w_in, w_out, ACT_RELU, flags)
+    return int(lib().slicegcn_layer_bwd_workspace_bytes(g.handle, ctypes.byref(desc), int(need_dHin)))
 
 
 def slicegcn_layer_bwd(g: Graph, Hin, W_agg, W_self, Z, mask, dHout, dHin, dW_agg, db, dW_self, db_self, ws,
-                       act: int = ACT_RELU):
-    """Gradients of one layer.  ``dHin`` may be None (skipped).  ``ws`` is a uint8 workspace tensor."""
+                       act: int = ACT_RELU, order: int = 0):
+    """Gradients of one layer.  ``dHin`` may be None (skipped).  ``ws`` is a uint8 workspace tensor.
+    ``order``: the same order flag the forward call was given."""
     w_in, w_out = int(W_agg.shape[0]), int(W_agg.shape[1])
-    desc, params = _layer_structs(w_in, w_out, act, W_agg, None, W_self, None)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, None, W_self, None, order)
     pi, ldi = _mat(Hin, "Hin")
     pg, ldo = _mat(dHout, "dHout")
     pgi, ldgi = _mat(dHin, "dHin") if dHin is not None else (None, 0)
@@ -350,10 +402,6 @@ def slicegcn_concat_bwd(dH: torch.Tensor, widths, dHs=None, dE=None, ws=None):
                                      ctypes.addressof(lds) if lds is not None else None, pe, lde,
                                      ws.data_ptr() if ws is not None else None,
                                      ws.numel() * ws.element_size() if ws is not None else 0, _stream()))
-
-
-def _ws(ws):
-    return (ws.data_ptr(), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
 
 
 def slicegcn_linear_fwd(X, W, b, Y, mask=None, act: int = ACT_NONE):
@@ -427,16 +475,21 @@ def slicegcn_softmax_ce(logits, labels, loss, dlogits, ws):
     return loss
 
 
+def slicegcn_profile_reserve(scopes: int):
+    """Create the events of ``scopes`` kernel groups ahead of a profiled region."""
+    _check(lib().slicegcn_profile_reserve(int(scopes)))
+
+
 def slicegcn_profile_begin():
     _check(lib().slicegcn_profile_begin())
 
 
 def slicegcn_profile_end(capacity: int = 64, with_range: bool = False):
     """[(kind name, width, launches, total_ms)] of the kernels launched since profile_begin;
-    with_range appends (min_ms, max_ms) of a single launch group."""
+    with_range appends (min_ms, max_ms, median_ms) of a single launch group."""
     arr = (_ProfileEntry * capacity)()
     count = ctypes.c_int32(0)
     _check(lib().slicegcn_profile_end(arr, capacity, ctypes.byref(count)))
     return [(PROF_KINDS.get(e.kind, str(e.kind)), int(e.width), int(e.launches), float(e.total_ms))
-            + ((float(e.min_ms), float(e.max_ms)) if with_range else ())
+            + ((float(e.min_ms), float(e.max_ms), float(e.median_ms)) if with_range else ())
             for e in arr[:min(count.value, capacity)]]

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libslicegcn.so")
-SOURCES = ["build_csr.hip", "spmm.hip", "dense.hip", "misc.hip", "loss.hip"]
+SOURCES = ["build_csr.hip", "order.hip", "spmm.hip", "dense.hip", "misc.hip", "loss.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions stay off for every kernel in this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,9 +30,17 @@ def _hipcc() -> str:
     return exe
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+# host code only: the device code is compiled as always (sanitizers do not run on the GPU here)
+# (the checks clang's own runtime alone provides are left out: the tests preload gcc's sanitizer runtimes, which the
+# oracle's sanitized build shares)
+SANITIZE_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize=function",
+                 "-Xarch_host", "-fno-sanitize=vptr", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+LIB_SANITIZED = os.path.join(PKG, "libslicegcn_hostsan.so")
+
+
+def _compile(src: str, sanitize_host: bool = False) -> str:
+    obj = os.path.join(OBJ, src.replace(".hip", ".san.o" if sanitize_host else ".o"))
+    cmd = [_hipcc(), *FLAGS, *(SANITIZE_HOST if sanitize_host else []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}")
@@ -43,21 +51,25 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every source and link the shared library.  Always rebuilds."""
+def build(verbose: bool = True, sanitize_host: bool = False) -> str:
+    """Compile every source and link the shared library.  Always rebuilds.  ``sanitize_host`` builds a second
+    library whose host code carries AddressSanitizer / UndefinedBehaviorSanitizer checks (for the CPU-only tests
+    of argument validation; load it with SLICEGCN_SANITIZE=1 and the sanitizer runtime preloaded)."""
     os.makedirs(OBJ, exist_ok=True)
+    lib = LIB_SANITIZED if sanitize_host else LIB
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
+        objs = list(pool.map(lambda s: _compile(s, sanitize_host), SOURCES))
+    tmp = lib + f".tmp{os.getpid()}"
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *(["-Wl,--allow-shlib-undefined"] if sanitize_host else []),  # the sanitizer runtime comes from the preloaded libraries
+           "-o", tmp, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}")
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {lib}")
+    return lib
 
 
 if __name__ == "__main__":
-    build()
+    build(sanitize_host="--sanitize-host" in sys.argv[1:])

@@ -193,31 +193,38 @@ __device__ inline int for_each_item(const int32_t *__restrict__ colidx, int32_t 
     return total;
 }
 
+// Thread p handles the row at position p of the schedule (order[p], or p itself in natural order); all
+// per-row tables are indexed by position, so the scans below lay the items out in schedule order.
 __global__ void sched_count_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
+                                   const int32_t *__restrict__ order,
                                    int n_classes, const ClassBounds cb, int32_t part_row, int32_t item_max, int32_t *__restrict__ cnt,
                                    int32_t *__restrict__ c_slot, int32_t *__restrict__ c_fix)
 {
-    const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (r > n) return;
+    const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (p > n) return;
     const int64_t stride = n + 1;
     int32_t per[MAX_TABLES];
     for (int t = 0; t < MAX_TABLES; ++t) per[t] = 0;
     int total = 0;
-    if (r < n)
+    if (p < n) {
+        const int64_t r = order ? order[p] : p;
         total = for_each_item(colidx, rowptr[r], rowptr[r + 1], n_classes, cb, part_row, item_max,
                               [&](int t, int32_t, int32_t) { per[t] += 1; });
-    for (int t = 0; t < 2 * n_classes + 2; ++t) cnt[t * stride + r] = per[t];
-    c_slot[r] = total > 1 ? total : 0;
-    c_fix[r] = total > 1 ? 1 : 0;
+    }
+    for (int t = 0; t < 2 * n_classes + 2; ++t) cnt[t * stride + p] = per[t];
+    c_slot[p] = total > 1 ? total : 0;
+    c_fix[p] = total > 1 ? 1 : 0;
 }
 
 __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, int64_t n,
+                                  const int32_t *__restrict__ order,
                                   int n_classes, const ClassBounds cb, int32_t part_row, int32_t item_max, const int32_t *__restrict__ off,
                                   const int32_t *__restrict__ o_slot, const int32_t *__restrict__ o_fix,
                                   Segment *__restrict__ items, FixRow *__restrict__ fix)
 {
-    const int64_t r = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (r >= n) return;
+    const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (p >= n) return;
+    const int64_t r = order ? order[p] : p;
     const int64_t stride = n + 1;
     const int32_t beg = rowptr[r], end = rowptr[r + 1];
     if (end - beg <= TINY_ROW) return;
@@ -225,24 +232,24 @@ __global__ void sched_fill_kernel(const int32_t *__restrict__ rowptr, const int3
     const int total = for_each_item(colidx, beg, end, n_classes, cb, part_row, item_max, [](int, int32_t, int32_t) {});
     int32_t used[MAX_TABLES];
     for (int t = 0; t < MAX_TABLES; ++t) used[t] = 0;
-    int slot = o_slot[r]; // slots are handed out in (class, piece) order
+    int slot = o_slot[p]; // slots are handed out in (class, piece) order
     for_each_item(colidx, beg, end, n_classes, cb, part_row, item_max, [&](int t, int32_t b, int32_t e) {
         Segment sg;
         sg.row = (int32_t)r;
         sg.beg = b;
         sg.end = e;
         sg.dst = total == 1 ? (int32_t)r : -(slot + 1);
-        items[off[t * stride + r] + used[t]] = sg;
+        items[off[t * stride + p] + used[t]] = sg;
         used[t] += 1;
         ++slot;
     });
     if (total > 1) {
         FixRow f;
         f.row = (int32_t)r;
-        f.slot_beg = o_slot[r];
-        f.slot_end = o_slot[r] + total;
+        f.slot_beg = o_slot[p];
+        f.slot_end = o_slot[p] + total;
         f.pad = 0;
-        fix[o_fix[r]] = f;
+        fix[o_fix[p]] = f;
     }
 }
 
@@ -304,14 +311,16 @@ void free_csr(Csr &m, bool owns_pattern)
     m = Csr();
 }
 
-int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream)
+int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, const int32_t *order, int n_classes, uint32_t flags,
+                   Schedule &out, hipStream_t stream)
 {
     out = Schedule();
     out.n_classes = n_classes;
     // entries (8 bytes each) plus one 128-byte operand row per node against the 256 MB last-level cache
     const bool resident = nnz * 8 + n * 128 <= ((int64_t)256 << 20);
     int32_t item_max = resident ? ITEM_SHORT : ITEM_LONG;
-    if (const char *e = getenv("SLICEGCN_ITEM_MAX")) item_max = atoi(e) == ITEM_SHORT ? ITEM_SHORT : ITEM_LONG;
+    if (flags & SLICEGCN_SCHED_SHORT_ITEMS) item_max = ITEM_SHORT;
+    if (flags & SLICEGCN_SCHED_LONG_ITEMS) item_max = ITEM_LONG;
     out.item_max = item_max;
     const int n_tables = 2 * n_classes + 2;
     const size_t stride = (size_t)(n + 1);
@@ -327,8 +336,8 @@ int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, 
     SG_LAUNCH_CHECK();
     SG_HIP(hipMemcpyAsync(cb.first, x + 4 * stride, sizeof(cb.first), hipMemcpyDeviceToHost, stream));
     SG_HIP(hipStreamSynchronize(stream));
-    const int32_t part_row = getenv("SLICEGCN_PART_ROW") ? atoi(getenv("SLICEGCN_PART_ROW")) : PART_ROW;
-    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, item_max, c, x, x + stride);
+    const int32_t part_row = PART_ROW;
+    sched_count_kernel<<<blocks_for(n + 1), TPB, 0, stream>>>(m.rowptr, m.colidx, n, order, n_classes, cb, part_row, item_max, c, x, x + stride);
     SG_LAUNCH_CHECK();
     if (int rc = scan_i32(c, o, (int64_t)n_cnt, stream)) return rc;
     if (int rc = scan_i32(x, x + 2 * stride, n + 1, stream)) return rc;
@@ -359,13 +368,14 @@ int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, 
     DevBuf items, fix;
     if (int rc = items.alloc((size_t)out.n_items * sizeof(Segment))) return rc;
     if (int rc = fix.alloc((size_t)out.n_fix * sizeof(FixRow))) return rc;
-    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, n_classes, cb, part_row, item_max, o, x + 2 * stride,
+    sched_fill_kernel<<<blocks_for(n), TPB, 0, stream>>>(m.rowptr, m.colidx, n, order, n_classes, cb, part_row, item_max, o, x + 2 * stride,
                                                          x + 3 * stride, items.as<Segment>(), fix.as<FixRow>());
     SG_LAUNCH_CHECK();
     SG_HIP(hipStreamSynchronize(stream));
     out.items = items.release<Segment>();
     out.fix = fix.release<FixRow>();
-    if (getenv("SLICEGCN_VERBOSE")) {
+    static const bool verbose = getenv("SLICEGCN_VERBOSE") != nullptr;
+    if (verbose) {
         fprintf(stderr, "[slicegcn] schedule with %d class(es): whole rows %d wavefront + %d lane-group items, %lld rows with "
                         "several items, %lld partial-sum slots\n", n_classes, out.wbig_cnt, out.wsmall_cnt,
                 (long long)out.n_fix, (long long)out.n_slots);
@@ -377,16 +387,10 @@ int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, 
 }
 
 // colptr: row pointer of the transposed pattern
-static int build_schedules(int64_t n, int64_t nnz, Csr &m, const int32_t *colptr, hipStream_t stream)
+static int build_schedules(int64_t n, int64_t nnz, Csr &m, const int32_t *colptr, const int32_t *order, uint32_t flags, hipStream_t stream)
 {
-    if (int rc = build_schedule(n, nnz, m, colptr, 1, m.wide, stream)) return rc;
-    return build_schedule(n, nnz, m, colptr, MAX_CLASSES, m.xcd, stream);
-}
-
-static int64_t scratch_need(const Csr &m)
-{
-    const int64_t a = m.wide.n_slots * WIDE_SLOT_COLS, b = m.xcd.n_slots * XCD_SLOT_COLS;
-    return a > b ? a : b;
+    if (int rc = build_schedule(n, nnz, m, colptr, order, 1, flags, m.wide, stream)) return rc;
+    return build_schedule(n, nnz, m, colptr, order, MAX_CLASSES, flags, m.xcd, stream);
 }
 
 } // namespace slicegcn
@@ -401,8 +405,13 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
     SG_REQUIRE(n_nodes >= 1, SLICEGCN_EINVAL, "build_norm_csr: n_nodes = %lld < 1", (long long)n_nodes);
     SG_REQUIRE(n_edges >= 0, SLICEGCN_EINVAL, "build_norm_csr: n_edges = %lld < 0", (long long)n_edges);
     SG_REQUIRE(n_edges == 0 || (src && dst), SLICEGCN_EINVAL, "build_norm_csr: NULL edge arrays");
-    SG_REQUIRE((flags & ~(SLICEGCN_SYMMETRIZE | SLICEGCN_ADD_SELF_LOOPS)) == 0, SLICEGCN_EINVAL,
-               "build_norm_csr: unknown flag bits 0x%x", flags);
+    SG_REQUIRE((flags & ~(SLICEGCN_SYMMETRIZE | SLICEGCN_ADD_SELF_LOOPS | SLICEGCN_REORDER_DEGREE | SLICEGCN_REORDER_BFS |
+                          SLICEGCN_SCHED_SHORT_ITEMS | SLICEGCN_SCHED_LONG_ITEMS)) == 0,
+               SLICEGCN_EINVAL, "build_norm_csr: unknown flag bits 0x%x", flags);
+    SG_REQUIRE(!((flags & SLICEGCN_REORDER_DEGREE) && (flags & SLICEGCN_REORDER_BFS)), SLICEGCN_EINVAL,
+               "build_norm_csr: REORDER_DEGREE and REORDER_BFS exclude each other");
+    SG_REQUIRE(!((flags & SLICEGCN_SCHED_SHORT_ITEMS) && (flags & SLICEGCN_SCHED_LONG_ITEMS)), SLICEGCN_EINVAL,
+               "build_norm_csr: SCHED_SHORT_ITEMS and SCHED_LONG_ITEMS exclude each other");
     SG_REQUIRE(n_nodes <= INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: n_nodes exceeds int32");
     const int sym = (flags & SLICEGCN_SYMMETRIZE) != 0, loops = (flags & SLICEGCN_ADD_SELF_LOOPS) != 0;
     SG_REQUIRE(n_edges <= (int64_t)INT32_MAX, SLICEGCN_ERANGE, "build_norm_csr: n_edges exceeds int32");
@@ -482,8 +491,11 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
     }
     if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
 
+    if (flags & (SLICEGCN_REORDER_DEGREE | SLICEGCN_REORDER_BFS))
+        if (int rc = build_row_order(n_nodes, g->fwd.rowptr, g->fwd.colidx, (flags & SLICEGCN_REORDER_BFS) != 0, &g->order, stream)) return rc;
+
     if (sym) {
-        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->fwd.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->fwd.rowptr, g->order, flags, stream)) return rc;
         g->tr = g->fwd; // A^ is symmetric: the same arrays serve the transposed product
     } else {
         uint64_t *swapped = keys_b.as<uint64_t>();
@@ -503,18 +515,11 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
         SG_LAUNCH_CHECK();
         g->tr.rowptr = rowptr.release<int32_t>();
         if (int rc = pattern_from_keys(keys_c.as<uint64_t>(), nnz, n_nodes, g->dinv, g->tr, stream)) return rc;
-        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->tr.rowptr, stream)) return rc;
-        if (int rc = build_schedules(n_nodes, nnz, g->tr, g->fwd.rowptr, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->fwd, g->tr.rowptr, g->order, flags, stream)) return rc;
+        if (int rc = build_schedules(n_nodes, nnz, g->tr, g->fwd.rowptr, g->order, flags, stream)) return rc;
         SG_HIP(hipStreamSynchronize(stream));
     }
 
-    const int64_t need_f = scratch_need(g->fwd), need_t = scratch_need(g->tr);
-    g->scratch_floats = need_f > need_t ? need_f : need_t;
-    if (g->scratch_floats > 0) {
-        DevBuf scratch;
-        if (int rc = scratch.alloc((size_t)g->scratch_floats * sizeof(float))) return rc;
-        g->scratch = scratch.release<float>();
-    }
     SG_HIP(hipStreamSynchronize(stream));
     guard.g = nullptr;
     *out = g;
@@ -532,6 +537,7 @@ extern "C" int slicegcn_graph_view(const slicegcn_graph *g, slicegcn_csr_view *v
     view->dinv = g->dinv;
     view->vals = g->fwd.vals;
     view->symmetric = g->symmetric;
+    view->order = g->order;
     return SLICEGCN_OK;
 }
 
@@ -542,7 +548,7 @@ extern "C" int slicegcn_graph_destroy(slicegcn_graph *g)
     free_csr(g->fwd, true);
     (void)hipFree(g->deg);
     (void)hipFree(g->dinv);
-    (void)hipFree(g->scratch);
+    (void)hipFree(g->order);
     delete g;
     return SLICEGCN_OK;
 }

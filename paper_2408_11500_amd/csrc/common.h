@@ -55,8 +55,8 @@ __host__ __device__ inline bool aligned16(const void *p) { return (reinterpret_c
 // own class of columns of the gathered operand for the partitioned rows.  Whole-row items form
 // two lists of their own (wavefront and lane-group items, in row order) that are dealt to the
 // classes in fixed-size chunks, round-robin, and run behind the class's pieces.  A row with
-// several items gets one partial-sum slot per item and is finished by a fix-up pass that adds the
-// slots in order.
+// several items gets one partial-sum slot per item (in a workspace the caller of the aggregation
+// provides) and is finished by a fix-up pass that adds the slots in order.
 constexpr int TINY_ROW = 4;
 constexpr int ITEM_SHORT = 32;
 constexpr int ITEM_LONG = 64;
@@ -111,17 +111,18 @@ struct slicegcn_graph {
     int device = 0;
     int32_t *deg = nullptr;
     float *dinv = nullptr;
+    int32_t *order = nullptr; // order[p] = row at position p of the aggregation's schedule; NULL = natural order
     slicegcn::Csr fwd;  // A^
     slicegcn::Csr tr;   // A^^T (arrays alias fwd when the pattern is symmetric)
-    float *scratch = nullptr; // partial sums of rows with several items (see Schedule)
-    int64_t scratch_floats = 0;
 };
 
 namespace slicegcn {
 
-// spmm.hip: Y[:, 0:width] = M X (+ Add), M given by `m`.  Add may alias Y.
+// spmm.hip: Y[:, 0:width] = M X (+ Add), M given by `m`.  Add may alias Y.  ws: 256-byte aligned, at least
+// spmm_workspace_bytes(m, width) bytes (partial sums of rows cut into several items; may be NULL when that is 0).
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
-                float *Y, int64_t ldy, const float *Add, int64_t ldadd, hipStream_t stream);
+                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream);
+size_t spmm_workspace_bytes(const Csr &m, int32_t width);
 
 // dense.hip: column sums of an n x w matrix: fp32 per block of rows into ws[blocks][w], then
 // out[j] = sum over blocks of ws[b][first + j] in fp64 (ws_row = floats per ws row)
@@ -140,7 +141,11 @@ struct ProfScope {
 };
 
 // build_csr.hip
-int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, int n_classes, Schedule &out, hipStream_t stream);
+int build_schedule(int64_t n, int64_t nnz, const Csr &m, const int32_t *colptr, const int32_t *order, int n_classes, uint32_t flags,
+                   Schedule &out, hipStream_t stream);
+
+// order.hip: order[p] = id of the row at position p (by degree, or breadth first); *out is a device array the caller frees
+int build_row_order(int64_t n, const int32_t *rowptr, const int32_t *colidx, bool breadth_first, int32_t **out, hipStream_t stream);
 void free_csr(Csr &m, bool owns_pattern);
 
 } // namespace slicegcn

@@ -6,21 +6,15 @@
 //   backward:  dZ = (dHout * mask) W_agg^T,  T = dHout W_self^T            (pair kernel, transposed)
 //              dW_agg = Z^T (dHout * mask), dW_self = Hin^T dHout, db, db_self   (reduce kernels)
 //
-// Two implementations of the pair kernel and of the weight-gradient reduction live here:
-//   * MFMA (default): v_mfma_f32_32x32x2_f32 tiles, one 32-row strip per wavefront, operands staged
-//     through LDS with coalesced 16-byte loads; fp32 in, fp32 accumulate.
-//   * plain fp32 FMA with 4x4 register micro-tiles (SLICEGCN_DENSE=fma), kept as a cross-check.
+// Every product runs on v_mfma_f32_32x32x2_f32 tiles (fp32 in, fp32 accumulate), one 32-row strip per
+// wavefront, operands staged through LDS with coalesced 16-byte loads.
 // Lane layout of the 32x32x2 fp32 MFMA (64 lanes, l = lane): A operand = A[m = l % 32][k = l / 32],
 // B operand = B[k = l / 32][n = l % 32], accumulator register r (0..15) = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
 #include "common.h"
 
-#include <cstdlib>
-
 namespace slicegcn {
 
 namespace {
-
-constexpr int KT = 16;
 
 struct PairArgs {
     const float *A1; int64_t lda1; // forward: Z          backward: dHout (masked on load)
@@ -38,134 +32,6 @@ struct PairArgs {
     int32_t ldw;   // leading dimension of W (= w_out)
     int32_t act;
 };
-
-// CGP: column groups (of 4 columns) per block, 8 / 16 / 32.  Rows per block = (256 / CGP) * 4.
-template <int CGP, bool BWD>
-__global__ __launch_bounds__(256) void pair_gemm_kernel(const PairArgs a)
-{
-    constexpr int BM = (256 / CGP) * 4;
-    constexpr int BN = CGP * 4;
-    __shared__ float As1[BM][KT + 1];
-    __shared__ float As2[BM][KT + 1];
-    __shared__ __attribute__((aligned(16))) float Bs1[KT][BN];
-    __shared__ __attribute__((aligned(16))) float Bs2[KT][BN];
-
-    const int tid = threadIdx.x;
-    const int rg = tid / CGP, cg = tid % CGP;
-    const int64_t row0 = (int64_t)blockIdx.x * BM;
-    const int col0 = blockIdx.y * BN;
-    const bool two = a.A2 != nullptr && a.B2 != nullptr;
-
-    float acc1[4][4], acc2[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { acc1[i][j] = 0.f; acc2[i][j] = 0.f; }
-
-    for (int k0 = 0; k0 < a.K; k0 += KT) {
-        // ---- stage A tiles (BM x KT) ----
-        for (int t = tid; t < BM * KT; t += 256) {
-            const int r = t / KT, k = t % KT;
-            const int64_t row = row0 + r;
-            const int kk = k0 + k;
-            float v1 = 0.f, v2 = 0.f;
-            if (row < a.n && kk < a.K) {
-                v1 = a.A1[row * a.lda1 + kk];
-                if (BWD) {
-                    if (a.mask) {
-                        const uint32_t w = a.mask[row * a.mask_words + (kk >> 5)];
-                        if (((w >> (kk & 31)) & 1u) == 0u) v1 = 0.f;
-                    }
-                }
-                if (two) v2 = a.A2[row * a.lda2 + kk];
-            }
-            As1[r][k] = v1;
-            As2[r][k] = v2;
-        }
-        // ---- stage B tiles (KT x BN) ----
-        for (int t = tid; t < KT * BN; t += 256) {
-            const int k = t / BN, j = t % BN;
-            const int kk = k0 + k, col = col0 + j;
-            float w1 = 0.f, w2 = 0.f;
-            if (kk < a.K && col < a.Nout) {
-                const int64_t idx = BWD ? (int64_t)col * a.ldw + kk : (int64_t)kk * a.ldw + col;
-                w1 = a.B1[idx];
-                if (two) w2 = a.B2[idx];
-            }
-            Bs1[k][j] = w1;
-            Bs2[k][j] = w2;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < KT; ++k) {
-            const float4 b1 = *reinterpret_cast<const float4 *>(&Bs1[k][cg * 4]);
-            float x1[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) x1[i] = As1[rg * 4 + i][k];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc1[i][0] += x1[i] * b1.x; acc1[i][1] += x1[i] * b1.y;
-                acc1[i][2] += x1[i] * b1.z; acc1[i][3] += x1[i] * b1.w;
-            }
-            if (two) {
-                const float4 b2 = *reinterpret_cast<const float4 *>(&Bs2[k][cg * 4]);
-                float x2[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) x2[i] = As2[rg * 4 + i][k];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc2[i][0] += x2[i] * b2.x; acc2[i][1] += x2[i] * b2.y;
-                    acc2[i][2] += x2[i] * b2.z; acc2[i][3] += x2[i] * b2.w;
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-    // ---- epilogue ----
-    const int colb = col0 + cg * 4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t row = row0 + rg * 4 + i;
-        float o1[4], o2[4];
-        uint32_t bits = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = colb + j;
-            if (!BWD) {
-                float p = acc1[i][j] + ((a.bias1 && col < a.Nout) ? a.bias1[col] : 0.f);
-                if (p > 0.f && col < a.Nout) bits |= 1u << j;
-                const float r = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
-                float s = 0.f;
-                if (two) s = acc2[i][j] + ((a.bias2 && col < a.Nout) ? a.bias2[col] : 0.f);
-                o1[j] = r + s;
-                o2[j] = 0.f;
-            } else {
-                o1[j] = acc1[i][j];
-                o2[j] = acc2[i][j];
-            }
-        }
-        if (!BWD && a.act == SLICEGCN_ACT_RELU) {
-            // eight neighbouring lanes hold the 32 columns of one mask word of this row
-            uint32_t word = bits << ((cg & 7) * 4);
-            word |= __shfl_xor(word, 1, 64);
-            word |= __shfl_xor(word, 2, 64);
-            word |= __shfl_xor(word, 4, 64);
-            const int widx = (col0 >> 5) + (cg >> 3);
-            if ((cg & 7) == 0 && row < a.n && widx * 32 < a.Nout) a.mask[row * a.mask_words + widx] = word;
-        }
-        if (row < a.n) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = colb + j;
-                if (col < a.Nout) {
-                    a.O1[row * a.ldo1 + col] = o1[j];
-                    if (BWD && a.O2) a.O2[row * a.ldo2 + col] = o2[j];
-                }
-            }
-        }
-    }
-}
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -817,22 +683,12 @@ void launch_direct(const PairArgs &a, dim3 grid, hipStream_t stream)
     else pair_mfma_direct_kernel<NT, 2, BWD><<<grid, 256, 0, stream>>>(a);
 }
 
-bool use_mfma()
-{
-    static const bool v = [] {
-        const char *e = getenv("SLICEGCN_DENSE");
-        return !(e && strcmp(e, "fma") == 0);
-    }();
-    return v;
-}
-
 template <bool BWD>
-int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
+int launch_pair(const PairArgs &a, hipStream_t stream)
 {
     const int nt = a.Nout <= 32 ? 1 : a.Nout <= 64 ? 2 : a.Nout <= 96 ? 3 : 4;
     dim3 grid((unsigned)((a.n + 127) / 128), (unsigned)((a.Nout + nt * 32 - 1) / (nt * 32)));
-    static const bool no_direct = getenv("SLICEGCN_DENSE_STAGED") != nullptr;
-    if (a.K <= 32 && a.Nout <= 32 && !no_direct) { // narrowest layers: per-wavefront strips, no barriers
+    if (a.K <= 32 && a.Nout <= 32) { // narrowest layers: per-wavefront strips, no barriers
         const int64_t strips = (a.n + 31) / 32;
         const unsigned gb = (unsigned)((strips + 3) / 4 < 2048 ? (strips + 3) / 4 : 2048);
         const bool two = a.A2 != nullptr && a.B2 != nullptr;
@@ -841,8 +697,7 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
     }
-    static const bool no_strip64 = getenv("SLICEGCN_NO_STRIP64") != nullptr;
-    if (a.K <= 64 && a.Nout <= 64 && a.n >= 262144 && !no_direct && !no_strip64) { // up to 64 wide: strips, weights in LDS
+    if (a.K <= 64 && a.Nout <= 64 && a.n >= 262144) { // up to 64 wide: strips, weights in LDS
         const int64_t strips = (a.n + 31) / 32;
         // as many workgroups as the chip holds at once (two per CU): each stages the weights once
         const unsigned gb = (unsigned)((strips + 3) / 4 < 512 ? (strips + 3) / 4 : 512);
@@ -852,7 +707,7 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
     }
-    if (a.K <= 64 && nt == 1 && !no_direct) { // short reduction, one output tile: weights resident in LDS, workgroups walk over row tiles
+    if (a.K <= 64 && nt == 1) { // short reduction, one output tile: weights resident in LDS, workgroups walk over row tiles
         const unsigned tiles = grid.x;
         grid.x = tiles < 2048u ? tiles : 2048u;
         switch (nt) {
@@ -893,23 +748,6 @@ int launch_pair_mfma(const PairArgs &a, hipStream_t stream)
     return SLICEGCN_OK;
 }
 
-template <bool BWD>
-int launch_pair(const PairArgs &a, hipStream_t stream)
-{
-    if (use_mfma()) return launch_pair_mfma<BWD>(a, stream);
-    int cgp = 8;
-    while (cgp < 32 && cgp * 4 < a.Nout) cgp <<= 1;
-    const int bm = (256 / cgp) * 4, bn = cgp * 4;
-    dim3 grid((unsigned)((a.n + bm - 1) / bm), (unsigned)((a.Nout + bn - 1) / bn));
-    switch (cgp) {
-    case 8: pair_gemm_kernel<8, BWD><<<grid, 256, 0, stream>>>(a); break;
-    case 16: pair_gemm_kernel<16, BWD><<<grid, 256, 0, stream>>>(a); break;
-    default: pair_gemm_kernel<32, BWD><<<grid, 256, 0, stream>>>(a); break;
-    }
-    SG_LAUNCH_CHECK();
-    return SLICEGCN_OK;
-}
-
 // ---- weight-gradient reductions over the node axis ----------------------------------------
 constexpr int RED_ROWS = 1024; // rows per block: fp32 chains stay this short
 constexpr int RED_TILE = 32;   // output tile edge
@@ -928,86 +766,9 @@ struct ReduceArgs {
     int32_t rows_per_block = RED_ROWS;  // tiled kernels: node rows per workgroup (one partial each)
 };
 
-__global__ __launch_bounds__(256) void grad_partial_kernel(const ReduceArgs a)
-{
-    __shared__ float Zs[RED_RK][RED_TILE + 1];
-    __shared__ float Hs[RED_RK][RED_TILE + 1];
-    __shared__ float Ps[RED_RK][RED_TILE + 1];
-    __shared__ float Gs[RED_RK][RED_TILE + 1];
-    const int tid = threadIdx.x;
-    const int ty = tid / 16, tx = tid % 16;
-    const int i_base = blockIdx.y * RED_TILE, j_base = blockIdx.z * RED_TILE;
-    const int64_t r_begin = (int64_t)blockIdx.x * a.rows_per_block;
-    const int64_t r_end = r_begin + a.rows_per_block < a.n ? r_begin + a.rows_per_block : a.n;
-    const bool self = a.Hin != nullptr;
-
-    float accA[2][2] = {{0.f, 0.f}, {0.f, 0.f}}, accS[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-    float accb[2] = {0.f, 0.f}, accbs[2] = {0.f, 0.f};
-
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
-        for (int t = tid; t < RED_RK * RED_TILE; t += 256) {
-            const int r = t / RED_TILE, c = t % RED_TILE;
-            const int64_t row = r0 + r;
-            float z = 0.f, h = 0.f, p = 0.f, gq = 0.f;
-            if (row < r_end) {
-                const int i = i_base + c, j = j_base + c;
-                if (i < a.w_in) {
-                    z = a.Z[row * a.ldz + i];
-                    if (self) h = a.Hin[row * a.ldi + i];
-                }
-                if (j < a.w_out) {
-                    gq = a.dHout[row * a.ldo + j];
-                    p = gq;
-                    if (a.mask) {
-                        const uint32_t w = a.mask[row * a.mask_words + (j >> 5)];
-                        if (((w >> (j & 31)) & 1u) == 0u) p = 0.f;
-                    }
-                }
-            }
-            Zs[r][c] = z; Hs[r][c] = h; Ps[r][c] = p; Gs[r][c] = gq;
-        }
-        __syncthreads();
-#pragma unroll 8
-        for (int r = 0; r < RED_RK; ++r) {
-            const float z0 = Zs[r][ty * 2], z1 = Zs[r][ty * 2 + 1];
-            const float p0 = Ps[r][tx * 2], p1 = Ps[r][tx * 2 + 1];
-            accA[0][0] += z0 * p0; accA[0][1] += z0 * p1; accA[1][0] += z1 * p0; accA[1][1] += z1 * p1;
-            const float g0 = Gs[r][tx * 2], g1 = Gs[r][tx * 2 + 1];
-            if (self) {
-                const float h0 = Hs[r][ty * 2], h1 = Hs[r][ty * 2 + 1];
-                accS[0][0] += h0 * g0; accS[0][1] += h0 * g1; accS[1][0] += h1 * g0; accS[1][1] += h1 * g1;
-            }
-            if (ty == 0) { accb[0] += p0; accb[1] += p1; accbs[0] += g0; accbs[1] += g1; }
-        }
-        __syncthreads();
-    }
-
-    float *out = a.partial + (int64_t)blockIdx.x * a.stride;
-    const int ww = a.w_in * a.w_out;
-#pragma unroll
-    for (int di = 0; di < 2; ++di)
-#pragma unroll
-        for (int dj = 0; dj < 2; ++dj) {
-            const int i = i_base + ty * 2 + di, j = j_base + tx * 2 + dj;
-            if (i < a.w_in && j < a.w_out) {
-                out[i * a.w_out + j] = accA[di][dj];
-                if (!a.compact) out[ww + i * a.w_out + j] = accS[di][dj];
-            }
-        }
-    if (blockIdx.y == 0 && ty == 0) {
-#pragma unroll
-        for (int dj = 0; dj < 2; ++dj) {
-            const int j = j_base + tx * 2 + dj;
-            if (j < a.w_out) {
-                out[(a.compact ? ww : 2 * ww) + j] = accb[dj];
-                if (!a.compact) out[2 * ww + a.w_out + j] = accbs[dj];
-            }
-        }
-    }
-}
-
-// MFMA version of the partial weight gradients.  Same grid and output layout as
-// grad_partial_kernel.  Per step the workgroup stages 32 rows of the four operand tiles in LDS;
+// Partial weight gradients, tiled: grid = (row blocks, w_in tiles, w_out tiles), every workgroup writes its
+// tile of the four results [Z^T dP | Hin^T dHout | colsum dP | colsum dHout] of its row block into
+// partial[row block][...].  Per step the workgroup stages 32 rows of the four operand tiles in LDS;
 // wavefront w multiplies rows 8w..8w+7 (the node axis is the MFMA's k axis: A[m][k] = Z[k][m]),
 // and the four wavefronts' accumulators are added in wavefront order at the end.
 __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs a)
@@ -1119,7 +880,7 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
 // its own accumulators and every n_waves-th strip of 32 rows (so that the chip reads one contiguous
 // window at a time), reads a strip with coalesced 16-byte loads into wave-private LDS tiles (the
 // next strip's loads in flight during the MFMAs), and writes one partial result.  The node axis is the MFMA's k axis (lane (m, h) feeds
-// column m of node row 2s + h).  No workgroup barrier; same output layout as grad_partial_kernel,
+// column m of node row 2s + h).  No workgroup barrier; same output layout as grad_partial_mfma_kernel,
 // one partial per wavefront.
 __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, int64_t n_waves)
 {
@@ -1565,12 +1326,84 @@ inline int64_t layer_grad_blocks(int64_t n, int32_t w_in, int32_t w_out)
     return (n + rows - 1) / rows;
 }
 
+
+// ---- pieces of the transform-first layer order -------------------------------------------------
+// Hout[v, j] = act(P[v, j] + bias[j]) (+ Hout[v, j] when add), mask bit j of row v = [P + bias > 0].
+// One thread per element of the row padded to a multiple of 32 columns, so every half wavefront lies
+// inside one mask word of one row and a ballot assembles the word.
+__global__ __launch_bounds__(256) void bias_act_add_kernel(const float *__restrict__ P, int64_t ldp, const float *__restrict__ bias,
+                                                           float *__restrict__ Hout, int64_t ldo, int add, uint32_t *__restrict__ mask,
+                                                           int64_t mask_words, int64_t n, int32_t w_out, int32_t act)
+{
+    const int wpad = (w_out + 31) / 32 * 32;
+    const int64_t total = n * (int64_t)wpad;
+    const int64_t padded_total = (total + 63) / 64 * 64; // whole wavefronts take part in every ballot
+    const int lane = threadIdx.x & 63;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < padded_total; t += (int64_t)gridDim.x * 256) {
+        const int64_t row = t / wpad;
+        const int col = (int)(t - row * wpad);
+        const bool valid = t < total && col < w_out;
+        const float p = valid ? P[row * ldp + col] + (bias ? bias[col] : 0.f) : 0.f;
+        const bool pos = valid && p > 0.f;
+        const unsigned long long bits = __ballot(pos);
+        if (valid) {
+            float r = act == SLICEGCN_ACT_RELU ? (pos ? p : 0.f) : p;
+            if (add) r += Hout[row * ldo + col];
+            Hout[row * ldo + col] = r;
+        }
+        if (act == SLICEGCN_ACT_RELU && (lane & 31) == 0 && t < total)
+            mask[row * mask_words + (col >> 5)] = (uint32_t)(bits >> (lane & 32));
+    }
+}
+
+// dP[v, j] = dHout[v, j] where the activation passed (all of it when mask == NULL)
+__global__ __launch_bounds__(256) void mask_apply_kernel(const float *__restrict__ dHout, int64_t ldo, const uint32_t *__restrict__ mask,
+                                                         int64_t mask_words, float *__restrict__ dP, int64_t ldp, int64_t n, int32_t w_out)
+{
+    const int64_t total = n * (int64_t)w_out;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t row = t / w_out;
+        const int col = (int)(t - row * w_out);
+        float v = dHout[row * ldo + col];
+        if (mask && ((mask[row * mask_words + (col >> 5)] >> (col & 31)) & 1u) == 0u) v = 0.f;
+        dP[row * ldp + col] = v;
+    }
+}
+
+// Wt[j][i] = W[i][j] for a rows x cols row-major W (weights are small: one thread per element)
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ W, int32_t rows, int32_t cols, float *__restrict__ Wt)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows * cols) return;
+    const int i = t / cols, j = t - i * cols;
+    Wt[(int64_t)j * rows + i] = W[t];
+}
+
+inline unsigned ew_grid(int64_t total)
+{
+    const int64_t b = (total + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : (b > 262144 ? 262144 : b));
+}
+
+// aggregate first: Z = A^ Hin, then the weight products; transform first: T = Hin W_agg, then P = A^ T.
+// Equal in exact arithmetic; the second gathers rows of w_out instead of w_in columns.
+inline bool transform_first(const slicegcn_layer_desc *d)
+{
+    if (d->flags & SLICEGCN_LAYER_TRANSFORM_FIRST) return true;
+    return (d->flags & SLICEGCN_LAYER_ORDER_AUTO) && d->w_out < d->w_in;
+}
+
 int check_layer(const slicegcn_graph *g, const slicegcn_layer_desc *d, const slicegcn_layer_params *p, const char *who)
 {
     SG_REQUIRE(g && d && p, SLICEGCN_EINVAL, "%s: NULL graph, desc or params", who);
     SG_REQUIRE(d->w_in >= 1 && d->w_out >= 1, SLICEGCN_EINVAL, "%s: widths must be >= 1", who);
     SG_REQUIRE(d->act == SLICEGCN_ACT_NONE || d->act == SLICEGCN_ACT_RELU, SLICEGCN_EINVAL, "%s: unknown act %d", who, d->act);
-    SG_REQUIRE((d->flags & ~SLICEGCN_LAYER_Z_VALID) == 0, SLICEGCN_EINVAL, "%s: unknown flag bits 0x%x", who, d->flags);
+    SG_REQUIRE((d->flags & ~(SLICEGCN_LAYER_Z_VALID | SLICEGCN_LAYER_TRANSFORM_FIRST | SLICEGCN_LAYER_ORDER_AUTO)) == 0, SLICEGCN_EINVAL,
+               "%s: unknown flag bits 0x%x", who, d->flags);
+    SG_REQUIRE(!((d->flags & SLICEGCN_LAYER_TRANSFORM_FIRST) && (d->flags & SLICEGCN_LAYER_ORDER_AUTO)), SLICEGCN_EINVAL,
+               "%s: TRANSFORM_FIRST and ORDER_AUTO exclude each other", who);
+    SG_REQUIRE(!((d->flags & SLICEGCN_LAYER_Z_VALID) && transform_first(d)), SLICEGCN_EINVAL,
+               "%s: Z_VALID needs the aggregate-first order (no aggregation of the input is kept by the transform-first order)", who);
     SG_REQUIRE(p->W_agg != nullptr, SLICEGCN_EINVAL, "%s: W_agg is NULL", who);
     SG_REQUIRE(p->W_self != nullptr || p->b_self == nullptr, SLICEGCN_EINVAL, "%s: b_self without W_self", who);
     return SLICEGCN_OK;
@@ -1578,9 +1411,12 @@ int check_layer(const slicegcn_graph *g, const slicegcn_layer_desc *d, const sli
 
 int check_saved(const slicegcn_layer_desc *d, const slicegcn_layer_saved *s, const char *who)
 {
-    SG_REQUIRE(s && s->Z, SLICEGCN_EINVAL, "%s: saved or saved->Z is NULL", who);
-    SG_REQUIRE(s->ldz >= d->w_in && s->ldz % 4 == 0 && aligned16(s->Z), SLICEGCN_EINVAL,
-               "%s: saved->Z needs ldz >= w_in, ldz %% 4 == 0 and a 16-byte aligned base", who);
+    SG_REQUIRE(s != nullptr, SLICEGCN_EINVAL, "%s: saved is NULL", who);
+    if (!transform_first(d)) { // the transform-first order keeps no aggregation: Z is neither written nor read
+        SG_REQUIRE(s->Z != nullptr, SLICEGCN_EINVAL, "%s: saved->Z is NULL", who);
+        SG_REQUIRE(s->ldz >= d->w_in && s->ldz % 4 == 0 && aligned16(s->Z), SLICEGCN_EINVAL,
+                   "%s: saved->Z needs ldz >= w_in, ldz %% 4 == 0 and a 16-byte aligned base", who);
+    }
     if (d->act == SLICEGCN_ACT_RELU)
         SG_REQUIRE(s->mask && s->mask_words >= (d->w_out + 31) / 32, SLICEGCN_EINVAL,
                    "%s: mask is NULL or mask_words < ceil(w_out / 32)", who);
@@ -1617,18 +1453,159 @@ size_t colsum_workspace_bytes(int64_t n, int32_t w) { return (size_t)red_blocks(
 
 using namespace slicegcn;
 
+// partial sums of a dense layer's weight and bias gradients: one [w_in*w_out + w_out] row per block of 1024 rows
+static size_t linear_partial_bytes(int64_t n, int32_t w_in, int32_t w_out)
+{
+    const size_t stride = (size_t)w_in * w_out + (size_t)w_out;
+    return (size_t)round_up((int64_t)(red_blocks(n) * stride * sizeof(float)), 256);
+}
+
+// dW = X^T (dY * mask) (w_in x w_out), db = colsum(dY * mask); NULL outputs are skipped.  ws: linear_partial_bytes bytes.
+static int launch_linear_grads(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out, const uint32_t *m,
+                               int64_t mask_words, const float *dY, int64_t lddy, float *dW, float *db, void *ws, hipStream_t stream)
+{
+    const int64_t nb = red_blocks(n);
+    const int ww = w_in * w_out;
+    const int32_t stride = ww + w_out;
+    ReduceArgs r;
+    r.Z = X; r.ldz = ldx; r.Hin = nullptr; r.ldi = 0; r.dHout = dY; r.ldo = lddy;
+    r.mask = m; r.mask_words = mask_words;
+    r.partial = static_cast<float *>(ws); r.n = n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 1;
+    dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
+    if (w_in > 64 || w_out > 64) { // wide layer: 128 x 128 output tiles
+        dim3 big((unsigned)nb, (unsigned)((w_in + GB_T - 1) / GB_T), (unsigned)((w_out + GB_T - 1) / GB_T));
+        grad_big_mfma_kernel<<<big, 256, 0, stream>>>(r);
+    } else {
+        grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
+    }
+    SG_LAUNCH_CHECK();
+    FinalDst dst;
+    dst.ptr[0] = dW; dst.ptr[1] = db; dst.ptr[2] = dst.ptr[3] = nullptr;
+    dst.begin[0] = 0; dst.begin[1] = ww; dst.begin[2] = dst.begin[3] = dst.begin[4] = stride;
+    reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(r.partial, nb, stride, stride, dst);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
+// ---- transform-first order of a slice layer ------------------------------------------------
+// forward : T = Hin W_agg;  S = Hin W_self + b_self (stored straight into Hout);  P = A^ T;
+//           Hout = act(P + b) + S,  mask = [P + b > 0]
+// backward: dP = dHout * mask;  db = colsum dP;  G = A^^T dP;  dW_agg = Hin^T G;
+//           dW_self = Hin^T dHout, db_self = colsum dHout;  dHin = G W_agg^T + dHout W_self^T
+// Nothing of the forward pass but the mask is kept: the backward pass aggregates dP instead of re-using A^ Hin.
+static size_t tf_mat_bytes(int64_t n, int32_t w) { return (size_t)round_up(n * round_up(w, 32) * (int64_t)sizeof(float), 256); }
+static size_t tf_wt_bytes(const slicegcn_layer_desc *d) { return (size_t)round_up((int64_t)d->w_in * d->w_out * (int64_t)sizeof(float), 256); }
+static size_t tf_red_bytes(int64_t n, const slicegcn_layer_desc *d)
+{
+    const size_t a = linear_partial_bytes(n, d->w_in, d->w_out), b = (size_t)round_up((int64_t)colsum_workspace_bytes(n, d->w_out), 256);
+    return a > b ? a : b;
+}
+// backward workspace: [dP | G | W_agg^T | W_self^T | reduction partials | aggregation workspace]
+static size_t tf_bwd_bytes(const slicegcn_graph *g, const slicegcn_layer_desc *d)
+{
+    return 2 * tf_mat_bytes(g->n, d->w_out) + 2 * tf_wt_bytes(d) + tf_red_bytes(g->n, d) + spmm_workspace_bytes(g->tr, d->w_out);
+}
+
+static int layer_fwd_transform_first(const slicegcn_graph *g, const slicegcn_layer_desc *desc, const slicegcn_layer_params *params,
+                                     const float *Hin, int64_t ldi, float *Hout, int64_t ldo, slicegcn_layer_saved *saved,
+                                     void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    const int w_in = desc->w_in, w_out = desc->w_out;
+    const size_t need = slicegcn_layer_fwd_workspace_bytes(g, desc);
+    SG_REQUIRE(ws != nullptr && ws_bytes >= need, SLICEGCN_EWORKSPACE, "layer_fwd: workspace of %zu bytes, %zu needed", ws_bytes, need);
+    SG_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255u) == 0, SLICEGCN_EINVAL, "layer_fwd: workspace not 256-byte aligned");
+    const int64_t ldt = round_up(w_out, 32);
+    float *T = static_cast<float *>(ws);
+    float *P = reinterpret_cast<float *>(static_cast<char *>(ws) + tf_mat_bytes(g->n, w_out));
+    void *agg_ws = static_cast<char *>(ws) + 2 * tf_mat_bytes(g->n, w_out);
+    {
+        ProfScope prof(SLICEGCN_PROF_DENSE_FWD, w_out, stream);
+        PairArgs a;
+        a.A1 = Hin; a.lda1 = ldi; a.A2 = nullptr; a.lda2 = 0;
+        a.B1 = params->W_agg; a.B2 = nullptr; a.bias1 = a.bias2 = nullptr;
+        a.O1 = T; a.ldo1 = ldt; a.O2 = nullptr; a.ldo2 = 0;
+        a.mask = nullptr; a.mask_words = 0;
+        a.n = g->n; a.K = w_in; a.Nout = w_out; a.ldw = w_out; a.act = SLICEGCN_ACT_NONE;
+        if (int rc = launch_pair<false>(a, stream)) return rc;
+        if (params->W_self) { // the self term goes straight to the output; the epilogue below adds the activated part
+            a.B1 = params->W_self; a.bias1 = params->b_self; a.O1 = Hout; a.ldo1 = ldo;
+            if (int rc = launch_pair<false>(a, stream)) return rc;
+        }
+    }
+    if (int rc = launch_spmm(g, g->fwd, T, ldt, w_out, P, ldt, nullptr, 0, agg_ws, spmm_workspace_bytes(g->fwd, w_out), stream)) return rc;
+    ProfScope prof(SLICEGCN_PROF_DENSE_FWD, w_out, stream);
+    const int64_t total = g->n * round_up(w_out, 32);
+    bias_act_add_kernel<<<ew_grid(total), 256, 0, stream>>>(P, ldt, params->b, Hout, ldo, params->W_self != nullptr,
+                                                            desc->act == SLICEGCN_ACT_RELU ? saved->mask : nullptr, saved->mask_words,
+                                                            g->n, w_out, desc->act);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
+}
+
+static int layer_bwd_transform_first(const slicegcn_graph *g, const slicegcn_layer_desc *desc, const slicegcn_layer_params *params,
+                                     const float *Hin, int64_t ldi, const uint32_t *mask, int64_t mask_words, const float *dHout,
+                                     int64_t ldo, float *dHin, int64_t ldgi, slicegcn_layer_grads *grads, void *ws, hipStream_t stream)
+{
+    const int w_in = desc->w_in, w_out = desc->w_out;
+    const int64_t n = g->n, ldp = round_up(w_out, 32);
+    char *base = static_cast<char *>(ws);
+    float *dP = reinterpret_cast<float *>(base);
+    float *G = reinterpret_cast<float *>(base + tf_mat_bytes(n, w_out));
+    float *WaT = reinterpret_cast<float *>(base + 2 * tf_mat_bytes(n, w_out));
+    float *WsT = reinterpret_cast<float *>(base + 2 * tf_mat_bytes(n, w_out) + tf_wt_bytes(desc));
+    void *red = base + 2 * tf_mat_bytes(n, w_out) + 2 * tf_wt_bytes(desc);
+    void *agg_ws = static_cast<char *>(red) + tf_red_bytes(n, desc);
+    {
+        ProfScope prof(SLICEGCN_PROF_DENSE_BWD, w_out, stream);
+        mask_apply_kernel<<<ew_grid(n * w_out), 256, 0, stream>>>(dHout, ldo, mask, mask_words, dP, ldp, n, w_out);
+        SG_LAUNCH_CHECK();
+    }
+    if (int rc = launch_spmm(g, g->tr, dP, ldp, w_out, G, ldp, nullptr, 0, agg_ws, spmm_workspace_bytes(g->tr, w_out), stream)) return rc;
+    {
+        ProfScope prof(SLICEGCN_PROF_GRAD_REDUCE, w_out, stream);
+        if (grads->db) {
+            if (int rc = launch_colsum_partial(dP, ldp, n, w_out, static_cast<float *>(red), stream)) return rc;
+            if (int rc = launch_colsum_final(static_cast<float *>(red), n, w_out, w_out, grads->db, stream)) return rc;
+        }
+        if (grads->dW_agg)
+            if (int rc = launch_linear_grads(Hin, ldi, n, w_in, w_out, nullptr, 0, G, ldp, grads->dW_agg, nullptr, red, stream)) return rc;
+        if (params->W_self && (grads->dW_self || grads->db_self))
+            if (int rc = launch_linear_grads(Hin, ldi, n, w_in, w_out, nullptr, 0, dHout, ldo, grads->dW_self, grads->db_self, red, stream))
+                return rc;
+    }
+    if (dHin) { // dHin = G W_agg^T + dHout W_self^T: one forward-form launch over the transposed weights
+        ProfScope prof(SLICEGCN_PROF_DENSE_BWD, w_in, stream);
+        const int count = w_in * w_out;
+        transpose_kernel<<<(count + 255) / 256, 256, 0, stream>>>(params->W_agg, w_in, w_out, WaT);
+        if (params->W_self) transpose_kernel<<<(count + 255) / 256, 256, 0, stream>>>(params->W_self, w_in, w_out, WsT);
+        SG_LAUNCH_CHECK();
+        PairArgs a;
+        a.A1 = G; a.lda1 = ldp;
+        a.A2 = params->W_self ? dHout : nullptr; a.lda2 = ldo;
+        a.B1 = WaT; a.B2 = params->W_self ? WsT : nullptr;
+        a.bias1 = a.bias2 = nullptr;
+        a.O1 = dHin; a.ldo1 = ldgi; a.O2 = nullptr; a.ldo2 = 0;
+        a.mask = nullptr; a.mask_words = 0;
+        a.n = n; a.K = w_out; a.Nout = w_in; a.ldw = w_in; a.act = SLICEGCN_ACT_NONE;
+        if (int rc = launch_pair<false>(a, stream)) return rc;
+    }
+    return SLICEGCN_OK;
+}
+
 extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_desc *desc,
                                   const slicegcn_layer_params *params, const float *Hin, int64_t ldi,
-                                  float *Hout, int64_t ldo, slicegcn_layer_saved *saved, void *stream_)
+                                  float *Hout, int64_t ldo, slicegcn_layer_saved *saved, void *ws, size_t ws_bytes,
+                                  void *stream_)
 {
     if (int rc = check_layer(g, desc, params, "layer_fwd")) return rc;
     SG_REQUIRE(Hin && Hout, SLICEGCN_EINVAL, "layer_fwd: NULL Hin or Hout");
     SG_REQUIRE(ldi >= desc->w_in && ldo >= desc->w_out, SLICEGCN_EINVAL, "layer_fwd: leading dimension too small");
     if (int rc = check_saved(desc, saved, "layer_fwd")) return rc;
     hipStream_t stream = as_stream(stream_);
+    if (transform_first(desc)) return layer_fwd_transform_first(g, desc, params, Hin, ldi, Hout, ldo, saved, ws, ws_bytes, stream);
 
     if (!(desc->flags & SLICEGCN_LAYER_Z_VALID))
-        if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, stream)) return rc;
+        if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, ws, ws_bytes, stream)) return rc;
 
     PairArgs a;
     a.A1 = saved->Z; a.lda1 = saved->ldz;
@@ -1642,12 +1619,30 @@ extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_
     return launch_pair<false>(a, stream);
 }
 
-extern "C" size_t slicegcn_layer_bwd_workspace_bytes(int64_t n_nodes, const slicegcn_layer_desc *desc, int need_dHin)
+extern "C" size_t slicegcn_layer_fwd_workspace_bytes(const slicegcn_graph *g, const slicegcn_layer_desc *desc)
 {
-    if (!desc || n_nodes < 1 || desc->w_in < 1 || desc->w_out < 1) return 0;
+    if (!g || !desc || desc->w_in < 1 || desc->w_out < 1) return 0;
+    if (transform_first(desc)) return 2 * tf_mat_bytes(g->n, desc->w_out) + spmm_workspace_bytes(g->fwd, desc->w_out);
+    return spmm_workspace_bytes(g->fwd, desc->w_in);
+}
+
+// layout of the backward workspace: [partial weight gradients | dZ (only with dHin) | aggregation workspace (only with dHin)]
+static size_t bwd_partial_bytes(int64_t n, const slicegcn_layer_desc *desc)
+{
     const size_t stride = 2 * (size_t)desc->w_in * desc->w_out + 2 * (size_t)desc->w_out;
-    size_t bytes = (size_t)round_up((int64_t)(layer_grad_blocks(n_nodes, desc->w_in, desc->w_out) * stride * sizeof(float)), 256);
-    if (need_dHin) bytes += (size_t)round_up(n_nodes * round_up(desc->w_in, 32) * (int64_t)sizeof(float), 256);
+    return (size_t)round_up((int64_t)(layer_grad_blocks(n, desc->w_in, desc->w_out) * stride * sizeof(float)), 256);
+}
+static size_t bwd_dz_bytes(int64_t n, const slicegcn_layer_desc *desc)
+{
+    return (size_t)round_up(n * round_up(desc->w_in, 32) * (int64_t)sizeof(float), 256);
+}
+
+extern "C" size_t slicegcn_layer_bwd_workspace_bytes(const slicegcn_graph *g, const slicegcn_layer_desc *desc, int need_dHin)
+{
+    if (!g || !desc || desc->w_in < 1 || desc->w_out < 1) return 0;
+    if (transform_first(desc)) return tf_bwd_bytes(g, desc);
+    size_t bytes = bwd_partial_bytes(g->n, desc);
+    if (need_dHin) bytes += bwd_dz_bytes(g->n, desc) + spmm_workspace_bytes(g->tr, desc->w_in);
     return bytes;
 }
 
@@ -1662,13 +1657,14 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
     SG_REQUIRE(ldi >= desc->w_in && ldo >= desc->w_out, SLICEGCN_EINVAL, "layer_bwd: leading dimension too small");
     SG_REQUIRE(dHin == nullptr || ldgi >= desc->w_in, SLICEGCN_EINVAL, "layer_bwd: ldgi < w_in");
     if (int rc = check_saved(desc, saved, "layer_bwd")) return rc;
-    const size_t need = slicegcn_layer_bwd_workspace_bytes(g->n, desc, dHin != nullptr);
+    const size_t need = slicegcn_layer_bwd_workspace_bytes(g, desc, dHin != nullptr);
     SG_REQUIRE(ws != nullptr && ws_bytes >= need, SLICEGCN_EWORKSPACE, "layer_bwd: workspace of %zu bytes, %zu needed",
                ws_bytes, need);
     SG_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255u) == 0, SLICEGCN_EINVAL, "layer_bwd: workspace not 256-byte aligned");
     hipStream_t stream = as_stream(stream_);
     const uint32_t *mask = desc->act == SLICEGCN_ACT_RELU ? saved->mask : nullptr;
     const int w_in = desc->w_in, w_out = desc->w_out;
+    if (transform_first(desc)) return layer_bwd_transform_first(g, desc, params, Hin, ldi, mask, saved->mask_words, dHout, ldo, dHin, ldgi, grads, ws, stream);
 
     // ---- parameter gradients: per-row-block partial sums, then an fp64 combination ----
     float *partial = static_cast<float *>(ws);
@@ -1685,14 +1681,14 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.rows_per_block = layer_grad_rows(g->n, w_in, w_out);
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
         int64_t n_partials = nb;
-        if (use_mfma() && w_in <= 32 && w_out <= 32 && g->n >= 65536) {
+        if (w_in <= 32 && w_out <= 32 && g->n >= 65536) {
             // one partial per wavefront, at most as many as the workspace has rows (nb) and as fill the chip
             int64_t waves = nb < 8192 ? nb : 8192;
             const int64_t n_strips = (g->n + 31) / 32;
             if (waves > n_strips) waves = n_strips;
             n_partials = waves;
             grad_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, waves);
-        } else if (use_mfma() && w_in <= 64 && w_out <= 64 && g->n >= ((int64_t)1 << 21) && !getenv("SLICEGCN_NO_STRIP64")) {
+        } else if (w_in <= 64 && w_out <= 64 && g->n >= ((int64_t)1 << 21)) {
             // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
             const int64_t resident = 3072;
             int64_t waves = nb >= resident ? nb / resident * resident : nb >= 2048 ? 2048 : nb;
@@ -1703,10 +1699,8 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
             if (w_in <= 32) grad_strip64_kernel<1, 2, 8, 3><<<gb, 256, 0, stream>>>(r, waves);
             else if (w_out <= 32) grad_strip64_kernel<2, 1, 8, 3><<<gb, 256, 0, stream>>>(r, waves);
             else grad_strip64_kernel<2, 2, 8, 2><<<gb, 256, 0, stream>>>(r, waves);
-        } else if (use_mfma()) {
-            grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
         } else {
-            grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
+            grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
         }
         SG_LAUNCH_CHECK();
         FinalDst dst;
@@ -1723,8 +1717,10 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
     // ---- input gradient: dHin = A^^T (dP W_agg^T) + dHout W_self^T ----
     if (dHin) {
         const int64_t ldz = round_up(w_in, 32); // rows of the gathered operand start on 128-byte boundaries
-        float *dZ = reinterpret_cast<float *>(static_cast<char *>(ws) +
-                                              round_up((int64_t)(nb * stride * sizeof(float)), 256));
+        char *after_partials = static_cast<char *>(ws) + bwd_partial_bytes(g->n, desc);
+        float *dZ = reinterpret_cast<float *>(after_partials);
+        void *agg_ws = after_partials + bwd_dz_bytes(g->n, desc);
+        const size_t agg_ws_bytes = spmm_workspace_bytes(g->tr, w_in);
         PairArgs a;
         a.A1 = dHout; a.lda1 = ldo;
         a.A2 = params->W_self ? dHout : nullptr; a.lda2 = ldo;
@@ -1739,17 +1735,13 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
             if (int rc = launch_pair<true>(a, stream)) return rc;
         }
         // padding columns of dZ are never read as data: the aggregation masks them on store
-        if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, stream)) return rc;
+        if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, agg_ws, agg_ws_bytes, stream))
+            return rc;
     }
     return SLICEGCN_OK;
 }
 
 // ---- dense layer Y = act(X W + b): the unit of the paper's classifier MLP_CLS and of MLP_FF ----
-static size_t linear_partial_bytes(int64_t n, int32_t w_in, int32_t w_out)
-{
-    const size_t stride = (size_t)w_in * w_out + (size_t)w_out;
-    return (size_t)round_up((int64_t)(red_blocks(n) * stride * sizeof(float)), 256);
-}
 
 extern "C" int slicegcn_linear_fwd(const float *X, int64_t ldx, int64_t n, int32_t w_in, int32_t w_out, const float *W,
                                    const float *b, int32_t act, float *Y, int64_t ldy, uint32_t *mask, int64_t mask_words,
@@ -1799,28 +1791,7 @@ extern "C" int slicegcn_linear_bwd(const float *X, int64_t ldx, int64_t n, int32
                    ws_bytes, need);
         SG_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255u) == 0, SLICEGCN_EINVAL, "linear_bwd: workspace not 256-byte aligned");
         ProfScope prof(SLICEGCN_PROF_LINEAR_GRAD, w_out, stream);
-        const int64_t nb = red_blocks(n);
-        const int ww = w_in * w_out;
-        const int32_t stride = ww + w_out;
-        ReduceArgs r;
-        r.Z = X; r.ldz = ldx; r.Hin = nullptr; r.ldi = 0; r.dHout = dY; r.ldo = lddy;
-        r.mask = m; r.mask_words = mask_words;
-        r.partial = static_cast<float *>(ws); r.n = n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 1;
-        dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
-        if (use_mfma() && (w_in > 64 || w_out > 64)) { // wide layer: 128 x 128 output tiles
-            dim3 big((unsigned)nb, (unsigned)((w_in + GB_T - 1) / GB_T), (unsigned)((w_out + GB_T - 1) / GB_T));
-            grad_big_mfma_kernel<<<big, 256, 0, stream>>>(r);
-        } else if (use_mfma()) {
-            grad_partial_mfma_kernel<<<grid, 256, 0, stream>>>(r);
-        } else {
-            grad_partial_kernel<<<grid, 256, 0, stream>>>(r);
-        }
-        SG_LAUNCH_CHECK();
-        FinalDst dst;
-        dst.ptr[0] = dW; dst.ptr[1] = db; dst.ptr[2] = dst.ptr[3] = nullptr;
-        dst.begin[0] = 0; dst.begin[1] = ww; dst.begin[2] = dst.begin[3] = dst.begin[4] = stride;
-        reduce_final_kernel<<<(unsigned)((stride + 31) / 32), 1024, 0, stream>>>(r.partial, nb, stride, stride, dst);
-        SG_LAUNCH_CHECK();
+        if (int rc = launch_linear_grads(X, ldx, n, w_in, w_out, m, mask_words, dY, lddy, dW, db, ws, stream)) return rc;
     }
     if (dX) {
         PairArgs a;

@@ -18,8 +18,10 @@ constexpr int CE_LPR = 16;                // lanes per row
 constexpr int CE_ROWS = 256 / CE_LPR;     // rows per workgroup pass
 constexpr int CE_ROWS_PER_BLOCK = 4 * CE_ROWS; // each group handles four rows
 
-__global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict__ logits, int64_t ld, int64_t n, int32_t c,
-                                                         const int32_t *__restrict__ labels, float *__restrict__ dlogits,
+// logits and dlogits may be the same buffer (gradient in place), so neither is declared restrict: every
+// read of a row element, the label's logit included, precedes in program order the store that replaces it.
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const float *logits, int64_t ld, int64_t n, int32_t c,
+                                                         const int32_t *__restrict__ labels, float *dlogits,
                                                          int64_t ldd, double *__restrict__ partial)
 {
     __shared__ double row_loss[CE_ROWS_PER_BLOCK];

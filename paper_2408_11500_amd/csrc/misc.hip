@@ -4,6 +4,7 @@
 
 #include <cmath>
 
+#include <algorithm>
 #include <cstdarg>
 #include <map>
 #include <mutex>
@@ -30,6 +31,17 @@ struct ProfRecord { int kind, width; hipEvent_t start, stop; bool closed; };
 std::mutex g_prof_mutex;
 bool g_prof_on = false;
 std::vector<ProfRecord> g_prof;
+std::vector<hipEvent_t> g_prof_pool; // events created ahead of time by slicegcn_profile_reserve
+
+bool take_event(hipEvent_t *e)
+{
+    if (!g_prof_pool.empty()) {
+        *e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return true;
+    }
+    return hipEventCreate(e) == hipSuccess;
+}
 } // namespace
 
 ProfScope::ProfScope(int kind, int width, hipStream_t stream) : slot_(-1), stream_(stream)
@@ -37,8 +49,8 @@ ProfScope::ProfScope(int kind, int width, hipStream_t stream) : slot_(-1), strea
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (!g_prof_on) return;
     ProfRecord r{kind, width, nullptr, nullptr, false};
-    if (hipEventCreate(&r.start) != hipSuccess) return;
-    if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+    if (!take_event(&r.start)) return;
+    if (!take_event(&r.stop)) { (void)hipEventDestroy(r.start); return; }
     (void)hipEventRecord(r.start, stream);
     g_prof.push_back(r);
     slot_ = (int)g_prof.size() - 1;
@@ -57,8 +69,9 @@ ProfScope::~ProfScope()
 namespace {
 
 // dst[r, c] = src[r, c] (+ e[c]) for c < w, 0 for w <= c < w_pad.  One thread per element of
-// the padded destination row, rows strided over the grid.
-__global__ __launch_bounds__(256) void copy_cols_kernel(const float *__restrict__ src, int64_t lds_, float *__restrict__ dst,
+// the padded destination row, rows strided over the grid.  src and dst may be the same view (slice
+// encoding in place), so they are not declared restrict: a thread reads only the element it writes.
+__global__ __launch_bounds__(256) void copy_cols_kernel(const float *src, int64_t lds_, float *dst,
                                                         int64_t ldd, int64_t n, int32_t w, int32_t w_pad,
                                                         const float *__restrict__ e)
 {
@@ -76,7 +89,7 @@ __global__ __launch_bounds__(256) void copy_cols_kernel(const float *__restrict_
 }
 
 // Same copy, 16 bytes per thread: needs aligned bases, leading dimensions, w and w_pad all multiples of 4.
-__global__ __launch_bounds__(256) void copy_cols_vec_kernel(const float *__restrict__ src, int64_t lds_, float *__restrict__ dst,
+__global__ __launch_bounds__(256) void copy_cols_vec_kernel(const float *src, int64_t lds_, float *dst,
                                                             int64_t ldd, int64_t n, int32_t w, int32_t w_pad,
                                                             const float *__restrict__ e)
 {
@@ -312,9 +325,21 @@ extern "C" int slicegcn_concat_bwd(int32_t k, const float *dH, int64_t ldh, int6
 extern "C" int slicegcn_profile_begin(void)
 {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    for (auto &r : g_prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (auto &r : g_prof) { g_prof_pool.push_back(r.start); g_prof_pool.push_back(r.stop); }
     g_prof.clear();
     g_prof_on = true;
+    return SLICEGCN_OK;
+}
+
+extern "C" int slicegcn_profile_reserve(int32_t scopes)
+{
+    SG_REQUIRE(scopes >= 0, SLICEGCN_EINVAL, "profile_reserve: negative count");
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    while ((int64_t)g_prof_pool.size() < 2 * (int64_t)scopes) {
+        hipEvent_t e;
+        SG_HIP(hipEventCreate(&e));
+        g_prof_pool.push_back(e);
+    }
     return SLICEGCN_OK;
 }
 
@@ -324,7 +349,7 @@ extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t cap
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_prof_on = false;
     SG_HIP(hipDeviceSynchronize());
-    struct Acc { int64_t launches = 0; double total = 0.0, lo = 0.0, hi = 0.0; };
+    struct Acc { int64_t launches = 0; double total = 0.0, lo = 0.0, hi = 0.0; std::vector<float> all; };
     std::map<std::pair<int, int>, Acc> sum;
     for (auto &r : g_prof) {
         float ms = 0.f;
@@ -334,9 +359,10 @@ extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t cap
             if (e.launches == 0 || ms > e.hi) e.hi = ms;
             e.launches += 1;
             e.total += (double)ms;
+            e.all.push_back(ms);
         }
-        (void)hipEventDestroy(r.start);
-        (void)hipEventDestroy(r.stop);
+        g_prof_pool.push_back(r.start); // kept for the next profiled region
+        g_prof_pool.push_back(r.stop);
     }
     g_prof.clear();
     int32_t i = 0;
@@ -348,6 +374,10 @@ extern "C" int slicegcn_profile_end(slicegcn_profile_entry *entries, int32_t cap
             entries[i].total_ms = kv.second.total;
             entries[i].min_ms = kv.second.lo;
             entries[i].max_ms = kv.second.hi;
+            std::vector<float> &v = kv.second.all;
+            std::sort(v.begin(), v.end());
+            const size_t h = v.size() / 2;
+            entries[i].median_ms = v.empty() ? 0.0 : (v.size() % 2 ? (double)v[h] : 0.5 * ((double)v[h - 1] + (double)v[h]));
         }
         ++i;
     }

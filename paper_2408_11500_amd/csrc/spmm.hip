@@ -25,15 +25,10 @@
 // loads, else 1), lane `sub` of a group owns columns [V*sub, V*sub + V) of the current column
 // pass; wider operands take several passes.
 //
-// Environment (diagnostics / tuning, read once): SLICEGCN_SPMM_SCHEDULE=rowsplit|xcd forces the
-// single-class or the 8-class schedule; SLICEGCN_PART_ROW=<d> sets the row length above which rows
-// are cut by column class when a graph is built; SLICEGCN_PASS_COLS=<c> narrows the column passes of
-// the 16-byte path (default 128); SLICEGCN_ITEM_MAX=32|64 fixes the longest lane-group item when a graph
-// is built (default: by working-set size); SLICEGCN_SPMM_SEPARATE=1 keeps the three item kernels as
-// separate launches for small graphs too; SLICEGCN_VERBOSE=1 prints schedule statistics.
+// The partial sums of rows with several items live in a workspace the caller passes in (its size comes
+// from spmm_workspace_bytes), so a graph handle is read-only here and calls on different streams
+// only have to use different workspaces.
 #include "common.h"
-
-#include <cstdlib>
 
 namespace slicegcn {
 
@@ -45,6 +40,7 @@ struct SpmmArgs {
     const float *vals;
     const Segment *items;
     const FixRow *fix;
+    const int32_t *order; // row at every position of the schedule (NULL: natural order), for the short rows
     const float *X;
     float *Y;
     const float *Add;
@@ -408,7 +404,8 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
     }
 }
 
-// Rows of at most TINY_ROW entries, 64 consecutive rows per wavefront in natural order.
+// Rows of at most TINY_ROW entries, 64 consecutive positions of the schedule per wavefront (consecutive
+// rows in natural order).
 template <int LPR, int V, bool S32>
 __device__ __forceinline__ void tiny_rows_body(const SpmmArgs &a, int block)
 {
@@ -418,7 +415,7 @@ __device__ __forceinline__ void tiny_rows_body(const SpmmArgs &a, int block)
     if (first >= a.n) return; // uniform per wavefront
     int beg_l = 0, end_l = 0, row_l = 0, dst_l = NO_UNIT;
     if (lane < UNITS && first + lane < a.n) {
-        const int row = first + lane;
+        const int row = a.order ? a.order[first + lane] : first + lane;
         const int b = a.rowptr[row], e = a.rowptr[row + 1];
         if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
     }
@@ -483,8 +480,7 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
     const int64_t g2 = (int64_t)a.n_classes * a.small_blocks;
     const int64_t g3 = (a.n + units_per_block - 1) / units_per_block;
     SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX && g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
-    static const bool no_merge = getenv("SLICEGCN_SPMM_SEPARATE") != nullptr;
-    if (a.item_max <= ITEM_SHORT && g1 + g2 + g3 <= INT32_MAX && !no_merge) { // cache-resident graph: one launch
+    if (a.item_max <= ITEM_SHORT && g1 + g2 + g3 <= INT32_MAX) { // cache-resident graph: one launch
         spmm_merged_kernel<LPR, V, S32><<<(unsigned)(g1 + g2 + g3), 256, 0, stream>>>(a, (int)g1, (int)g2);
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
@@ -521,23 +517,21 @@ int launch_pass(const SpmmArgs &a, int lpr, hipStream_t stream)
     }
 }
 
-// SLICEGCN_SPMM_SCHEDULE=rowsplit | xcd forces one schedule (for A/B measurements); default: by width.
-int forced_schedule()
-{
-    static const int v = [] {
-        const char *e = getenv("SLICEGCN_SPMM_SCHEDULE");
-        if (!e) return 0;
-        if (strcmp(e, "rowsplit") == 0) return 1;
-        if (strcmp(e, "xcd") == 0) return 2;
-        return 0;
-    }();
-    return v;
-}
-
 } // namespace
 
+// Bytes of partial-sum workspace an aggregation of `width` columns over pattern `m` may need: the larger
+// of the two schedules (which one runs depends on the operand layout, unknown here), one slot of
+// min(width rounded up to 4, pass width) floats per item of every row cut into several items.
+size_t spmm_workspace_bytes(const Csr &m, int32_t width)
+{
+    const int64_t w4 = round_up(width, 4);
+    const int64_t a = m.wide.n_slots * (w4 < WIDE_SLOT_COLS ? w4 : WIDE_SLOT_COLS);
+    const int64_t b = m.xcd.n_slots * (w4 < XCD_SLOT_COLS ? w4 : XCD_SLOT_COLS);
+    return (size_t)round_up((a > b ? a : b) * (int64_t)sizeof(float), 256);
+}
+
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
-                float *Y, int64_t ldy, const float *Add, int64_t ldadd, hipStream_t stream)
+                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
     const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
@@ -546,15 +540,18 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     // narrower passes re-read the index streams more often, wider ones make the set of hot rows of
     // the operand too large for the L2s (301 columns: 7.8 / 7.4 / 7.7 ms for passes of 64 / 128 / 256);
     // the scalar path keeps the single-class schedule
-    const int forced = forced_schedule();
-    const bool use_xcd = forced ? forced == 2 : vec_load;
+    const bool use_xcd = vec_load;
     const Schedule &sc = use_xcd ? m.xcd : m.wide;
     const int slot_cols = use_xcd ? XCD_SLOT_COLS : WIDE_SLOT_COLS;
-    SG_REQUIRE(sc.n_slots == 0 || (g->scratch != nullptr && sc.n_slots * slot_cols <= g->scratch_floats), SLICEGCN_EINVAL,
-               "spmm: graph handle has no scratch buffer for this schedule");
+    const int64_t used_cols = width < slot_cols ? round_up(width, 4) : slot_cols; // one pass: slots packed densely
+    const size_t need = (size_t)(sc.n_slots * used_cols) * sizeof(float);
+    SG_REQUIRE(need == 0 || (ws != nullptr && ws_bytes >= need), SLICEGCN_EWORKSPACE,
+               "aggregation: workspace of %zu bytes, %zu needed", ws_bytes, need);
+    SG_REQUIRE(need == 0 || (reinterpret_cast<uintptr_t>(ws) & 255u) == 0, SLICEGCN_EINVAL,
+               "aggregation: workspace not 256-byte aligned");
     SpmmArgs a;
-    a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.items = sc.items; a.fix = sc.fix;
-    a.X = X; a.Y = Y; a.Add = Add; a.scratch = g->scratch;
+    a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.items = sc.items; a.fix = sc.fix; a.order = g->order;
+    a.X = X; a.Y = Y; a.Add = Add; a.scratch = static_cast<float *>(ws);
     a.ldx = ldx; a.ldy = ldy; a.ldadd = Add ? ldadd : 0;
     const bool s32 = g->n < (1 << 24) && ldx * 4 < (1 << 24) && (int64_t)g->n * ldx * 4 < ((int64_t)1 << 32);
     a.ldx_bytes = s32 ? (uint32_t)(ldx * 4) : 0u;
@@ -578,10 +575,8 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     SG_REQUIRE(big_blocks * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
     a.big_blocks = (int32_t)big_blocks;
     ProfScope prof(Add ? SLICEGCN_PROF_SPMM_ADD : SLICEGCN_PROF_SPMM, width, stream);
-    int pass_cols = vec_load ? slot_cols : 64;
-    if (pass_cols > 256) pass_cols = 256;
-    if (const char *e = getenv("SLICEGCN_PASS_COLS")) { const int v = atoi(e); if (v >= 4 && v <= pass_cols && v % 4 == 0) pass_cols = v; }
-    if (width < pass_cols) a.slot_cols = (int32_t)round_up(width, 4); // one pass: pack the slots densely
+    const int pass_cols = vec_load ? slot_cols : 64;
+    a.slot_cols = (int32_t)used_cols;
     for (int32_t c0 = 0; c0 < width; c0 += pass_cols) {
         a.col0 = c0;
         a.col_end = width < c0 + pass_cols ? width : c0 + pass_cols;
@@ -611,11 +606,17 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
 
 using namespace slicegcn;
 
+extern "C" size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int transpose, int32_t width)
+{
+    if (!g || width < 1) return 0;
+    return spmm_workspace_bytes(transpose ? g->tr : g->fwd, width);
+}
+
 extern "C" int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
-                                   int32_t width, float *Y, int64_t ldy, void *stream)
+                                   int32_t width, float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
 {
     SG_REQUIRE(g && X && Y, SLICEGCN_EINVAL, "spmm_slice: NULL argument");
     SG_REQUIRE(width >= 1, SLICEGCN_EINVAL, "spmm_slice: width = %d < 1", width);
     SG_REQUIRE(ldx >= width && ldy >= width, SLICEGCN_EINVAL, "spmm_slice: leading dimension smaller than width");
-    return launch_spmm(g, transpose ? g->tr : g->fwd, X, ldx, width, Y, ldy, nullptr, 0, as_stream(stream));
+    return launch_spmm(g, transpose ? g->tr : g->fwd, X, ldx, width, Y, ldy, nullptr, 0, ws, ws_bytes, as_stream(stream));
 }

@@ -21,19 +21,23 @@ class SliceStack:
     def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
                  device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU,
                  shared_input: torch.Tensor | None = None, cache_first_aggregation: bool = False,
-                 fuse_encoding: bool = True):
+                 fuse_encoding: bool = True, order: int = 0):
         """``shared_input``: with feature fusion every slice model reads the same fused n x first_width
-        matrix; the stack then also returns the gradient with respect to it (``dXin``)."""
+        matrix; the stack then also returns the gradient with respect to it (``dXin``).
+        ``order``: 0 (aggregate first), LAYER_TRANSFORM_FIRST or LAYER_ORDER_AUTO, applied to every layer."""
         self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
         self.w0, self.hs = first_width, slice_hidden
         self.dev = torch.device(device)
         self.act_last = act_last
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.widths = [(first_width if l == 0 else slice_hidden, slice_hidden) for l in range(layers)]
+        self.order = order
+        # layers that run in the transform-first order keep no aggregation of their input
+        self.tf = [order == B.LAYER_TRANSFORM_FIRST or (order == B.LAYER_ORDER_AUTO and wo < wi) for wi, wo in self.widths]
         # inputs
         # with direct slicing the first layer aggregates constant features: A^ X_s can be kept across passes
         # (the paper's implementation recomputes it; off by default so that a pass measures every kernel)
-        self.cache_first = cache_first_aggregation and shared_input is None
+        self.cache_first = cache_first_aggregation and shared_input is None and not self.tf[0]
         self.first_valid = [False] * k
         self.shared = shared_input is not None
         self.X = ([shared_input] * k if self.shared
@@ -47,7 +51,8 @@ class SliceStack:
         self.dE = torch.zeros((k, slice_hidden), **f32) if slice_encoding else None
         # activations kept for the backward pass
         self.H = [[torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(layers - 1)] for _ in range(k)]
-        self.Z = [[torch.empty((n_nodes, padded_ld(wi)), **f32) for (wi, _) in self.widths] for _ in range(k)]
+        self.Z = [[None if self.tf[l] else torch.empty((n_nodes, padded_ld(wi)), **f32) for l, (wi, _) in enumerate(self.widths)]
+                  for _ in range(k)]
         mw = (slice_hidden + 31) // 32
         self.mask = [[torch.zeros((n_nodes, mw), dtype=torch.int32, device=self.dev) for _ in range(layers)] for _ in range(k)]
         self.Hcat = torch.empty((n_nodes, k * slice_hidden), **f32)
@@ -60,7 +65,8 @@ class SliceStack:
         self.dbuf = [torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
         ws = 0
         for l, (wi, wo) in enumerate(self.widths):
-            ws = max(ws, B.slicegcn_layer_bwd_workspace_bytes(n_nodes, wi, wo, l > 0 or self.shared))
+            ws = max(ws, B.slicegcn_layer_fwd_workspace_bytes(graph, wi, wo, order),
+                     B.slicegcn_layer_bwd_workspace_bytes(graph, wi, wo, l > 0 or self.shared, order))
         ws = max(ws, B.slicegcn_concat_bwd_workspace_bytes(n_nodes, [slice_hidden] * k))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
@@ -100,6 +106,9 @@ class SliceStack:
             return self.Hcat[:, i * self.hs:(i + 1) * self.hs]
         return self.H[i][l][:, :self.hs]
 
+    def zbuf(self, i: int, l: int):
+        return None if self.tf[l] else self.Z[i][l][:, :self.widths[l][0]]
+
     def act(self, l: int) -> int:
         return self.act_last if l == self.L - 1 else B.ACT_RELU
 
@@ -120,8 +129,8 @@ class SliceStack:
                 B.slicegcn_slice_feature(p["b_self"].view(1, -1), 0, self.hs, b_self.view(1, -1))
                 B.slicegcn_accumulate(b_self.view(1, -1), self.E[i].view(1, -1))
             B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], b_self, self.hout(i, l),
-                                 self.Z[i][l][:, :wi], self.mask[i][l], act=self.act(l),
-                                 z_valid=l == 0 and self.cache_first and self.first_valid[i])
+                                 self.zbuf(i, l), self.mask[i][l], act=self.act(l),
+                                 z_valid=l == 0 and self.cache_first and self.first_valid[i], ws=self.ws, order=self.order)
         self.first_valid[i] = True
 
     def forward(self) -> torch.Tensor:
@@ -147,9 +156,9 @@ class SliceStack:
                     g_in = (self.dXin if i == 0 else self.dXtmp)[:, :wi]
                 else:
                     g_in = None  # raw features need no gradient
-                B.slicegcn_layer_bwd(self.g, self.hin(i, l), p["W_agg"], p["W_self"], self.Z[i][l][:, :wi], self.mask[i][l],
+                B.slicegcn_layer_bwd(self.g, self.hin(i, l), p["W_agg"], p["W_self"], self.zbuf(i, l), self.mask[i][l],
                                      g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws,
-                                     act=self.act(l))
+                                     act=self.act(l), order=self.order)
                 if l == 0 and self.shared and i > 0:
                     B.slicegcn_accumulate(self.dXin[:, :wi], g_in)
                 if fused and l == self.L - 1:  # dE[i] = column sums of dH^i = this layer's db_self

@@ -28,7 +28,7 @@ class Workload:
     hidden: int         # total hidden width H (per slice: H // k)
     layers: int
     classes: int
-    kind: str           # "er" | "rmat"
+    kind: str           # "er" | "rmat" | "comm" (planted communities: m_und is then an upper bound)
 
     @property
     def seed(self) -> int:
@@ -47,18 +47,34 @@ class Workload:
         return self.hidden // self.k
 
 
+COMM_SIZE, COMM_D_IN, COMM_D_OUT = 512, 24, 2
+
 WORKLOADS = {
     "cfg1": Workload("cfg1", 1, 2_048, 4_096, 128, 2, 64, 2, 8, "er"),
     "cfg2": Workload("cfg2", 2, 169_343, 1_185_401, 128, 4, 256, 3, 40, "rmat"),
     "cfg3": Workload("cfg3", 3, 232_965, 57_000_000, 602, 2, 256, 2, 41, "rmat"),
     "cfg4": Workload("cfg4", 4, 2_449_029, 62_000_000, 100, 4, 256, 3, 47, "rmat"),
     "cfg5": Workload("cfg5", 5, 10_000_000, 150_000_000, 256, 8, 256, 3, 64, "rmat"),
+    # not one of the five benchmark workloads: 2 M nodes in planted communities of 512, scattered over the index
+    # range by the random relabelling -- the input on which a locality-restoring row order can be measured
+    "comm": Workload("comm", 6, 2_000_000, 2_000_000 * (COMM_D_IN + COMM_D_OUT), 128, 4, 128, 2, 16, "comm"),
 }
+
+
+def get_workload(name: str) -> Workload:
+    """A named workload, or ``er:<n_nodes>:<m_und>``: a uniform random graph with one 32-wide slice (used to
+    measure what the aggregation's row gathers cost as a function of the size of the gathered matrix)."""
+    if name.startswith("er:"):
+        _, n, m = name.split(":")
+        return Workload(name, 100, int(n), int(m), 32, 1, 32, 1, 2, "er")
+    return WORKLOADS[name]
 
 
 def edges(w: Workload, device="cpu", permute: bool = True):
     if w.kind == "er":
         return graphs.erdos_renyi(w.n_nodes, w.m_und, w.seed, device=device, permute=permute)
+    if w.kind == "comm":
+        return graphs.planted_communities(w.n_nodes, COMM_SIZE, COMM_D_IN, COMM_D_OUT, w.seed, device=device, permute=permute)
     return graphs.rmat(w.n_nodes, w.m_und, w.seed, device=device, permute=permute)
 
 

@@ -1,4 +1,4 @@
-"""Seeded synthetic graphs: G(n, M) Erdos-Renyi and R-MAT edge lists.
+"""Seeded synthetic graphs: G(n, M) Erdos-Renyi, R-MAT and planted-community edge lists.
 
 Both return ``M_und`` distinct undirected edges (u != v) as two int64 tensors
 (src, dst), in order of first occurrence in the counter-indexed stream of draws, so the
@@ -94,3 +94,22 @@ def rmat(n_nodes: int, m_und: int, seed: int, a=0.57, b=0.19, c=0.19, d=0.05,
         batch = max(1024, min(int(m_und * 1.3), 1 << 26))
     lo, hi = _first_distinct(draw, n_nodes, m_und, device, batch=batch)
     return _permute(lo, hi, n_nodes, seed) if permute else (lo, hi)
+
+
+def planted_communities(n_nodes: int, community: int, d_in: int, d_out: int, seed: int, device="cpu", permute: bool = True):
+    """Planted communities (a stochastic block model with equal blocks): vertex v of block v // community
+    draws ``d_in`` neighbours uniformly inside its block and ``d_out`` uniformly over the whole graph.  Returns
+    the n_nodes * (d_in + d_out) drawn pairs as they come (repeats and self pairs included: the adjacency
+    builder collapses them), so the number of distinct edges is a little below that.  With ``permute`` the
+    vertices are relabelled by a seeded random permutation: the communities are then scattered over the index
+    range, which is the situation a locality-restoring row order has to undo.  (R-MAT has no such structure.)"""
+    per = d_in + d_out
+    idx = rng.arange64(n_nodes * per, device)
+    v = idx // per
+    j = idx % per
+    block = v // community
+    size = torch.clamp(n_nodes - block * community, max=community)   # the last block may be short
+    u_in = block * community + (rng.uniform(seed, STREAM_EDGES, idx) * size).to(torch.int64)
+    u_out = (rng.uniform(seed, STREAM_EDGES, idx) * n_nodes).to(torch.int64)
+    u = torch.where(j < d_in, u_in, u_out)
+    return _permute(v, u, n_nodes, seed) if permute else (v, u)

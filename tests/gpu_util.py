@@ -1,8 +1,27 @@
 """Helpers shared by the GPU parity tests (comparison metrics and small fixtures)."""
+import os
+import time
+
 import numpy as np
 import torch
 
 TOL = 1e-4  # max relative error for fp32 outputs and gradients
+
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def progress(msg: str):
+    """A progress line of a long test: printed, and appended to gpurun_out/test_progress.log when that folder
+    exists (pytest holds printed output back until the test ends; a run that stays silent for minutes looks hung)."""
+    line = f"[{time.strftime('%H:%M:%S')}] {msg}"
+    print(line, flush=True)
+    d = os.path.join(_ROOT, "gpurun_out")
+    if os.path.isdir(d):
+        try:
+            with open(os.path.join(d, "test_progress.log"), "a") as f:
+                f.write(line + "\n")
+        except OSError:
+            pass
 
 
 def rel_err(got, want) -> float:

@@ -29,7 +29,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_symbols()
-    assert len(names) == 24 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 27 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(L, n) is not None
 
@@ -61,13 +61,15 @@ def test_null_and_size_errors_return_codes(L):
     h = ctypes.c_void_p(0)
     assert L.slicegcn_build_norm_csr(None, None, 0, 0, 3, None, ctypes.byref(h)) == binding.EINVAL      # n_nodes < 1
     assert L.slicegcn_build_norm_csr(None, None, 5, 10, 3, None, ctypes.byref(h)) == binding.EINVAL     # NULL edges
-    assert L.slicegcn_build_norm_csr(None, None, 0, 10, 8, None, ctypes.byref(h)) == binding.EINVAL     # unknown flag
+    assert L.slicegcn_build_norm_csr(None, None, 0, 10, 1 << 20, None, ctypes.byref(h)) == binding.EINVAL  # unknown flag
+    assert L.slicegcn_build_norm_csr(None, None, 0, 10, 3 | 16 | 32, None, ctypes.byref(h)) == binding.EINVAL  # both item limits
     assert L.slicegcn_build_norm_csr(None, None, 0, 1 << 31, 3, None, ctypes.byref(h)) == binding.ERANGE
     assert L.slicegcn_build_norm_csr(None, None, 0, 10, 3, None, None) == binding.EINVAL
-    assert L.slicegcn_spmm_slice(None, 0, None, 4, 4, None, 4, None) == binding.EINVAL
+    assert L.slicegcn_spmm_slice(None, 0, None, 4, 4, None, 4, None, 0, None) == binding.EINVAL
+    assert L.slicegcn_spmm_workspace_bytes(None, 0, 32) == 0 and L.slicegcn_layer_fwd_workspace_bytes(None, None) == 0
     assert L.slicegcn_slice_feature(None, 4, 4, 0, 2, None, 2, None) == binding.EINVAL
     assert L.slicegcn_graph_destroy(None) == binding.OK
-    assert L.slicegcn_layer_bwd_workspace_bytes(0, None, 1) == 0
+    assert L.slicegcn_layer_bwd_workspace_bytes(None, None, 1) == 0
     assert b"NULL" in L.slicegcn_last_error()
     assert L.slicegcn_strerror(binding.EWORKSPACE) == b"workspace missing or too small"
     assert L.slicegcn_strerror(-99) == b"unknown status"
@@ -92,13 +94,3 @@ def test_widened_entry_points_validate_before_device_work(L):
     assert L.slicegcn_adam_step(None, None, None, None, 4, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == binding.EINVAL
     assert L.slicegcn_adam_step(one, one, one, one, 4, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, None) == binding.EINVAL  # step < 1
     assert L.slicegcn_adam_step(one, one, one, one, 4, 1e-3, 1.0, 0.999, 1e-8, 0.0, 1, None) == binding.EINVAL  # beta1 = 1
-
-
-def test_workspace_formula(L):
-    # partial sums: one per block of 1024 rows (256 rows while that leaves the tiled kernel under 2048
-    # workgroups, as here) x (2*w_in*w_out + 2*w_out) floats, 256-byte rounded,
-    # plus an n x roundup32(w_in) fp32 staging matrix (rows on 128-byte boundaries) when the input gradient is wanted
-    n, w_in, w_out = 5000, 25, 64
-    part = -(-(20 * (2 * w_in * w_out + 2 * w_out) * 4) // 256) * 256
-    assert binding.slicegcn_layer_bwd_workspace_bytes(n, w_in, w_out, False) == part
-    assert binding.slicegcn_layer_bwd_workspace_bytes(n, w_in, w_out, True) == part + -(-(n * 32 * 4) // 256) * 256

@@ -20,9 +20,10 @@ from gpu_util import (TOL, assert_close, dev, hub_edges, messy_edges, pack_mask,
 pytestmark = pytest.mark.gpu
 
 
-def build_both(src, dst, n, flags=3):
+def build_both(src, dst, n, flags=3, sched=0):
+    """``sched``: schedule-tuning flags for the library only (they do not change the matrix)."""
     o = oracle.build_norm_csr(src, dst, n, flags)
-    g = sg.slicegcn_build_norm_csr(dev(src, torch.int64), dev(dst, torch.int64), n, flags)
+    g = sg.slicegcn_build_norm_csr(dev(src, torch.int64), dev(dst, torch.int64), n, flags | sched)
     return o, g
 
 
@@ -157,6 +158,49 @@ def test_spmm_transpose_and_scalar_path(graphs, case, width):
     assert_close(Y[:, :width].cpu().numpy(), oracle.spmm(o, X, transpose=True), f"spmm^T scalar {case}")
 
 
+@pytest.mark.parametrize("mode", ["degree", "bfs"])
+@pytest.mark.parametrize("case", ["tiny", "ragged", "hubs", "ragged_dir", "communities"])
+def test_row_order_flags(case, mode):
+    """REORDER_DEGREE / REORDER_BFS: the order the library reports equals the oracle's (bit-exact), the CSR arrays
+    are untouched, and aggregation results are bitwise those of the natural order (a row's sum is formed in the
+    same order whichever position the row is visited at), in both directions."""
+    rng = np.random.default_rng(41)
+    if case == "communities":
+        from synth import graphs as sgraphs
+        n = 20000
+        s_, d_ = sgraphs.planted_communities(n, 128, 12, 1, seed=3)
+        src, dst = s_.numpy(), d_.numpy()
+        flags = 3
+    else:
+        name = case.replace("_dir", "")
+        src, dst, n = GRAPH_CASES[name](rng)
+        flags = 2 if case.endswith("_dir") else 3
+    o, g0 = build_both(src, dst, n, flags)
+    o2, g = build_both(src, dst, n, flags, sched=B.REORDER_DEGREE if mode == "degree" else B.REORDER_BFS)
+    check_csr(o, g)
+    want_order = oracle.row_order(o, oracle.ORDER_DEGREE if mode == "degree" else oracle.ORDER_BFS)
+    got_order = g.to_host()["order"]
+    assert g0.to_host()["order"] is None
+    assert np.array_equal(got_order, want_order)
+    for w, tr in ((32, False), (25, True), (100, False)):
+        X = rng.standard_normal((n, w)).astype(np.float32)
+        Xd = padded(X, padded_ld(w))
+        Y0 = torch.empty((n, w), dtype=torch.float32, device="cuda")
+        Y1 = torch.full((n, w), np.nan, dtype=torch.float32, device="cuda")
+        sg.slicegcn_spmm_slice(g0, Xd, Y0, transpose=tr)
+        sg.slicegcn_spmm_slice(g, Xd, Y1, transpose=tr)
+        assert torch.equal(Y0, Y1), f"{case} {mode} w={w} transpose={tr}"
+        assert_close(Y1.cpu().numpy(), oracle.spmm(o, X.astype(np.float64), transpose=tr), f"{case} {mode} w={w}")
+    g0.destroy(); g.destroy()
+
+
+def test_build_rejects_both_orders():
+    src = dev(np.array([0, 1], dtype=np.int64), torch.int64)
+    with pytest.raises(B.SliceGCNError) as e:
+        sg.slicegcn_build_norm_csr(src, src, 4, 3 | B.REORDER_DEGREE | B.REORDER_BFS)
+    assert e.value.status == B.EINVAL
+
+
 def test_spmm_argument_errors(graphs):
     n, o, g = graphs["tiny"]
     X = torch.zeros((n, 8), dtype=torch.float32, device="cuda")
@@ -234,7 +278,7 @@ def test_layer_bwd_vs_oracle(graphs, case, shape, act, has_self, need_dhin):
     dW_agg = torch.empty((w_in, w_out), **f); db = torch.empty(w_out, **f)
     dW_self = torch.empty((w_in, w_out), **f) if has_self else None
     db_self = torch.empty(w_out, **f) if has_self else None
-    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(n, w_in, w_out, need_dhin), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, need_dhin), dtype=torch.uint8, device="cuda")
     sg.slicegcn_layer_bwd(g, Hd, dev(W_agg), dev(W_self) if has_self else None, Zd, maskd, dHd, dHin,
                           dW_agg, db, dW_self, db_self, ws, act=act)
     assert_close(dW_agg.cpu().numpy(), want["dW_agg"], "dW_agg")
@@ -250,6 +294,132 @@ def test_layer_bwd_vs_oracle(graphs, case, shape, act, has_self, need_dhin):
             sg.slicegcn_layer_bwd(g, Hd, dev(W_agg), dev(W_self) if has_self else None, Zd, maskd, dHd, dHin,
                                   dW_agg, db, dW_self, db_self, ws[:ws.numel() - 256], act=act)
         assert e.value.status == B.EWORKSPACE
+
+
+@pytest.mark.parametrize("case", ["ragged", "hubs", "ragged_dir"])
+@pytest.mark.parametrize("shape", [(64, 32), (301, 128), (25, 64), (7, 5), (33, 130), (128, 128)])
+@pytest.mark.parametrize("order,act,has_self,need_dhin", [("tf", 1, True, True), ("tf", 1, True, False), ("tf", 0, False, True),
+                                                          ("auto", 1, True, True)])
+def test_layer_transform_first_vs_oracle(graphs, case, shape, order, act, has_self, need_dhin):
+    """The transform-first order, A^ (Hin W_agg) instead of (A^ Hin) W_agg, forward and backward, against the oracle's
+    layer (which evaluates the layer equation as stated).  No aggregation is kept: Z is NULL.  ORDER_AUTO must pick
+    the transform-first order exactly when w_out < w_in (then it also runs without Z) and the default one otherwise."""
+    n, o, g = graphs[case]
+    w_in, w_out = shape
+    flag = B.LAYER_TRANSFORM_FIRST if order == "tf" else B.LAYER_ORDER_AUTO
+    runs_tf = order == "tf" or w_out < w_in
+    Hin, W_agg, b, W_self, b_self = layer_inputs(n, w_in, w_out, 13 * w_in + w_out, has_self)
+    want, Zo, Po = oracle.layer_fwd(o, Hin, W_agg, b, W_self, b_self, act=act)
+    Hd = padded(Hin, padded_ld(w_in))
+    f = dict(dtype=torch.float32, device="cuda")
+    Hout = torch.full((n, w_out + 3), np.nan, **f)
+    Z = None if runs_tf else torch.empty((n, padded_ld(w_in)), **f)[:, :w_in]
+    mask = torch.full((n, (w_out + 31) // 32), -1, dtype=torch.int32, device="cuda") if act else None
+    Wa, Ws = dev(W_agg), (dev(W_self) if has_self else None)
+    ws = torch.empty(sg.slicegcn_layer_fwd_workspace_bytes(g, w_in, w_out, flag), dtype=torch.uint8, device="cuda")
+    sg.slicegcn_layer_fwd(g, Hd, Wa, dev(b), Ws, dev(b_self) if has_self else None, Hout[:, :w_out], Z, mask, act=act,
+                          ws=ws, order=flag)
+    got = Hout.cpu().numpy()
+    assert_close(got[:, :w_out], want, "Hout")
+    assert np.all(np.isnan(got[:, w_out:]))
+    mask_bits = (Po > 0).astype(np.uint8) if act else np.ones_like(Po, dtype=np.uint8)
+    if act:
+        differ = unpack_mask(mask.cpu().numpy(), w_out) != mask_bits
+        assert np.all(np.abs(Po[differ]) <= 1e-5 * np.sqrt(np.mean(Po * Po))), "mask differs outside the rounding band"
+        full = mask.cpu().numpy().astype(np.uint32)
+        if w_out % 32:
+            assert np.all((full[:, -1] >> np.uint32(w_out % 32)) == 0)
+        mask.copy_(torch.as_tensor(pack_mask(mask_bits)))
+    if not runs_tf:
+        Z.copy_(torch.as_tensor(Zo.astype(np.float32)))
+    rng = np.random.default_rng(w_in + 7 * w_out)
+    dHout = rng.standard_normal((n, w_out)).astype(np.float32)
+    ref = oracle.layer_bwd(o, Hin, Zo, mask_bits, W_agg, W_self, dHout, need_dHin=need_dhin)
+    dHin = torch.full((n, padded_ld(w_in)), np.nan, **f)[:, :w_in] if need_dhin else None
+    dW_agg = torch.empty((w_in, w_out), **f); db = torch.empty(w_out, **f)
+    dW_self = torch.empty((w_in, w_out), **f) if has_self else None
+    db_self = torch.empty(w_out, **f) if has_self else None
+    wsb = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, need_dhin, flag), dtype=torch.uint8, device="cuda")
+    sg.slicegcn_layer_bwd(g, Hd, Wa, Ws, Z, mask, padded(dHout, w_out + 1), dHin, dW_agg, db, dW_self, db_self, wsb,
+                          act=act, order=flag)
+    names = [("dW_agg", dW_agg), ("db", db)] + ([("dW_self", dW_self), ("db_self", db_self)] if has_self else []) \
+        + ([("dHin", dHin)] if need_dhin else [])
+    for name, t in names:
+        assert_close(t.cpu().numpy(), ref[name], name)
+    if wsb.numel() > 256:
+        with pytest.raises(B.SliceGCNError) as e:
+            sg.slicegcn_layer_bwd(g, Hd, Wa, Ws, Z, mask, padded(dHout, w_out + 1), dHin, dW_agg, db, dW_self, db_self,
+                                  wsb[:wsb.numel() - 256], act=act, order=flag)
+        assert e.value.status == B.EWORKSPACE
+
+
+def test_layer_order_flag_errors(graphs):
+    n, o, g = graphs["tiny"]
+    f = dict(dtype=torch.float32, device="cuda")
+    Hin = torch.zeros((n, 32), **f); Hout = torch.zeros((n, 8), **f); Z = torch.zeros((n, 32), **f)
+    W = torch.zeros((32, 8), **f)
+    mask = torch.zeros((n, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.SliceGCNError) as e:      # both order flags
+        sg.slicegcn_layer_fwd(g, Hin, W, None, None, None, Hout, Z, mask, order=B.LAYER_TRANSFORM_FIRST | B.LAYER_ORDER_AUTO)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.SliceGCNError) as e:      # a kept aggregation cannot be declared valid when none is kept
+        sg.slicegcn_layer_fwd(g, Hin, W, None, None, None, Hout, Z, mask, z_valid=True, order=B.LAYER_TRANSFORM_FIRST)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.SliceGCNError) as e:      # the default order needs Z
+        sg.slicegcn_layer_fwd(g, Hin, W, None, None, None, Hout, None, mask)
+    assert e.value.status == B.EINVAL
+
+
+def test_workspace_formulas(graphs):
+    """Backward workspace = partial weight gradients (one per block of 1024 rows, or of 256 rows while that
+    leaves the tiled kernel under 2048 workgroups, x (2*w_in*w_out + 2*w_out) floats, 256-byte rounded), plus, when
+    the input gradient is wanted, an n x roundup32(w_in) fp32 staging matrix and the aggregation's own workspace.
+    The aggregation's workspace is zero for a graph without long rows and positive for one with them."""
+    n, o, g = graphs["ragged"]
+    w_in, w_out = 25, 64
+    blocks = -(-n // 256)
+    part = -(-(blocks * (2 * w_in * w_out + 2 * w_out) * 4) // 256) * 256
+    agg = sg.slicegcn_spmm_workspace_bytes(g, w_in, transpose=True)
+    assert agg == 0 and sg.slicegcn_layer_fwd_workspace_bytes(g, w_in, w_out) == 0
+    assert sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, False) == part
+    assert sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, True) == part + -(-(n * 32 * 4) // 256) * 256 + agg
+    n, o, g = graphs["hubs"]
+    agg = sg.slicegcn_spmm_workspace_bytes(g, 32)
+    assert agg > 0 and agg % 256 == 0 and sg.slicegcn_layer_fwd_workspace_bytes(g, 32, 8) == agg
+    assert sg.slicegcn_spmm_workspace_bytes(g, 64) == 2 * agg     # one slot of `width` floats per item
+    X = torch.zeros((n, 32), dtype=torch.float32, device="cuda")
+    Y = torch.empty_like(X)
+    with pytest.raises(B.SliceGCNError) as e:    # a workspace that is too small is refused, not overrun
+        sg.slicegcn_spmm_slice(g, X, Y, ws=torch.empty(agg - 256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == B.EWORKSPACE
+
+
+def test_spmm_two_streams_one_handle(graphs):
+    """A graph handle is read-only: two aggregations (one of them transposed) issued on two streams at the
+    same time, each with its own workspace, both give the oracle's result."""
+    n, o, g = graphs["hubs"]
+    rng = np.random.default_rng(3)
+    w = 32
+    Xa = rng.standard_normal((n, w)).astype(np.float32)
+    Xb = rng.standard_normal((n, w)).astype(np.float32)
+    want_a = oracle.spmm(o, Xa)
+    want_b = oracle.spmm(o, Xb, transpose=True)
+    Xad, Xbd = padded(Xa, padded_ld(w)), padded(Xb, padded_ld(w))
+    Ya = torch.empty((n, w), dtype=torch.float32, device="cuda")
+    Yb = torch.empty_like(Ya)
+    ws_a = torch.empty(sg.slicegcn_spmm_workspace_bytes(g, w, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(sg.slicegcn_spmm_workspace_bytes(g, w, True), dtype=torch.uint8, device="cuda")
+    assert ws_a.numel() > 0 and ws_b.numel() > 0
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(20):      # many overlapping pairs
+        with torch.cuda.stream(s1):
+            sg.slicegcn_spmm_slice(g, Xad, Ya, ws=ws_a)
+        with torch.cuda.stream(s2):
+            sg.slicegcn_spmm_slice(g, Xbd, Yb, transpose=True, ws=ws_b)
+    torch.cuda.synchronize()
+    assert_close(Ya.cpu().numpy(), want_a, "stream 1")
+    assert_close(Yb.cpu().numpy(), want_b, "stream 2 (transposed)")
 
 
 # ---------------------------------------------------------------------------------------
@@ -287,7 +457,7 @@ def test_concat_fwd_bwd():
 
 
 # ---------------------------------------------------------------------------------------
-def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0):
+def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0, order=0):
     """All k slices x L layers + encoding/concat, forward and backward, against the oracle.  With
     ``classifier`` the upstream gradient comes from the classifier MLP and the cross-entropy loss
     (also checked against the oracle) instead of a seeded random matrix."""
@@ -297,7 +467,7 @@ def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0
     sl, _ = sg.slicegcn_slice_strategy(w.feat, k, scale)
     assert sl == oracle.slice_strategy(w.feat, k, scale)[0]
     c = sl[0][1] - sl[0][0]  # every slice of a strategy has the same width
-    st = SliceStack(g, n, k, c, slice_hidden, L)
+    st = SliceStack(g, n, k, c, slice_hidden, L, order=order)
     X = configs.features(w)
     Xd = X.cuda()
     E = configs.normal_matrix(w.seed, configs.STREAM_E, k, slice_hidden, std=0.1)
@@ -404,11 +574,10 @@ def test_epoch_overlapping_and_scaled_slices():
     run_epoch_parity(dataclasses.replace(base, feat=50, k=2, hidden=64), 32, scale=0.5)  # 12 wide, gaps
 
 
-def test_epoch_feature_fusion():
+def run_epoch_feature_fusion(w):
     """The feature-fusion variant: one shared two-layer MLP d' -> d' -> slice_size feeds every slice
     model; its gradient is the sum of the slice models' input gradients.  Forward and backward
     against the oracle (dense layers + slice layers composed)."""
-    w = synth.WORKLOADS["cfg1"]
     s_, d_ = configs.edges(w)
     o, g = build_both(s_.numpy(), d_.numpy(), w.n_nodes)
     k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
@@ -467,6 +636,35 @@ def test_epoch_feature_fusion():
                             (ff.dW1, g1["dW"], "fusion dW1"), (ff.db1, g1["db"], "fusion db1")):
         assert_close(got.cpu().numpy(), want, what)
     g.destroy()
+
+
+def test_epoch_feature_fusion():
+    run_epoch_feature_fusion(synth.WORKLOADS["cfg1"])
+
+
+def test_epoch_feature_fusion_cfg2_size():
+    """The same on the 169 K-node workload: the first layer's input gradient (a transposed aggregation per
+    slice), the gradient accumulation over slices and the fusion MLP's backward at a size where the strip
+    kernels and 1024-row gradient blocks are the ones that run."""
+    run_epoch_feature_fusion(synth.WORKLOADS["cfg2"])
+
+
+def test_epoch_ragged_slices_cfg2_size():
+    """p does not divide d' on the 169 K-node graph: 101 features in 3 slices of 34 (the last one shifted left
+    and overlapping), per-slice hidden 32, three layers, with the classifier and the loss on top."""
+    import dataclasses
+    w = dataclasses.replace(synth.WORKLOADS["cfg2"], feat=101, k=3, hidden=96)
+    assert sg.slicegcn_slice_strategy(101, 3)[0] == [(0, 34), (34, 68), (67, 101)]
+    run_epoch_parity(w, 32, classifier=True)
+
+
+def test_epoch_layer_order_auto_and_transform_first():
+    """Whole passes in the other product order: ORDER_AUTO on a model whose first layer narrows (128 -> 32: transform
+    first) while the later ones do not (32 -> 32: aggregate first), and TRANSFORM_FIRST on every layer."""
+    import dataclasses
+    w = dataclasses.replace(synth.WORKLOADS["cfg1"], feat=256, hidden=64, layers=3)    # k = 2: slices of 128, hidden 32 per slice
+    run_epoch_parity(w, 32, order=B.LAYER_ORDER_AUTO)
+    run_epoch_parity(synth.WORKLOADS["cfg1"], 32, order=B.LAYER_TRANSFORM_FIRST)
 
 
 def test_epoch_with_classifier_and_loss():
@@ -552,10 +750,11 @@ def test_cached_first_aggregation_equals_recomputed():
     cached.inputs_changed()
     assert torch.equal(cached.forward(), ref) and torch.equal(cached.forward(), ref)
     with pytest.raises(B.SliceGCNError):  # unknown flag bit
-        desc, params = B._layer_structs(c, hs, 1, plain.params[0][0]["W_agg"], None, None, None, flags=2)
+        desc, params = B._layer_structs(c, hs, 1, plain.params[0][0]["W_agg"], None, None, None, flags=1 << 20)
         B._check(B.lib().slicegcn_layer_fwd(g.handle, __import__("ctypes").byref(desc), __import__("ctypes").byref(params),
                                             plain.X[0].data_ptr(), plain.X[0].stride(0), plain.Hcat.data_ptr(), plain.Hcat.stride(0),
-                                            __import__("ctypes").byref(B._saved_struct(plain.Z[0][0], plain.mask[0][0])), 0))
+                                            __import__("ctypes").byref(B._saved_struct(plain.Z[0][0], plain.mask[0][0])),
+                                            None, 0, 0))
     g.destroy()
 
 
@@ -607,7 +806,7 @@ def layer_many_rows(n, shape, act, has_self):
     dW_agg = torch.empty((w_in, w_out), **f); db = torch.empty(w_out, **f)
     dW_self = torch.empty((w_in, w_out), **f) if has_self else None
     db_self = torch.empty(w_out, **f) if has_self else None
-    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(n, w_in, w_out, True), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, True), dtype=torch.uint8, device="cuda")
     sg.slicegcn_layer_bwd(g, Hd, dev(W_agg), dev(W_self) if has_self else None, padded(Z32, padded_ld(w_in)), maskd,
                           padded(dHout, padded_ld(w_out)), dHin, dW_agg, db, dW_self, db_self, ws, act=act)
     names = [("dW_agg", dW_agg), ("db", db), ("dHin", dHin)] + ([("dW_self", dW_self), ("db_self", db_self)] if has_self else [])
@@ -640,11 +839,8 @@ def test_spmm_seeded_fuzz():
                 src = np.concatenate([src, np.full(nb.size, hnode)]); dst = np.concatenate([dst, nb])
         flags = int(rng.choice([3, 3, 2, 1, 0]))
         # both lane-group item limits (graphs this small would all get the short one)
-        os.environ["SLICEGCN_ITEM_MAX"] = "64" if case % 2 else "32"
-        try:
-            o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n, flags)
-        finally:
-            del os.environ["SLICEGCN_ITEM_MAX"]
+        o, g = build_both(src.astype(np.int64), dst.astype(np.int64), n, flags,
+                          sched=B.SCHED_LONG_ITEMS if case % 2 else B.SCHED_SHORT_ITEMS)
         check_csr(o, g)
         for _ in range(2):
             w = int(rng.choice([1, 2, 5, 25, 31, 32, 33, 64, 100, 130]))
@@ -678,11 +874,8 @@ def test_spmm_skewed_vertex_numbering(graph, directed):
         n = 30000
         lo, hi = sgraphs.rmat(n, 600000, seed=77, device="cpu", permute=False)
         src = lo.numpy().astype(np.int64); dst = hi.numpy().astype(np.int64)
-    os.environ["SLICEGCN_ITEM_MAX"] = "64"            # the limit large graphs get; the other tests run the short one
-    try:
-        o, g = build_both(src, dst, n, flags=2 if directed else 3)
-    finally:
-        del os.environ["SLICEGCN_ITEM_MAX"]
+    # the item limit large graphs get; the other tests run the short one
+    o, g = build_both(src, dst, n, flags=2 if directed else 3, sched=B.SCHED_LONG_ITEMS)
     check_csr(o, g)
     assert int(o.deg.max()) > 256                     # rows cut by column class exist
     rng = np.random.default_rng(5)
