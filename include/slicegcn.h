@@ -204,6 +204,21 @@ int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, 
                         int32_t width, float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * The same aggregation for callers that cannot allocate device memory and have no workspace to pass
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the partial
+ * sums go to a fixed SLICEGCN_STATIC_WS_BYTES buffer inside the library (one per GPU, held until the
+ * process ends) and the call allocates nothing.  Results are bitwise those of slicegcn_spmm_slice.
+ * Every call on one GPU shares that buffer, which keeps the last call's contents (nothing in it has to
+ * start at zero: every slot is written before it is read): calls that may overlap on one GPU, from
+ * several streams or threads, race -- order them on one stream or use slicegcn_spmm_slice.
+ * EINVAL as slicegcn_spmm_slice; EWORKSPACE: slicegcn_spmm_workspace_bytes(g, transpose, width) exceeds
+ * SLICEGCN_STATIC_WS_BYTES (graphs with very many long rows); EUNSUPPORTED: device index >= 64.
+ * ------------------------------------------------------------------------------------- */
+#define SLICEGCN_STATIC_WS_BYTES (16u << 20)
+int slicegcn_spmm_slice_static(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+                               int32_t width, float *Y, int64_t ldy, void *stream);
+
+/* ---------------------------------------------------------------------------------------
  * One layer of one slice, forward (the SliceGCN layer equation as typeset, self term outside
  * the activation):
  *   Z = A^ Hin;  P = b + Z W_agg;  Hout = act(P) + Hin W_self + b_self.

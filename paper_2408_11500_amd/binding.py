@@ -34,7 +34,8 @@ OK, EINVAL, ERANGE, ENOMEM, EHIP, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3, -4, 
 
 EXPORTS = [
     "slicegcn_slice_strategy", "slicegcn_build_norm_csr", "slicegcn_graph_view", "slicegcn_graph_destroy",
-    "slicegcn_slice_feature", "slicegcn_spmm_workspace_bytes", "slicegcn_spmm_slice", "slicegcn_layer_fwd_workspace_bytes",
+    "slicegcn_slice_feature", "slicegcn_spmm_workspace_bytes", "slicegcn_spmm_slice", "slicegcn_spmm_slice_static",
+    "slicegcn_layer_fwd_workspace_bytes",
     "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
     "slicegcn_strerror", "slicegcn_last_error", "slicegcn_profile_reserve", "slicegcn_profile_begin", "slicegcn_profile_end",
@@ -101,6 +102,7 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_spmm_workspace_bytes.argtypes = [vp, ctypes.c_int, i32]
         L.slicegcn_spmm_workspace_bytes.restype = sz
         L.slicegcn_spmm_slice.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp, sz, vp]
+        L.slicegcn_spmm_slice_static.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp]
         L.slicegcn_layer_fwd_workspace_bytes.argtypes = [vp, ctypes.POINTER(_LayerDesc)]
         L.slicegcn_layer_fwd_workspace_bytes.restype = sz
         L.slicegcn_layer_fwd.argtypes = [vp, ctypes.POINTER(_LayerDesc), ctypes.POINTER(_LayerParams), vp, i64, vp, i64,
@@ -294,6 +296,20 @@ def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int |
         ws = g.default_ws(slicegcn_spmm_workspace_bytes(g, w, transpose))
     pws, nws = _ws(ws)
     _check(lib().slicegcn_spmm_slice(g.handle, int(transpose), px, ldx, w, py, ldy, pws, nws, _stream()))
+    return Y
+
+
+STATIC_WS_BYTES = 16 << 20
+
+
+def slicegcn_spmm_slice_static(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False):
+    """The aggregation with the library's built-in partial-sum buffer: no workspace, no allocation."""
+    px, ldx = _mat(X, "X")
+    py, ldy = _mat(Y, "Y")
+    if X.shape[0] != Y.shape[0]:
+        raise ValueError("X and Y differ in rows")
+    w = int(X.shape[1] if width is None else width)
+    _check(lib().slicegcn_spmm_slice_static(g.handle, int(transpose), px, ldx, w, py, ldy, _stream()))
     return Y
 
 

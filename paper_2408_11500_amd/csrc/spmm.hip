@@ -30,6 +30,8 @@
 // only have to use different workspaces.
 #include "common.h"
 
+#include <mutex>
+
 namespace slicegcn {
 
 namespace {
@@ -605,6 +607,52 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
 } // namespace slicegcn
 
 using namespace slicegcn;
+
+// ---- aggregation without a caller workspace --------------------------------------------------
+// The partial sums go to this fixed array instead (one copy per GPU the library runs on, held until the
+// process ends).  In host code `scratch` is only a handle for the symbol: the device address comes from
+// hipGetSymbolAddress, once per device, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[SLICEGCN_STATIC_WS_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    SG_HIP(hipGetDevice(&dev));
+    SG_REQUIRE(dev >= 0 && dev < MAX_DEVICES, SLICEGCN_EUNSUPPORTED, "spmm_slice_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        SG_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        SG_REQUIRE(ptr != nullptr, SLICEGCN_EHIP, "spmm_slice_static: hipGetSymbolAddress returned NULL");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLICEGCN_OK;
+}
+} // namespace
+
+extern "C" int slicegcn_spmm_slice_static(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+                                          int32_t width, float *Y, int64_t ldy, void *stream)
+{
+    SG_REQUIRE(g && X && Y, SLICEGCN_EINVAL, "spmm_slice_static: NULL argument");
+    SG_REQUIRE(width >= 1, SLICEGCN_EINVAL, "spmm_slice_static: width = %d < 1", width);
+    SG_REQUIRE(ldx >= width && ldy >= width, SLICEGCN_EINVAL, "spmm_slice_static: leading dimension smaller than width");
+    const Csr &m = transpose ? g->tr : g->fwd;
+    const size_t need = spmm_workspace_bytes(m, width);
+    SG_REQUIRE(need <= (size_t)SLICEGCN_STATIC_WS_BYTES, SLICEGCN_EWORKSPACE,
+               "spmm_slice_static: this graph and width need %zu bytes of partial sums, the built-in buffer holds %zu; "
+               "use slicegcn_spmm_slice with a workspace", need, (size_t)SLICEGCN_STATIC_WS_BYTES);
+    void *ptr = nullptr;
+    if (need > 0)
+        if (int rc = static_scratch(&ptr)) return rc;
+    return launch_spmm(g, m, X, ldx, width, Y, ldy, nullptr, 0, ptr, need, as_stream(stream));
+}
 
 extern "C" size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int transpose, int32_t width)
 {

@@ -1,0 +1,65 @@
+"""The aggregation entry point that allocates nothing (slicegcn_spmm_slice_static: partial sums in a
+buffer built into the library) against slicegcn_spmm_slice with a caller workspace: bitwise equal
+outputs, on two calls in a row, the second on a smaller input, then again in the other direction."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_11500_amd as sg
+from paper_2408_11500_amd import binding as B
+from paper_2408_11500_amd.stack import padded_ld
+from gpu_util import assert_close, dev, hub_edges, padded
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(n, m, hubs, hub_deg, width, seed, transpose):
+    rng = np.random.default_rng(seed)
+    src, dst = hub_edges(n, m, hubs=hubs, hub_deg=hub_deg, rng=rng)
+    o = oracle.build_norm_csr(src, dst, n)
+    g = sg.slicegcn_build_norm_csr(dev(src, torch.int64), dev(dst, torch.int64), n)
+    need = sg.slicegcn_spmm_workspace_bytes(g, width, transpose)
+    assert 0 < need <= B.STATIC_WS_BYTES          # rows cut into several items exist, and they fit the built-in buffer
+    X = rng.standard_normal((n, width)).astype(np.float32)
+    Xd = padded(X, padded_ld(width))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    Yref = torch.full((n, width), np.nan, dtype=torch.float32, device="cuda")
+    sg.slicegcn_spmm_slice(g, Xd, Yref, transpose=transpose, ws=ws)
+    Y = torch.full((n, width), np.nan, dtype=torch.float32, device="cuda")
+    before = torch.cuda.memory_allocated()
+    # straight through the C ABI: no workspace argument exists
+    px, ldx = Xd.data_ptr(), int(Xd.stride(0))
+    rc = B.lib().slicegcn_spmm_slice_static(g.handle, int(transpose), px, ldx, width, Y.data_ptr(), int(Y.stride(0)),
+                                            int(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0, B.lib().slicegcn_last_error()
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    assert torch.equal(Y, Yref), f"static entry differs (n={n}, width={width}, transpose={transpose})"
+    assert_close(Y.cpu().numpy(), oracle.spmm(o, X.astype(np.float64), transpose=transpose), "static entry vs oracle")
+    g.destroy()
+
+
+def test_static_entry_two_calls_second_smaller():
+    _case(30011, 90000, [0, 777, 30010, 15000], 9000, 64, seed=11, transpose=False)
+    _case(9001, 20000, [5, 4000], 3000, 32, seed=12, transpose=False)       # smaller graph, narrower operand
+    _case(9001, 20000, [5, 4000], 3000, 100, seed=13, transpose=True)       # scalar-free wide path, other direction
+
+
+def test_static_entry_rejects_what_does_not_fit():
+    """A graph whose partial sums exceed the built-in buffer is refused with EWORKSPACE before any launch."""
+    rng = np.random.default_rng(14)
+    n = 20000
+    hubs = list(range(0, n, 4))       # every row ends up with hundreds of entries and is cut into 8 class pieces
+    src, dst = hub_edges(n, 1000, hubs=hubs, hub_deg=2000, rng=rng)
+    g = sg.slicegcn_build_norm_csr(dev(src, torch.int64), dev(dst, torch.int64), n)
+    width = 128
+    assert sg.slicegcn_spmm_workspace_bytes(g, width) > B.STATIC_WS_BYTES
+    X = torch.zeros((n, width), dtype=torch.float32, device="cuda")
+    Y = torch.empty_like(X)
+    with pytest.raises(B.SliceGCNError) as e:
+        B.slicegcn_spmm_slice_static(g, X, Y)
+    assert e.value.status == B.EWORKSPACE
+    g.destroy()
