@@ -89,6 +89,13 @@ def main():
     ap.add_argument("--order", choices=("aggregate", "transform", "auto"), default="aggregate",
                     help="order of the two products of every layer (SLICEGCN_LAYER_*): aggregate first (the layer as stated, "
                          "default), transform first, or transform first where the layer narrows (w_out < w_in)")
+    ap.add_argument("--prescaled", action="store_true",
+                    help="with --spmm-only: aggregate operands pre-scaled by D~^-1/2 (SLICEGCN_SPMM_PRESCALED: the value "
+                         "stream is not read)")
+    ap.add_argument("--unscaled", action="store_true",
+                    help="keep the activations between the layers unscaled (every forward aggregation then reads the "
+                         "stored values); by default graphs of 16 M stored entries or more keep them as D~^-1/2 H "
+                         "(SLICEGCN_LAYER_IN/OUT_SCALED)")
     ap.add_argument("--reorder", choices=("none", "degree", "bfs"), default="none",
                     help="row order of the aggregation schedule (SLICEGCN_REORDER_*): by degree, or breadth first "
                          "(pays off on graphs with communities such as --workload comm, not on R-MAT)")
@@ -158,7 +165,7 @@ def main():
         ff.set_params(*model.fusion_params(w, width, device=dev))
         ff.forward(X)
     st = SliceStack(g, n, k, width, hs, L, device=dev, shared_input=ff.Xff if ff is not None else None,
-                    cache_first_aggregation=args.cache_first_agg,
+                    cache_first_aggregation=args.cache_first_agg, scaled=False if args.unscaled else None,
                     order={"aggregate": 0, "transform": sg.binding.LAYER_TRANSFORM_FIRST, "auto": sg.binding.LAYER_ORDER_AUTO}[args.order])
     for i, (a, b) in enumerate(slices):
         if ff is None:
@@ -178,11 +185,14 @@ def main():
     log("inputs resident")
 
     Yspmm = torch.empty_like(st.X[0]) if args.spmm_only else None
+    Xagg = st.X
+    if args.spmm_only and args.prescaled:   # D~^-1/2 X_s, made once: the raw features are constant
+        Xagg = [sg.slicegcn_scale_rows(g, x[:, :width], torch.empty_like(x), width=width) for x in st.X]
 
     def step():
         if args.spmm_only:
             for j in range(args.spmm_only):   # round-robin over the slices, as in the real pass
-                sg.slicegcn_spmm_slice(g, st.X[j % k][:, :width], Yspmm[:, :width])
+                sg.slicegcn_spmm_slice(g, Xagg[j % k][:, :width], Yspmm[:, :width], prescaled=args.prescaled)
         else:
             if ff is not None:
                 ff.forward(X)
@@ -229,8 +239,9 @@ def main():
     kernels = {f"{kind}_w{wd}": {"launches": cnt, "avg_ms": tot / cnt, "median_ms": med, "min_ms": lo, "max_ms": hi}
                for kind, wd, cnt, tot, lo, hi, med in prof_full}
     dom = next(((cnt, tot) for kind, wd, cnt, tot in prof if kind == "spmm" and wd == width), None)
-    if dom is None and args.cache_first_agg:
-        # the cached variant ran no aggregation at the slice width inside the steps: time it on its own
+    if dom is None:
+        # this variant of the step ran no aggregation at the slice width (cached first layer, or the transform-first
+        # order, which aggregates at the hidden width): time the slice-width aggregation on its own
         Y = torch.empty_like(st.X[0])
         sg.slicegcn_profile_begin()
         for j in range(2 * k):
@@ -262,7 +273,10 @@ def main():
                                + (" [generator's vertex numbering, hubs first]" if args.vertex_order != "permuted" else "")
                                + (f" [rows visited in {args.reorder} order]" if args.reorder != "none" else "")
                                + (f" [layer order: {args.order}]" if args.order != "aggregate" else "")
+                               + (" [activations kept as D~^-1/2 H between layers]" if st.scaled else "")
                                + (" [aggregation only]" if args.spmm_only else "")
+                               + (" [operands pre-scaled by D~^-1/2]" if args.spmm_only and args.prescaled else "")
+
                                + (" [first-layer aggregation cached across steps]" if args.cache_first_agg and ff is None else "")
                                + (f" + feature fusion {w.feat}->{w.feat}->{width}" if ff is not None else "")
                                + (f" + classifier {k * hs}->{w.hidden}->{w.classes} and cross-entropy" if cls is not None else ""),
@@ -281,8 +295,11 @@ def main():
     out["roofline"]["stream_copy_GBps"] = stream_copy()["GBps"]   # what a plain copy reaches on this machine, for scale
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
-        out["cpu_baseline"] = cpu_baseline(w, src, dst, lambda i: st.X[i][:, :width].cpu().numpy(), slices, width,
-                                           args.cpu_sample_frac)
+        # the raw slice, regenerated: the stack's own copies hold the scaled layout by now
+        out["cpu_baseline"] = cpu_baseline(w, src, dst,
+                                           lambda i: configs.features(w, device=dev, col_start=slices[i][0],
+                                                                      col_count=slices[i][1] - slices[i][0]).cpu().numpy(),
+                                           slices, width, args.cpu_sample_frac)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)

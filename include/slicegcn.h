@@ -101,6 +101,15 @@ typedef struct {
  * workspace queries of a layer. */
 #define SLICEGCN_LAYER_TRANSFORM_FIRST 2u
 #define SLICEGCN_LAYER_ORDER_AUTO 4u
+/* Scaled layout of activations (aggregate-first order only).  1/c_vu factors as dinv[v] dinv[u], so an
+ * activation kept as H' = D~^-1/2 H (row v times dinv[v]) is aggregated without reading the 4-byte value of every
+ * stored entry (SLICEGCN_SPMM_PRESCALED).  IN_SCALED: Hin holds D~^-1/2 times the layer's input (the self term
+ * and its weight gradient multiply the rows back by sqrt(d~_v)).  OUT_SCALED: Hout receives D~^-1/2 times the
+ * layer's output, ready to be the next layer's IN_SCALED input.  Gradients (dHout, dHin) are always those of the
+ * unscaled activations, and saved->Z is always the unscaled A^ Hin.  A stack of layers scales its constant input
+ * once (slicegcn_scale_rows), sets IN_SCALED on every layer and OUT_SCALED on all but the last. */
+#define SLICEGCN_LAYER_IN_SCALED 8u
+#define SLICEGCN_LAYER_OUT_SCALED 16u
 
 typedef struct {
     int32_t w_in;   /* width of the layer input  (columns of Hin, rows of W)    */
@@ -186,8 +195,12 @@ int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, int32_t start
 
 /* ---------------------------------------------------------------------------------------
  * Slice aggregation, the inner sum of the SliceGCN layer equation:
- *   Y[v, 0:width] = sum over stored (v,u) of vals_vu * X[u, 0:width]       (transpose = 0)
- *   Y = A^^T X                                                              (transpose != 0)
+ *   Y[v, 0:width] = sum over stored (v,u) of vals_vu * X[u, 0:width]       (op = 0)
+ *   Y = A^^T X                                                              (op & SLICEGCN_SPMM_TRANSPOSE)
+ * With SLICEGCN_SPMM_PRESCALED the caller passes X' = D~^-1/2 X (every row u already multiplied by dinv[u],
+ * e.g. by slicegcn_scale_rows; worthwhile when X is constant or its producer can scale it for free) and the
+ * call forms dinv[v] * sum of X'[u, :] instead: the same Y up to rounding, without reading the 4-byte value
+ * of every stored entry (1/c_vu factors as dinv[v] dinv[u]).
  * X, Y: n_nodes x width with leading dimensions ldx, ldy.  X and Y must not overlap.
  * The fast path needs X 16-byte aligned with ldx a multiple of 4 and ldx >= width rounded up
  * to 4 (padding columns are read but never used); other layouts take a scalar path.  Only
@@ -199,9 +212,17 @@ int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, int32_t start
  * EINVAL: NULL pointer, width < 1, ldx < width, ldy < width, misaligned ws;
  * EWORKSPACE: ws NULL or too small.
  * ------------------------------------------------------------------------------------- */
-size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int transpose, int32_t width);
-int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+#define SLICEGCN_SPMM_TRANSPOSE 1
+#define SLICEGCN_SPMM_PRESCALED 2
+size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int op, int32_t width);
+int slicegcn_spmm_slice(const slicegcn_graph *g, int op, const float *X, int64_t ldx,
                         int32_t width, float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/* Xs[u, 0:width] = dinv[u] * X[u, 0:width] (n_nodes rows; columns [width, ldxs) of Xs are written as zeros):
+ * the operand form SLICEGCN_SPMM_PRESCALED and SLICEGCN_LAYER_IN_SCALED expect.  Xs may be X itself (in place,
+ * same leading dimension).  EINVAL: NULL pointer, width < 1, ld < width. */
+int slicegcn_scale_rows(const slicegcn_graph *g, const float *X, int64_t ldx, int32_t width,
+                        float *Xs, int64_t ldxs, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * The same aggregation for callers that cannot allocate device memory and have no workspace to pass
@@ -211,11 +232,11 @@ int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, 
  * Every call on one GPU shares that buffer, which keeps the last call's contents (nothing in it has to
  * start at zero: every slot is written before it is read): calls that may overlap on one GPU, from
  * several streams or threads, race -- order them on one stream or use slicegcn_spmm_slice.
- * EINVAL as slicegcn_spmm_slice; EWORKSPACE: slicegcn_spmm_workspace_bytes(g, transpose, width) exceeds
+ * EINVAL as slicegcn_spmm_slice; EWORKSPACE: slicegcn_spmm_workspace_bytes(g, op, width) exceeds
  * SLICEGCN_STATIC_WS_BYTES (graphs with very many long rows); EUNSUPPORTED: device index >= 64.
  * ------------------------------------------------------------------------------------- */
 #define SLICEGCN_STATIC_WS_BYTES (16u << 20)
-int slicegcn_spmm_slice_static(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+int slicegcn_spmm_slice_static(const slicegcn_graph *g, int op, const float *X, int64_t ldx,
                                int32_t width, float *Y, int64_t ldy, void *stream);
 
 /* ---------------------------------------------------------------------------------------

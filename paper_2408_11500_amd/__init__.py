@@ -10,5 +10,5 @@ from .binding import (ACT_NONE, ACT_RELU, ADD_SELF_LOOPS, SYMMETRIZE, Graph, Sli
                       slicegcn_concat_bwd_workspace_bytes, slicegcn_layer_bwd,
                       slicegcn_layer_bwd_workspace_bytes, slicegcn_layer_fwd,
                       slicegcn_layer_fwd_workspace_bytes, slicegcn_profile_begin, slicegcn_profile_reserve,
-                      slicegcn_profile_end, slicegcn_slice_feature,
+                      slicegcn_profile_end, slicegcn_scale_rows, slicegcn_slice_feature,
                       slicegcn_slice_strategy, slicegcn_spmm_slice, slicegcn_spmm_workspace_bytes)

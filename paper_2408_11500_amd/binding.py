@@ -29,12 +29,14 @@ ACT_RELU = 1
 LAYER_Z_VALID = 1
 LAYER_TRANSFORM_FIRST = 2
 LAYER_ORDER_AUTO = 4
+LAYER_IN_SCALED = 8
+LAYER_OUT_SCALED = 16
 
 OK, EINVAL, ERANGE, ENOMEM, EHIP, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "slicegcn_slice_strategy", "slicegcn_build_norm_csr", "slicegcn_graph_view", "slicegcn_graph_destroy",
-    "slicegcn_slice_feature", "slicegcn_spmm_workspace_bytes", "slicegcn_spmm_slice", "slicegcn_spmm_slice_static",
+    "slicegcn_slice_feature", "slicegcn_scale_rows", "slicegcn_spmm_workspace_bytes", "slicegcn_spmm_slice", "slicegcn_spmm_slice_static",
     "slicegcn_layer_fwd_workspace_bytes",
     "slicegcn_layer_fwd", "slicegcn_layer_bwd_workspace_bytes",
     "slicegcn_layer_bwd", "slicegcn_concat", "slicegcn_concat_bwd_workspace_bytes", "slicegcn_concat_bwd",
@@ -99,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.slicegcn_graph_view.argtypes = [vp, ctypes.POINTER(_CsrView)]
         L.slicegcn_graph_destroy.argtypes = [vp]
         L.slicegcn_slice_feature.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp]
+        L.slicegcn_scale_rows.argtypes = [vp, vp, i64, i32, vp, i64, vp]
         L.slicegcn_spmm_workspace_bytes.argtypes = [vp, ctypes.c_int, i32]
         L.slicegcn_spmm_workspace_bytes.restype = sz
         L.slicegcn_spmm_slice.argtypes = [vp, ctypes.c_int, vp, i64, i32, vp, i64, vp, sz, vp]
@@ -284,9 +287,19 @@ def slicegcn_spmm_workspace_bytes(g: Graph, width: int, transpose: bool = False)
     return int(lib().slicegcn_spmm_workspace_bytes(g.handle, int(transpose), width))
 
 
+def slicegcn_scale_rows(g: Graph, X: torch.Tensor, Xs: torch.Tensor, width: int | None = None):
+    """Xs = D~^-1/2 X: the operand form ``slicegcn_spmm_slice(..., prescaled=True)`` expects."""
+    px, ldx = _mat(X, "X")
+    ps, lds = _mat(Xs, "Xs")
+    w = int(X.shape[1] if width is None else width)
+    _check(lib().slicegcn_scale_rows(g.handle, px, ldx, w, ps, lds, _stream()))
+    return Xs
+
+
 def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False,
-                        ws: torch.Tensor | None = None):
-    """``ws``: uint8 device tensor of slicegcn_spmm_workspace_bytes bytes; None = the graph object's cached buffer."""
+                        ws: torch.Tensor | None = None, prescaled: bool = False):
+    """``ws``: uint8 device tensor of slicegcn_spmm_workspace_bytes bytes; None = the graph object's cached buffer.
+    ``prescaled``: X already holds D~^-1/2 X (see slicegcn_scale_rows)."""
     px, ldx = _mat(X, "X")
     py, ldy = _mat(Y, "Y")
     if X.shape[0] != Y.shape[0]:
@@ -295,7 +308,7 @@ def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int |
     if ws is None and w >= 1:
         ws = g.default_ws(slicegcn_spmm_workspace_bytes(g, w, transpose))
     pws, nws = _ws(ws)
-    _check(lib().slicegcn_spmm_slice(g.handle, int(transpose), px, ldx, w, py, ldy, pws, nws, _stream()))
+    _check(lib().slicegcn_spmm_slice(g.handle, int(transpose) | (2 if prescaled else 0), px, ldx, w, py, ldy, pws, nws, _stream()))
     return Y
 
 
@@ -337,14 +350,15 @@ def slicegcn_layer_fwd_workspace_bytes(g: Graph, w_in: int, w_out: int, flags: i
 
 def slicegcn_layer_fwd(g: Graph, Hin, W_agg, b, W_self, b_self, Hout, Z, mask, act: int = ACT_RELU,
                        w_in: int | None = None, w_out: int | None = None, z_valid: bool = False,
-                       ws: torch.Tensor | None = None, order: int = 0):
+                       ws: torch.Tensor | None = None, order: int = 0, layout: int = 0):
     """Hout = act(A^ Hin W_agg + b) + Hin W_self + b_self; fills Z (and mask for ReLU).
     ``z_valid``: Z already holds A^ Hin (same graph and Hin as an earlier call): skip the aggregation.
     ``ws``: uint8 device tensor of slicegcn_layer_fwd_workspace_bytes bytes; None = the graph object's cached buffer.
-    ``order``: 0, LAYER_TRANSFORM_FIRST or LAYER_ORDER_AUTO (then Z may be None when the transform-first order runs)."""
+    ``order``: 0, LAYER_TRANSFORM_FIRST or LAYER_ORDER_AUTO (then Z may be None when the transform-first order runs).
+    ``layout``: LAYER_IN_SCALED and/or LAYER_OUT_SCALED (activations kept as D~^-1/2 H)."""
     w_in = int(W_agg.shape[0] if w_in is None else w_in)
     w_out = int(W_agg.shape[1] if w_out is None else w_out)
-    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, (LAYER_Z_VALID if z_valid else 0) | order)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, b, W_self, b_self, (LAYER_Z_VALID if z_valid else 0) | order | layout)
     pi, ldi = _mat(Hin, "Hin")
     po, ldo = _mat(Hout, "Hout")
     saved = _saved_struct(Z, mask)
@@ -362,11 +376,11 @@ def slicegcn_layer_bwd_workspace_bytes(g: Graph, w_in: int, w_out: int, need_dHi
 
 
 def slicegcn_layer_bwd(g: Graph, Hin, W_agg, W_self, Z, mask, dHout, dHin, dW_agg, db, dW_self, db_self, ws,
-                       act: int = ACT_RELU, order: int = 0):
+                       act: int = ACT_RELU, order: int = 0, layout: int = 0):
     """Gradients of one layer.  ``dHin`` may be None (skipped).  ``ws`` is a uint8 workspace tensor.
-    ``order``: the same order flag the forward call was given."""
+    ``order``, ``layout``: the flags the forward call was given."""
     w_in, w_out = int(W_agg.shape[0]), int(W_agg.shape[1])
-    desc, params = _layer_structs(w_in, w_out, act, W_agg, None, W_self, None, order)
+    desc, params = _layer_structs(w_in, w_out, act, W_agg, None, W_self, None, order | layout)
     pi, ldi = _mat(Hin, "Hin")
     pg, ldo = _mat(dHout, "dHout")
     pgi, ldgi = _mat(dHin, "dHin") if dHin is not None else (None, 0)

@@ -76,13 +76,14 @@ __global__ void rowptr_kernel(const uint64_t *__restrict__ keys, int64_t nnz, in
 }
 
 __global__ void degree_kernel(const int32_t *__restrict__ rowptr, int64_t n,
-                              int32_t *__restrict__ deg, float *__restrict__ dinv)
+                              int32_t *__restrict__ deg, float *__restrict__ dinv, float *__restrict__ sqrtd)
 {
     const int64_t v = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (v >= n) return;
     const int32_t d = rowptr[v + 1] - rowptr[v];
     deg[v] = d;
     dinv[v] = (float)(1.0 / sqrt((double)(d > 0 ? d : 1)));
+    sqrtd[v] = (float)sqrt((double)(d > 0 ? d : 1));
 }
 
 __global__ void entries_kernel(const uint64_t *__restrict__ keys, int64_t nnz,
@@ -476,18 +477,20 @@ extern "C" int slicegcn_build_norm_csr(const int64_t *src, const int64_t *dst, i
     const uint64_t *uniq = keys_a.as<uint64_t>(); // sorted distinct keys [0, nnz)
 
     {
-        DevBuf rowptr, deg, dinv;
+        DevBuf rowptr, deg, dinv, sqrtd;
         if (int rc = rowptr.alloc((size_t)(n_nodes + 1) * sizeof(int32_t))) return rc;
         if (int rc = deg.alloc((size_t)n_nodes * sizeof(int32_t))) return rc;
         if (int rc = dinv.alloc((size_t)n_nodes * sizeof(float))) return rc;
+        if (int rc = sqrtd.alloc((size_t)n_nodes * sizeof(float))) return rc;
         rowptr_kernel<<<blocks_for(n_nodes + 1), TPB, 0, stream>>>(uniq, nnz, n_nodes, rowptr.as<int32_t>());
         SG_LAUNCH_CHECK();
         degree_kernel<<<blocks_for(n_nodes), TPB, 0, stream>>>(rowptr.as<int32_t>(), n_nodes, deg.as<int32_t>(),
-                                                              dinv.as<float>());
+                                                              dinv.as<float>(), sqrtd.as<float>());
         SG_LAUNCH_CHECK();
         g->fwd.rowptr = rowptr.release<int32_t>();
         g->deg = deg.release<int32_t>();
         g->dinv = dinv.release<float>();
+        g->sqrtd = sqrtd.release<float>();
     }
     if (int rc = pattern_from_keys(uniq, nnz, n_nodes, g->dinv, g->fwd, stream)) return rc;
 
@@ -548,6 +551,7 @@ extern "C" int slicegcn_graph_destroy(slicegcn_graph *g)
     free_csr(g->fwd, true);
     (void)hipFree(g->deg);
     (void)hipFree(g->dinv);
+    (void)hipFree(g->sqrtd);
     (void)hipFree(g->order);
     delete g;
     return SLICEGCN_OK;

@@ -111,6 +111,7 @@ struct slicegcn_graph {
     int device = 0;
     int32_t *deg = nullptr;
     float *dinv = nullptr;
+    float *sqrtd = nullptr; // sqrt(max(d~_v, 1)) = 1 / dinv: undoes the row scaling of activations kept as D~^-1/2 H
     int32_t *order = nullptr; // order[p] = row at position p of the aggregation's schedule; NULL = natural order
     slicegcn::Csr fwd;  // A^
     slicegcn::Csr tr;   // A^^T (arrays alias fwd when the pattern is symmetric)
@@ -121,7 +122,8 @@ namespace slicegcn {
 // spmm.hip: Y[:, 0:width] = M X (+ Add), M given by `m`.  Add may alias Y.  ws: 256-byte aligned, at least
 // spmm_workspace_bytes(m, width) bytes (partial sums of rows cut into several items; may be NULL when that is 0).
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
-                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream);
+                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream,
+                bool prescaled = false); // prescaled: X rows carry dinv[u] already (the value stream is not read)
 size_t spmm_workspace_bytes(const Csr &m, int32_t width);
 
 // dense.hip: column sums of an n x w matrix: fp32 per block of rows into ws[blocks][w], then

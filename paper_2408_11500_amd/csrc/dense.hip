@@ -31,7 +31,12 @@ struct PairArgs {
     int32_t Nout;  // output width:     w_out forward, w_in backward
     int32_t ldw;   // leading dimension of W (= w_out)
     int32_t act;
+    // Scaled layout (activations stored as D~^-1/2 H, the operand form the aggregation wants): per-row factors.
+    const float *scale2 = nullptr;   // forward: rows of A2 are multiplied by scale2[row] when read (sqrt(d~): undoes the scaling of Hin)
+    const float *scale_o1 = nullptr; // rows of O1 are multiplied by scale_o1[row] (forward: on store; backward: dZ rows, folded into dP)
 };
+
+__device__ inline void scale4(float4 &v, float s) { v.x *= s; v.y *= s; v.z *= s; v.w *= s; }
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -88,6 +93,7 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
         for (int r = 0; r < 16; ++r) { acc1[t][r] = 0.f; if (TWO) acc2[t][r] = 0.f; }
 
     float4 ra1[4], ra2[TWO ? 4 : 1];
+    float rs[4]; // per-row factor of this thread's four rows (applied when the registers go to LDS, so that the loads stay in flight)
     float rb1[BPT], rb2[TWO ? BPT : 1];
     auto fetch = [&](int k0) { // this thread's share of the tiles of chunk k0, into registers
 #pragma unroll
@@ -97,10 +103,14 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
             const int64_t row = row0 + r;
             const int kk = k0 + c4;
             float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f), v2 = v1;
+            float f = 1.f;
             if (row < a.n && kk < a.K) {
                 v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
                 if (!BWD) {
-                    if (TWO) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                    if (TWO) {
+                        v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                        if (a.scale2) f = a.scale2[row];
+                    }
                 } else {
                     if (TWO) v2 = v1;
                     if (a.mask) { // four mask bits of this row; kk % 4 == 0 keeps them inside one word
@@ -110,9 +120,11 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
                         if (!(bits & 4u)) v1.z = 0.f;
                         if (!(bits & 8u)) v1.w = 0.f;
                     }
+                    if (a.scale_o1) f = a.scale_o1[row];
                 }
             }
             ra1[it] = v1;
+            rs[it] = f;
             if (TWO) ra2[it] = v2;
         }
 #pragma unroll
@@ -136,6 +148,8 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
         for (int it = 0; it < 4; ++it) {
             const int idx = tid + it * 256;
             const int r = idx >> 3, c4 = (idx & 7) * 4;
+            if (BWD && a.scale_o1) scale4(ra1[it], rs[it]);         // rows of the first product only (dZ rows)
+            if (!BWD && TWO && a.scale2) scale4(ra2[it], rs[it]);   // rows of Hin kept scaled
             *reinterpret_cast<float4 *>(&As1[r][c4]) = ra1[it];
             if (TWO) *reinterpret_cast<float4 *>(&As2[r][c4]) = ra2[it];
         }
@@ -192,7 +206,7 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
                 }
                 const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
                 const float o = rl + (TWO ? acc2[t][r] + bias2 : 0.f);
-                if (row < a.n && col_ok) a.O1[row * a.ldo1 + col] = o;
+                if (row < a.n && col_ok) a.O1[row * a.ldo1 + col] = a.scale_o1 ? o * a.scale_o1[row] : o;
             } else {
                 if (row < a.n && col_ok) {
                     a.O1[row * a.ldo1 + col] = acc1[t][r];
@@ -250,7 +264,10 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
             if (row < a.n && kk < a.K) {
                 v1 = load_k4(a.A1, a.lda1, row, kk, a.K, vec1);
                 if (!BWD) {
-                    if (two) v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                    if (two) {
+                        v2 = load_k4(a.A2, a.lda2, row, kk, a.K, vec2);
+                        if (a.scale2) scale4(v2, a.scale2[row]);
+                    }
                 } else {
                     if (two) v2 = v1;
                     if (a.mask) {
@@ -260,6 +277,7 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
                         if (!(bits & 4u)) v1.z = 0.f;
                         if (!(bits & 8u)) v1.w = 0.f;
                     }
+                    if (a.scale_o1) scale4(v1, a.scale_o1[row]); // scales the rows of the first product only
                 }
             }
             a1[q] = v1;
@@ -303,7 +321,7 @@ __global__ __launch_bounds__(256) void pair_mfma_direct_kernel(const PairArgs a)
                     }
                     const float rl = (a.act == SLICEGCN_ACT_RELU) ? (p > 0.f ? p : 0.f) : p;
                     const float o = rl + (two ? acc2[t][r] + bias2 : 0.f);
-                    if (orow < a.n && col_ok) a.O1[orow * a.ldo1 + col] = o;
+                    if (orow < a.n && col_ok) a.O1[orow * a.ldo1 + col] = a.scale_o1 ? o * a.scale_o1[orow] : o;
                 } else {
                     if (orow < a.n && col_ok) {
                         a.O1[orow * a.ldo1 + col] = acc1[t][r];
@@ -365,6 +383,11 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
     const int64_t first = (int64_t)blockIdx.x * 4 + wave, step = (int64_t)gridDim.x * 4;
     float4 p1[4], p2[4];
     uint32_t pw = ~0u; // backward: activation word of strip row m (the row this lane feeds to the MFMAs)
+    float ps = 1.f;    // backward: scale_o1 of strip row m
+    // forward, scaled layout: factors of the rows lr + 8 it this lane loads and stores (only fetched here; they are
+    // applied where the strip is consumed, so that the next strip's loads stay in flight behind the MFMAs).  One
+    // load per lane and strip handed on by cross-lane reads was measured slower (the LDS pipe carries the tiles).
+    float f2[4] = {1.f, 1.f, 1.f, 1.f}, fo[4] = {1.f, 1.f, 1.f, 1.f};
     auto fetch = [&](int64_t strip) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -374,32 +397,42 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
                 v1 = load_k4(a.A1, a.lda1, row, lc, a.K, vec1);
                 if (!BWD && TWO) v2 = load_k4(a.A2, a.lda2, row, lc, a.K, vec2);
             }
+            if (!BWD && row < a.n) {
+                if (TWO && a.scale2) f2[it] = a.scale2[row];
+                if (a.scale_o1) fo[it] = a.scale_o1[row];
+            }
             p1[it] = v1;
             p2[it] = v2;
         }
         if (BWD && a.mask) pw = strip * 32 + m < a.n ? a.mask[(strip * 32 + m) * a.mask_words] : 0u;
+        if (BWD && a.scale_o1) ps = strip * 32 + m < a.n ? a.scale_o1[strip * 32 + m] : 1.f;
     };
     if (first < n_strips) fetch(first);
     for (int64_t strip = first; strip < n_strips; strip += step) {
+        float out_f[4]; // output factors of the rows lr + 8 it of this strip (the fetch below overwrites fo)
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
+            if (TWO && !BWD && a.scale2) scale4(p2[it], f2[it]);
+            out_f[it] = fo[it];
             *reinterpret_cast<float4 *>(&t1[lr + 8 * it][lc]) = p1[it];
             if (TWO && !BWD) *reinterpret_cast<float4 *>(&t2[lr + 8 * it][lc]) = p2[it];
         }
         __builtin_amdgcn_wave_barrier();
         float4 a1[4], a2[4];
         const uint32_t word = pw;
+        const float so = ps;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             a1[q] = *reinterpret_cast<const float4 *>(&t1[m][8 * q + 4 * h]);
             if (TWO && !BWD) a2[q] = *reinterpret_cast<const float4 *>(&t2[m][8 * q + 4 * h]);
-            if (BWD) { // second product: dHout as it is; first product: dP = dHout * mask
+            if (BWD) { // second product: dHout as it is; first product: dP = dHout * mask (times the row's output factor)
                 a2[q] = a1[q];
                 const uint32_t bits = word >> (8 * q + 4 * h);
                 if (!(bits & 1u)) a1[q].x = 0.f;
                 if (!(bits & 2u)) a1[q].y = 0.f;
                 if (!(bits & 4u)) a1[q].z = 0.f;
                 if (!(bits & 8u)) a1[q].w = 0.f;
+                if (a.scale_o1) scale4(a1[q], so);
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -437,7 +470,9 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
         // Outputs leave through the wavefront's tile so that a row goes out as eight 16-byte stores
         // (register r of lane (m, h) is strip row 8*(r/4) + 4*h + r%4, column m); layouts that do not
         // allow 16-byte stores write the registers directly.
-        auto store_tile = [&](const float (&o)[16], float *O, int64_t ldo, bool vec_ok) {
+        // `rs`: per-row factor applied on the way out (forward outputs kept in the scaled layout), or NULL; the
+        // 16-byte path takes the factors from out_f, fetched a strip ahead.
+        auto store_tile = [&](const float (&o)[16], float *O, int64_t ldo, bool vec_ok, const float *rs) {
             if (vec_ok) {
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -446,21 +481,24 @@ __global__ __launch_bounds__(256) void pair_strip32_kernel(const PairArgs a)
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     const int64_t row = row0 + lr + 8 * it;
-                    const float4 v = *reinterpret_cast<const float4 *>(&t1[lr + 8 * it][lc]);
-                    if (row < a.n && lc < a.Nout) *reinterpret_cast<float4 *>(O + row * ldo + lc) = v;
+                    float4 v = *reinterpret_cast<const float4 *>(&t1[lr + 8 * it][lc]);
+                    if (row < a.n && lc < a.Nout) {
+                        if (rs) scale4(v, out_f[it]);
+                        *reinterpret_cast<float4 *>(O + row * ldo + lc) = v;
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
             } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
-                    if (orow < a.n && col_ok) O[orow * ldo + m] = o[r];
+                    if (orow < a.n && col_ok) O[orow * ldo + m] = rs ? o[r] * rs[orow] : o[r];
                 }
             }
         };
         const bool nout4 = a.Nout % 4 == 0;
-        store_tile(o1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0);
-        if (BWD && TWO && a.O2) store_tile(o2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0);
+        store_tile(o1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0, BWD ? nullptr : a.scale_o1);
+        if (BWD && TWO && a.O2) store_tile(o2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0, nullptr);
         if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && row0 + lane < a.n)
             a.mask[(row0 + lane) * a.mask_words] = my_word;
     }
@@ -516,6 +554,9 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
     const int64_t first = (int64_t)blockIdx.x * 4 + wave, step = (int64_t)gridDim.x * 4;
     float4 p1[PK], p2[(TWO && !BWD) ? PK : 1];
     uint32_t pw[KC]; // backward: activation words of strip row m
+    // forward, scaled layout: factors of the rows this lane loads (f2) and stores (fo); fetched a strip ahead, applied
+    // where the strip is consumed
+    float f2[(TWO && !BWD) ? PK : 1], fo[BWD ? 1 : PN];
 #pragma unroll
     for (int w = 0; w < KC; ++w) pw[w] = ~0u;
     auto fetch = [&](int64_t strip) {
@@ -527,6 +568,7 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
                 v1 = load_k4(a.A1, a.lda1, row, ck, a.K, vec1);
                 if (!BWD && TWO) v2 = load_k4(a.A2, a.lda2, row, ck, a.K, vec2);
             }
+            if (!BWD && TWO) f2[it] = (a.scale2 && row < a.n) ? a.scale2[row] : 1.f;
             p1[it] = v1;
             if (!BWD && TWO) p2[it] = v2;
         }
@@ -535,9 +577,21 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
             for (int w = 0; w < KC; ++w)
                 pw[w] = (strip * 32 + m < a.n && 32 * w < a.K) ? a.mask[(strip * 32 + m) * a.mask_words + w] : 0u;
         }
+        if (!BWD) {
+#pragma unroll
+            for (int it = 0; it < PN; ++it) {
+                const int64_t row = strip * 32 + rn + (64 / LN) * it;
+                fo[it] = (a.scale_o1 && row < a.n) ? a.scale_o1[row] : 1.f;
+            }
+        }
     };
     if (first < n_strips) fetch(first);
     for (int64_t strip = first; strip < n_strips; strip += step) {
+        float out_f[BWD ? 1 : PN]; // output factors of this strip's rows (the fetch below overwrites fo)
+        if (!BWD) {
+#pragma unroll
+            for (int it = 0; it < PN; ++it) out_f[it] = fo[it];
+        }
 #pragma unroll
         for (int it = 0; it < PK; ++it) *reinterpret_cast<float4 *>(&tl[rk + (64 / LK) * it][ck]) = p1[it];
         __builtin_amdgcn_wave_barrier();
@@ -547,7 +601,10 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
         __builtin_amdgcn_wave_barrier();
         if (TWO && !BWD) { // the second operand strip takes the tile while the first product runs from registers
 #pragma unroll
-            for (int it = 0; it < PK; ++it) *reinterpret_cast<float4 *>(&tl[rk + (64 / LK) * it][ck]) = p2[it];
+            for (int it = 0; it < PK; ++it) {
+                if (a.scale2) scale4(p2[it], f2[it]);
+                *reinterpret_cast<float4 *>(&tl[rk + (64 / LK) * it][ck]) = p2[it];
+            }
             __builtin_amdgcn_wave_barrier();
         }
         const bool more = strip + step < n_strips;
@@ -631,7 +688,8 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
         // Outputs leave through the wavefront's tile so that a row goes out as 16-byte stores
         // (register r of lane (m, h) is strip row 8*(r/4) + 4*h + r%4, column 32 t + m); layouts that
         // do not allow 16-byte stores write the registers directly.
-        auto store_tile = [&](const floatx16 (&o)[NC], float *O, int64_t ldo, bool vec_ok) {
+        // `rs`: per-row factor applied on the way out (forward outputs kept in the scaled layout), or NULL.
+        auto store_tile = [&](const floatx16 (&o)[NC], float *O, int64_t ldo, bool vec_ok, const float *rs) {
             if (vec_ok) {
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -642,8 +700,15 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
 #pragma unroll
                 for (int it = 0; it < PN; ++it) {
                     const int64_t row = row0 + rn + (64 / LN) * it;
-                    const float4 v = *reinterpret_cast<const float4 *>(&tl[rn + (64 / LN) * it][cn]);
-                    if (row < a.n && cn < a.Nout) *reinterpret_cast<float4 *>(O + row * ldo + cn) = v;
+                    float4 v = *reinterpret_cast<const float4 *>(&tl[rn + (64 / LN) * it][cn]);
+                    if (row < a.n && cn < a.Nout) {
+                        if constexpr (!BWD) {
+                            if (rs) scale4(v, out_f[it]);
+                        } else { // backward: the accumulators leave no register for a factor fetched ahead
+                            if (rs) scale4(v, rs[row]);
+                        }
+                        *reinterpret_cast<float4 *>(O + row * ldo + cn) = v;
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
             } else {
@@ -652,14 +717,14 @@ __global__ __launch_bounds__(256, 2) void pair_strip64_kernel(const PairArgs a)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int64_t orow = row0 + 8 * (r / 4) + 4 * h + (r % 4);
-                        if (orow < a.n && 32 * t + m < a.Nout) O[orow * ldo + 32 * t + m] = o[t][r];
+                        if (orow < a.n && 32 * t + m < a.Nout) O[orow * ldo + 32 * t + m] = rs ? o[t][r] * rs[orow] : o[t][r];
                     }
             }
         };
         const bool nout4 = a.Nout % 4 == 0;
-        store_tile(acc1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0);
+        store_tile(acc1, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0, a.scale_o1);
         if constexpr (BWD && TWO) {
-            if (a.O2) store_tile(acc2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0);
+            if (a.O2) store_tile(acc2, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0, nullptr);
         }
         if (!BWD && a.act == SLICEGCN_ACT_RELU && lane < 32 && row0 + lane < a.n) {
 #pragma unroll
@@ -764,6 +829,7 @@ struct ReduceArgs {
     int32_t stride;                     // 2*w_in*w_out + 2*w_out; compact: w_in*w_out + w_out
     int32_t compact;                    // 1: no self term and no slot for it: [Z^T dP | colsum dP]
     int32_t rows_per_block = RED_ROWS;  // tiled kernels: node rows per workgroup (one partial each)
+    const float *hin_scale = nullptr;   // rows of Hin are multiplied by hin_scale[row] when read (Hin stored as D~^-1/2 Hin)
 };
 
 // Partial weight gradients, tiled: grid = (row blocks, w_in tiles, w_out tiles), every workgroup writes its
@@ -798,13 +864,17 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
 
     const int lr = tid >> 3, lc = (tid & 7) * 4; // this thread's float4 of each 32 x 32 tile
     float4 z, hh, p, g;
+    float hf = 1.f; // factor of this thread's row of Hin (scaled layout); applied when the registers go to LDS
     auto fetch = [&](int64_t r0) { // this thread's share of the four tiles of rows [r0, r0 + 32)
         const int64_t row = r0 + lr;
         z = make_float4(0.f, 0.f, 0.f, 0.f); hh = z; p = z; g = z;
         if (row < r_end) {
             if (i_base + lc < a.w_in) {
                 z = load_k4(a.Z, a.ldz, row, i_base + lc, a.w_in, vz);
-                if (self) hh = load_k4(a.Hin, a.ldi, row, i_base + lc, a.w_in, vh);
+                if (self) {
+                    hh = load_k4(a.Hin, a.ldi, row, i_base + lc, a.w_in, vh);
+                    if (a.hin_scale) hf = a.hin_scale[row];
+                }
             }
             if (j_base + lc < a.w_out) {
                 g = load_k4(a.dHout, a.ldo, row, j_base + lc, a.w_out, vg);
@@ -822,6 +892,7 @@ __global__ __launch_bounds__(256) void grad_partial_mfma_kernel(const ReduceArgs
     };
     fetch(r_begin);
     for (int64_t r0 = r_begin; r0 < r_end; r0 += RED_RK) {
+        if (a.hin_scale) scale4(hh, hf);
         *reinterpret_cast<float4 *>(&Zs[lr][lc]) = z;
         *reinterpret_cast<float4 *>(&Hs[lr][lc]) = hh;
         *reinterpret_cast<float4 *>(&Ps[lr][lc]) = p;
@@ -908,6 +979,7 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
     float sum_p = 0.f, sum_g = 0.f; // column m of dP and of dHout over the node rows 2s + h
 
     float4 pz[4], ph[4], pg[4];
+    float hf[4] = {1.f, 1.f, 1.f, 1.f}; // factors of the rows of Hin this lane loads (scaled layout); applied on the way to LDS
     uint32_t pw = ~0u;
     auto fetch = [&](int64_t r0) {
 #pragma unroll
@@ -917,7 +989,10 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
             if (row < r_end) {
                 if (lc < a.w_in) {
                     z = load_k4(a.Z, a.ldz, row, lc, a.w_in, vz);
-                    if (self) hh = load_k4(a.Hin, a.ldi, row, lc, a.w_in, vh);
+                    if (self) {
+                        hh = load_k4(a.Hin, a.ldi, row, lc, a.w_in, vh);
+                        if (a.hin_scale) hf[it] = a.hin_scale[row];
+                    }
                 }
                 if (lc < a.w_out) g = load_k4(a.dHout, a.ldo, row, lc, a.w_out, vg);
             }
@@ -929,6 +1004,7 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
     for (int64_t strip = w_id; strip < n_strips; strip += n_waves) { // wavefront w takes strips w, w + n_waves, ...
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
+            if (a.hin_scale) scale4(ph[it], hf[it]);
             *reinterpret_cast<float4 *>(&zs[lr + 8 * it][lc]) = pz[it];
             *reinterpret_cast<float4 *>(&hs[lr + 8 * it][lc]) = ph[it];
             *reinterpret_cast<float4 *>(&gs[lr + 8 * it][lc]) = pg[it];
@@ -1010,15 +1086,20 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
     for (int j = 0; j < NJ; ++j) { sum_p[j] = 0.f; sum_g[j] = 0.f; }
 
     float4 pz[PI], ph[PI], pg[PJ];
+    float hf[PI]; // factors of the rows of Hin this lane loads (scaled layout); applied on the way to LDS
     uint32_t pw = ~0u; // lane l < SR * NJ: word l % NJ of strip row l / NJ
     auto fetch = [&](int64_t r0) {
 #pragma unroll
         for (int it = 0; it < PI; ++it) {
             const int64_t row = r0 + ri + (64 / LI) * it;
             float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z;
+            hf[it] = 1.f;
             if (row < a.n && ci < a.w_in) {
                 z = load_k4(a.Z, a.ldz, row, ci, a.w_in, vz);
-                if (self) hh = load_k4(a.Hin, a.ldi, row, ci, a.w_in, vh);
+                if (self) {
+                    hh = load_k4(a.Hin, a.ldi, row, ci, a.w_in, vh);
+                    if (a.hin_scale) hf[it] = a.hin_scale[row];
+                }
             }
             pz[it] = z; ph[it] = hh;
         }
@@ -1039,6 +1120,7 @@ __global__ __launch_bounds__(256, WPS) void grad_strip64_kernel(const ReduceArgs
     for (int64_t strip = w_id; strip < n_strips; strip += n_waves) { // wavefront w takes strips w, w + n_waves, ...
 #pragma unroll
         for (int it = 0; it < PI; ++it) {
+            if (a.hin_scale) scale4(ph[it], hf[it]);
             *reinterpret_cast<float4 *>(&zs[ri + (64 / LI) * it][ci]) = pz[it];
             *reinterpret_cast<float4 *>(&hs[ri + (64 / LI) * it][ci]) = ph[it];
         }
@@ -1398,8 +1480,11 @@ int check_layer(const slicegcn_graph *g, const slicegcn_layer_desc *d, const sli
     SG_REQUIRE(g && d && p, SLICEGCN_EINVAL, "%s: NULL graph, desc or params", who);
     SG_REQUIRE(d->w_in >= 1 && d->w_out >= 1, SLICEGCN_EINVAL, "%s: widths must be >= 1", who);
     SG_REQUIRE(d->act == SLICEGCN_ACT_NONE || d->act == SLICEGCN_ACT_RELU, SLICEGCN_EINVAL, "%s: unknown act %d", who, d->act);
-    SG_REQUIRE((d->flags & ~(SLICEGCN_LAYER_Z_VALID | SLICEGCN_LAYER_TRANSFORM_FIRST | SLICEGCN_LAYER_ORDER_AUTO)) == 0, SLICEGCN_EINVAL,
+    SG_REQUIRE((d->flags & ~(SLICEGCN_LAYER_Z_VALID | SLICEGCN_LAYER_TRANSFORM_FIRST | SLICEGCN_LAYER_ORDER_AUTO |
+                             SLICEGCN_LAYER_IN_SCALED | SLICEGCN_LAYER_OUT_SCALED)) == 0, SLICEGCN_EINVAL,
                "%s: unknown flag bits 0x%x", who, d->flags);
+    SG_REQUIRE(!((d->flags & (SLICEGCN_LAYER_IN_SCALED | SLICEGCN_LAYER_OUT_SCALED)) && transform_first(d)), SLICEGCN_EINVAL,
+               "%s: the scaled layout needs the aggregate-first order", who);
     SG_REQUIRE(!((d->flags & SLICEGCN_LAYER_TRANSFORM_FIRST) && (d->flags & SLICEGCN_LAYER_ORDER_AUTO)), SLICEGCN_EINVAL,
                "%s: TRANSFORM_FIRST and ORDER_AUTO exclude each other", who);
     SG_REQUIRE(!((d->flags & SLICEGCN_LAYER_Z_VALID) && transform_first(d)), SLICEGCN_EINVAL,
@@ -1605,7 +1690,9 @@ extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_
     if (transform_first(desc)) return layer_fwd_transform_first(g, desc, params, Hin, ldi, Hout, ldo, saved, ws, ws_bytes, stream);
 
     if (!(desc->flags & SLICEGCN_LAYER_Z_VALID))
-        if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, ws, ws_bytes, stream)) return rc;
+        if (int rc = launch_spmm(g, g->fwd, Hin, ldi, desc->w_in, saved->Z, saved->ldz, nullptr, 0, ws, ws_bytes, stream,
+                                 (desc->flags & SLICEGCN_LAYER_IN_SCALED) != 0))
+            return rc;
 
     PairArgs a;
     a.A1 = saved->Z; a.lda1 = saved->ldz;
@@ -1615,6 +1702,8 @@ extern "C" int slicegcn_layer_fwd(const slicegcn_graph *g, const slicegcn_layer_
     a.O1 = Hout; a.ldo1 = ldo; a.O2 = nullptr; a.ldo2 = 0;
     a.mask = desc->act == SLICEGCN_ACT_RELU ? saved->mask : nullptr; a.mask_words = saved->mask_words;
     a.n = g->n; a.K = desc->w_in; a.Nout = desc->w_out; a.ldw = desc->w_out; a.act = desc->act;
+    a.scale2 = ((desc->flags & SLICEGCN_LAYER_IN_SCALED) && params->W_self) ? g->sqrtd : nullptr;
+    a.scale_o1 = (desc->flags & SLICEGCN_LAYER_OUT_SCALED) ? g->dinv : nullptr;
     ProfScope prof(SLICEGCN_PROF_DENSE_FWD, desc->w_out, stream);
     return launch_pair<false>(a, stream);
 }
@@ -1679,6 +1768,7 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         r.mask = mask; r.mask_words = saved->mask_words;
         r.partial = partial; r.n = g->n; r.w_in = w_in; r.w_out = w_out; r.stride = stride; r.compact = 0;
         r.rows_per_block = layer_grad_rows(g->n, w_in, w_out);
+        r.hin_scale = (desc->flags & SLICEGCN_LAYER_IN_SCALED) ? g->sqrtd : nullptr;
         dim3 grid((unsigned)nb, (unsigned)((w_in + RED_TILE - 1) / RED_TILE), (unsigned)((w_out + RED_TILE - 1) / RED_TILE));
         int64_t n_partials = nb;
         if (w_in <= 32 && w_out <= 32 && g->n >= 65536) {
@@ -1730,12 +1820,14 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
         a.O2 = params->W_self ? dHin : nullptr; a.ldo2 = ldgi;
         a.mask = const_cast<uint32_t *>(mask); a.mask_words = saved->mask_words;
         a.n = g->n; a.K = w_out; a.Nout = w_in; a.ldw = w_out; a.act = desc->act;
+        a.scale_o1 = g->dinv; // dZ is staged as D~^-1/2 dZ: its aggregation then skips the stored values
         {
             ProfScope prof(SLICEGCN_PROF_DENSE_BWD, w_in, stream);
             if (int rc = launch_pair<true>(a, stream)) return rc;
         }
         // padding columns of dZ are never read as data: the aggregation masks them on store
-        if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, agg_ws, agg_ws_bytes, stream))
+        if (int rc = launch_spmm(g, g->tr, dZ, ldz, w_in, dHin, ldgi, params->W_self ? dHin : nullptr, ldgi, agg_ws, agg_ws_bytes, stream,
+                                 true))
             return rc;
     }
     return SLICEGCN_OK;

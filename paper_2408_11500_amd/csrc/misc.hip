@@ -110,6 +110,19 @@ __global__ __launch_bounds__(256) void copy_cols_vec_kernel(const float *src, in
     }
 }
 
+// dst[r, c] = scale[r] * src[r, c] for c < w, 0 for w <= c < w_pad (one thread per element of the padded row)
+// src and dst may be the same view (scaling in place): a thread reads only the element it writes.
+__global__ __launch_bounds__(256) void scale_rows_kernel(const float *src, int64_t lds_, float *dst, int64_t ldd,
+                                                         int64_t n, int32_t w, int32_t w_pad, const float *__restrict__ scale)
+{
+    const int64_t total = n * (int64_t)w_pad;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t r = t / w_pad;
+        const int c = (int)(t - r * w_pad);
+        dst[r * ldd + c] = c < w ? scale[r] * src[r * lds_ + c] : 0.f;
+    }
+}
+
 // dst[r, c] += src[r, c] for c < w; 16 bytes per thread when VEC (aligned bases, lds and w multiples of 4).
 template <bool VEC>
 __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ dst, int64_t ldd, const float *__restrict__ src,
@@ -240,6 +253,17 @@ extern "C" int slicegcn_slice_feature(const float *X, int64_t n, int64_t ldx, in
     SG_REQUIRE(ldxs >= end - start, SLICEGCN_EINVAL, "slice_feature: ldxs smaller than the slice width");
     SG_REQUIRE(ldxs <= INT32_MAX, SLICEGCN_EINVAL, "slice_feature: ldxs too large");
     return launch_copy_cols(X + start, ldx, Xs, ldxs, n, end - start, (int32_t)ldxs, nullptr, as_stream(stream));
+}
+
+extern "C" int slicegcn_scale_rows(const slicegcn_graph *g, const float *X, int64_t ldx, int32_t width, float *Xs, int64_t ldxs,
+                                   void *stream)
+{
+    SG_REQUIRE(g && X && Xs, SLICEGCN_EINVAL, "scale_rows: NULL pointer");
+    SG_REQUIRE(width >= 1 && ldx >= width && ldxs >= width && ldxs <= INT32_MAX, SLICEGCN_EINVAL,
+               "scale_rows: need 1 <= width <= ldx, ldxs");
+    scale_rows_kernel<<<grid_for(g->n * ldxs), 256, 0, as_stream(stream)>>>(X, ldx, Xs, ldxs, g->n, width, (int32_t)ldxs, g->dinv);
+    SG_LAUNCH_CHECK();
+    return SLICEGCN_OK;
 }
 
 extern "C" int slicegcn_concat(int32_t k, const float *const *Hs, const int64_t *lds, const int32_t *widths,

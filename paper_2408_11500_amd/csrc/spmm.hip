@@ -46,6 +46,7 @@ struct SpmmArgs {
     const float *X;
     float *Y;
     const float *Add;
+    const float *dinv;    // factored form only: X rows come pre-scaled by dinv[u], sums are scaled by dinv[row] on store
     float *scratch;
     int64_t ldx, ldy, ldadd;
     uint32_t ldx_bytes;   // S32 kernels: byte stride of X rows (n * ldx * 4 < 2^32, n and ldx * 4 < 2^24)
@@ -69,6 +70,8 @@ template <> struct Acc<4> {
     float4 v;
     __device__ Acc() : v(make_float4(0.f, 0.f, 0.f, 0.f)) {}
     __device__ void fma(float a, const float4 &x) { v.x += a * x.x; v.y += a * x.y; v.z += a * x.z; v.w += a * x.w; }
+    __device__ void plus(const float4 &x) { v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w; }
+    __device__ void scale(float a) { v.x *= a; v.y *= a; v.z *= a; v.w *= a; }
     __device__ void add(const Acc &o) { v.x += o.v.x; v.y += o.v.y; v.z += o.v.z; v.w += o.v.w; }
     __device__ float get(int i) const { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 };
@@ -76,6 +79,8 @@ template <> struct Acc<1> {
     float v;
     __device__ Acc() : v(0.f) {}
     __device__ void fma(float a, float x) { v += a * x; }
+    __device__ void plus(float x) { v += x; }
+    __device__ void scale(float a) { v *= a; }
     __device__ void add(const Acc &o) { v += o.v; }
     __device__ float get(int) const { return v; }
 };
@@ -104,6 +109,11 @@ __device__ inline typename Ld<V>::T load_x(const SpmmArgs &a, int c, int col)
     }
     return Ld<V>::load(a.X + (int64_t)c * a.ldx + col);
 }
+
+// Factored form (FACT): the operand rows already carry dinv[u], so every stored entry weighs 1 (the value stream is
+// not read, its cross-lane reads vanish and the multiply-adds fold to adds) and the row sum is scaled by dinv[row] on store.
+template <bool FACT> __device__ inline float ld_val(const SpmmArgs &a, int idx) { return FACT ? 1.f : a.vals[idx]; }
+template <bool FACT> __device__ inline float shfl_val(float v, int src) { return FACT ? 1.f : __shfl(v, src, 64); }
 
 template <int V> __device__ inline Acc<V> shfl_xor_acc(const Acc<V> &a, int mask);
 template <> __device__ inline Acc<4> shfl_xor_acc<4>(const Acc<4> &a, int mask)
@@ -145,7 +155,7 @@ __device__ inline void store_cols(const Acc<V> &acc, float *y_row, const float *
 // group grp through cross-lane reads, eight sub-steps (eight gathers per lane) at a time.  A
 // full chunk (cnt >= 64) runs without any per-entry test.  Every lane of the wavefront must call
 // this (lanes past the last column pass a valid `col` and drop their result).
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, float v_l, int cnt, int grp, int col)
 {
     constexpr int G = 64 / LPR; // lane groups = entries per sub-step
@@ -160,7 +170,7 @@ __device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, flo
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 c[u] = __shfl(c_l, (t + u) * G + grp, 64);
-                v[u] = __shfl(v_l, (t + u) * G + grp, 64);
+                v[u] = shfl_val<FACT>(v_l, (t + u) * G + grp);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
@@ -176,7 +186,7 @@ __device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, flo
             for (int u = 0; u < U; ++u) {
                 const int src = ((t + u) * G + grp) & 63;
                 c[u] = __shfl(c_l, src, 64);
-                v[u] = __shfl(v_l, src, 64);
+                v[u] = shfl_val<FACT>(v_l, src);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) x[u] = load_x<V, S32>(a, c[u], col);
@@ -189,9 +199,10 @@ __device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, flo
 
 // Write an item's (or a row's) sum: to the output row, or to its partial-sum slot.
 template <int V>
-__device__ inline void store_result(const Acc<V> &acc, const SpmmArgs &a, int row, int dst, int col)
+__device__ inline void store_result(Acc<V> acc, const SpmmArgs &a, int row, int dst, int col)
 {
     if (dst >= 0) {
+        if (a.dinv) acc.scale(a.dinv[row]); // factored form: the row's own factor (partial sums stay unscaled)
         store_cols<V>(acc, a.Y + (int64_t)row * a.ldy, a.Add ? a.Add + (int64_t)row * a.ldadd : nullptr, col, a.col_end,
                       a.vec_store != 0);
     } else {
@@ -205,7 +216,7 @@ constexpr int NO_UNIT = INT32_MIN;
 // One gather phase of the tiny-row path: sub-round t hands unit (t * GROUPS + grp) of the wavefront
 // to lane group grp.  c_l / v_l hold, per lane, four (column, value) pairs of the unit that lane
 // owns (column -1 = no entry).  Two sub-rounds (eight gathers per lane) are in flight at a time.
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const int (&c_l)[4], const float (&v_l)[4],
                                     int grp, int colc)
 {
@@ -220,7 +231,7 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 cc[u][i] = __shfl(c_l[i], (t0 + u) * G + grp, 64);
-                vv[u][i] = __shfl(v_l[i], (t0 + u) * G + grp, 64);
+                vv[u][i] = shfl_val<FACT>(v_l[i], (t0 + u) * G + grp);
             }
         typename L::T x[2][4];
 #pragma unroll
@@ -241,7 +252,7 @@ __device__ inline void batch_gather(Acc<V> (&acc)[8], const SpmmArgs &a, const i
 // Rows of at most TINY_ROW (= 4) entries: 8 * GROUPS rows per wavefront.  Lane i owns row i
 // (entries [beg_l, end_l), destination dst_l, NO_UNIT = nothing) and loads its entries; the gather
 // phase hands them to the lane groups.  Every lane of the wavefront must call this.
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int row_l, int dst_l, int lane)
 {
     constexpr int G = 64 / LPR;
@@ -257,9 +268,9 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
         const int idx = beg_l + i;
         const bool ok = idx < end_l;
         c_l[i] = ok ? a.colidx[idx] : -1;
-        v_l[i] = ok ? a.vals[idx] : 0.f;
+        v_l[i] = ok ? ld_val<FACT>(a, idx) : 0.f;
     }
-    batch_gather<LPR, V, S32>(acc, a, c_l, v_l, grp, colc);
+    batch_gather<LPR, V, S32, FACT>(acc, a, c_l, v_l, grp, colc);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const int d = __shfl(dst_l, t * G + grp, 64);
@@ -274,7 +285,7 @@ __device__ inline void batch_units(const SpmmArgs &a, int beg_l, int end_l, int 
 // entry base + i, and the next 64 are requested before the current ones are consumed.  (Giving a
 // wavefront several items and prefetching across them was measured and changes nothing: the
 // kernel is bound by the traffic of the gathers, not by the latency of its index loads.)
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __device__ __forceinline__ void wave_items_body(const SpmmArgs &a, int block)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -299,16 +310,16 @@ __device__ __forceinline__ void wave_items_body(const SpmmArgs &a, int block)
     Acc<V> acc;
     int idx = beg + lane;
     int c_l = a.colidx[idx < end ? idx : beg];
-    float v_l = a.vals[idx < end ? idx : beg];
+    float v_l = ld_val<FACT>(a, idx < end ? idx : beg);
     for (int base = beg; base < end; base += 64) {
         int c_n = 0;
         float v_n = 0.f;
         if (base + 64 < end) { // wavefront-uniform
             idx = base + 64 + lane;
             c_n = a.colidx[idx < end ? idx : beg];
-            v_n = a.vals[idx < end ? idx : beg];
+            v_n = ld_val<FACT>(a, idx < end ? idx : beg);
         }
-        gather_chunk<LPR, V, S32>(acc, a, c_l, v_l, end - base, grp, colc);
+        gather_chunk<LPR, V, S32, FACT>(acc, a, c_l, v_l, end - base, grp, colc);
         c_l = c_n;
         v_l = v_n;
     }
@@ -323,7 +334,7 @@ __device__ __forceinline__ void wave_items_body(const SpmmArgs &a, int block)
 // reads the item's (column, value) pairs with one read per LPR entries (lane `sub` holds entries
 // sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
 // gather takes its pair from the holding lane by a cross-lane read, eight gathers in flight.
-template <int LPR, int V, bool S32, int GI_MAX>
+template <int LPR, int V, bool S32, int GI_MAX, bool FACT>
 __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
 {
     constexpr int G = 64 / LPR;                 // items in flight per wavefront
@@ -362,7 +373,7 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
         const int e = beg + sub + LPR * k;
         const bool ok = e < end;
         c_k[k] = ok ? a.colidx[e] : 0;
-        v_k[k] = ok ? a.vals[e] : 0.f;
+        v_k[k] = ok ? ld_val<FACT>(a, e) : 0.f;
     }
     for (int r = 0; r < rounds; ++r) {
         const int row = __shfl(d.x, r * G + grp, 64), dst = __shfl(d.w, r * G + grp, 64);
@@ -376,7 +387,7 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
             const int e = nbeg + sub + LPR * k;
             const bool ok = e < nend;
             c_n[k] = ok ? a.colidx[e] : 0;
-            v_n[k] = ok ? a.vals[e] : 0.f;
+            v_n[k] = ok ? ld_val<FACT>(a, e) : 0.f;
         }
         Acc<V> acc;
 #pragma unroll
@@ -389,7 +400,7 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
             for (int u = 0; u < U; ++u) {
                 const int jj = j0 + u;
                 const int cc = __shfl(c_k[jj / LPR < K ? jj / LPR : 0], gbase + jj % LPR, 64);
-                v[u] = __shfl(v_k[jj / LPR < K ? jj / LPR : 0], gbase + jj % LPR, 64);
+                v[u] = shfl_val<FACT>(v_k[jj / LPR < K ? jj / LPR : 0], gbase + jj % LPR);
                 c[u] = jj < len ? cc : 0; // an absent entry re-reads row 0 and is not accumulated
             }
 #pragma unroll
@@ -408,7 +419,7 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
 
 // Rows of at most TINY_ROW entries, 64 consecutive positions of the schedule per wavefront (consecutive
 // rows in natural order).
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __device__ __forceinline__ void tiny_rows_body(const SpmmArgs &a, int block)
 {
     constexpr int UNITS = 8 * (64 / LPR); // rows per wavefront
@@ -421,17 +432,17 @@ __device__ __forceinline__ void tiny_rows_body(const SpmmArgs &a, int block)
         const int b = a.rowptr[row], e = a.rowptr[row + 1];
         if (e - b <= TINY_ROW) { row_l = row; beg_l = b; end_l = e; dst_l = row; }
     }
-    batch_units<LPR, V, S32>(a, beg_l, end_l, row_l, dst_l, lane);
+    batch_units<LPR, V, S32, FACT>(a, beg_l, end_l, row_l, dst_l, lane);
 }
 
-template <int LPR, int V, bool S32>
-__global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a) { wave_items_body<LPR, V, S32>(a, blockIdx.x); }
+template <int LPR, int V, bool S32, bool FACT>
+__global__ __launch_bounds__(256) void spmm_wave_items_kernel(const SpmmArgs a) { wave_items_body<LPR, V, S32, FACT>(a, blockIdx.x); }
 
-template <int LPR, int V, bool S32, int GI_MAX>
-__global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a) { group_items_body<LPR, V, S32, GI_MAX>(a, blockIdx.x); }
+template <int LPR, int V, bool S32, int GI_MAX, bool FACT>
+__global__ __launch_bounds__(256) void spmm_group_items_kernel(const SpmmArgs a) { group_items_body<LPR, V, S32, GI_MAX, FACT>(a, blockIdx.x); }
 
-template <int LPR, int V, bool S32>
-__global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a) { tiny_rows_body<LPR, V, S32>(a, blockIdx.x); }
+template <int LPR, int V, bool S32, bool FACT>
+__global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a) { tiny_rows_body<LPR, V, S32, FACT>(a, blockIdx.x); }
 
 // All three item kinds in one launch: workgroups [0, g1) take wavefront items, [g1, g1 + g2)
 // lane-group items, the rest tiny rows (g1 and g2 are multiples of n_classes, so workgroup b still
@@ -439,13 +450,13 @@ __global__ __launch_bounds__(256) void spmm_tiny_rows_kernel(const SpmmArgs a) {
 // each of three launches would pay its own ramp-up and its own chain of dependent loads; in one launch
 // they overlap (cfg2: 0.075 -> 0.056 ms per call).  Large graphs keep the three launches: there the
 // class pieces must have the L2s to themselves before the whole rows start (merged: cfg5 4.09 -> 4.30 ms).
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 __global__ __launch_bounds__(256) void spmm_merged_kernel(const SpmmArgs a, int g1, int g2)
 {
     const int b = blockIdx.x; // uniform per workgroup
-    if (b < g1) wave_items_body<LPR, V, S32>(a, b);
-    else if (b < g1 + g2) group_items_body<LPR, V, S32, ITEM_SHORT>(a, b - g1);
-    else tiny_rows_body<LPR, V, S32>(a, b - g1 - g2);
+    if (b < g1) wave_items_body<LPR, V, S32, FACT>(a, b);
+    else if (b < g1 + g2) group_items_body<LPR, V, S32, ITEM_SHORT, FACT>(a, b - g1);
+    else tiny_rows_body<LPR, V, S32, FACT>(a, b - g1 - g2);
 }
 
 // Rows with several items: add the partial slots in order.  One thread per (row, column); eight
@@ -469,12 +480,13 @@ __global__ __launch_bounds__(256) void spmm_fix_kernel(const SpmmArgs a, int32_t
         for (int i = 0; i < 8; ++i) acc += q[i];
     }
     for (; s < f.z; ++s) acc += p[(int64_t)s * a.slot_cols];
+    if (a.dinv) acc *= a.dinv[f.x]; // factored form: the row's own factor
     const int col = a.col0 + j;
     if (a.Add) acc += a.Add[(int64_t)f.x * a.ldadd + col];
     a.Y[(int64_t)f.x * a.ldy + col] = acc;
 }
 
-template <int LPR, int V, bool S32>
+template <int LPR, int V, bool S32, bool FACT>
 int launch_variant(const SpmmArgs &a, hipStream_t stream)
 {
     constexpr int units_per_block = 4 * 8 * (64 / LPR);
@@ -483,20 +495,20 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
     const int64_t g3 = (a.n + units_per_block - 1) / units_per_block;
     SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX && g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
     if (a.item_max <= ITEM_SHORT && g1 + g2 + g3 <= INT32_MAX) { // cache-resident graph: one launch
-        spmm_merged_kernel<LPR, V, S32><<<(unsigned)(g1 + g2 + g3), 256, 0, stream>>>(a, (int)g1, (int)g2);
+        spmm_merged_kernel<LPR, V, S32, FACT><<<(unsigned)(g1 + g2 + g3), 256, 0, stream>>>(a, (int)g1, (int)g2);
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
     }
     if (g1 > 0) {
-        spmm_wave_items_kernel<LPR, V, S32><<<(unsigned)g1, 256, 0, stream>>>(a);
+        spmm_wave_items_kernel<LPR, V, S32, FACT><<<(unsigned)g1, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
     if (g2 > 0) {
-        if (a.item_max <= ITEM_SHORT) spmm_group_items_kernel<LPR, V, S32, ITEM_SHORT><<<(unsigned)g2, 256, 0, stream>>>(a);
-        else spmm_group_items_kernel<LPR, V, S32, ITEM_LONG><<<(unsigned)g2, 256, 0, stream>>>(a);
+        if (a.item_max <= ITEM_SHORT) spmm_group_items_kernel<LPR, V, S32, ITEM_SHORT, FACT><<<(unsigned)g2, 256, 0, stream>>>(a);
+        else spmm_group_items_kernel<LPR, V, S32, ITEM_LONG, FACT><<<(unsigned)g2, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
-    spmm_tiny_rows_kernel<LPR, V, S32><<<(unsigned)g3, 256, 0, stream>>>(a);
+    spmm_tiny_rows_kernel<LPR, V, S32, FACT><<<(unsigned)g3, 256, 0, stream>>>(a);
     SG_LAUNCH_CHECK();
     return SLICEGCN_OK;
 }
@@ -504,8 +516,12 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
 template <int LPR, int V>
 int launch_kernels(const SpmmArgs &a, hipStream_t stream)
 {
-    if (V == 4 && a.ldx_bytes != 0) return launch_variant<LPR, V, V == 4>(a, stream);
-    return launch_variant<LPR, V, false>(a, stream);
+    if (a.dinv) { // factored form
+        if (V == 4 && a.ldx_bytes != 0) return launch_variant<LPR, V, V == 4, true>(a, stream);
+        return launch_variant<LPR, V, false, true>(a, stream);
+    }
+    if (V == 4 && a.ldx_bytes != 0) return launch_variant<LPR, V, V == 4, false>(a, stream);
+    return launch_variant<LPR, V, false, false>(a, stream);
 }
 
 template <int V>
@@ -533,7 +549,8 @@ size_t spmm_workspace_bytes(const Csr &m, int32_t width)
 }
 
 int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t ldx, int32_t width,
-                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream)
+                float *Y, int64_t ldy, const float *Add, int64_t ldadd, void *ws, size_t ws_bytes, hipStream_t stream,
+                bool prescaled)
 {
     // 16-byte gathers need an aligned base, ld % 4 == 0 and room for the last vector of a row
     const bool vec_load = aligned16(X) && (ldx % 4 == 0) && ldx >= round_up(width, 4);
@@ -554,6 +571,7 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     SpmmArgs a;
     a.rowptr = m.rowptr; a.colidx = m.colidx; a.vals = m.vals; a.items = sc.items; a.fix = sc.fix; a.order = g->order;
     a.X = X; a.Y = Y; a.Add = Add; a.scratch = static_cast<float *>(ws);
+    a.dinv = prescaled ? g->dinv : nullptr;
     a.ldx = ldx; a.ldy = ldy; a.ldadd = Add ? ldadd : 0;
     const bool s32 = g->n < (1 << 24) && ldx * 4 < (1 << 24) && (int64_t)g->n * ldx * 4 < ((int64_t)1 << 32);
     a.ldx_bytes = s32 ? (uint32_t)(ldx * 4) : 0u;
@@ -637,13 +655,14 @@ int static_scratch(void **out)
 }
 } // namespace
 
-extern "C" int slicegcn_spmm_slice_static(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+extern "C" int slicegcn_spmm_slice_static(const slicegcn_graph *g, int op, const float *X, int64_t ldx,
                                           int32_t width, float *Y, int64_t ldy, void *stream)
 {
     SG_REQUIRE(g && X && Y, SLICEGCN_EINVAL, "spmm_slice_static: NULL argument");
+    SG_REQUIRE((op & ~(SLICEGCN_SPMM_TRANSPOSE | SLICEGCN_SPMM_PRESCALED)) == 0, SLICEGCN_EINVAL, "spmm_slice_static: unknown op bits 0x%x", op);
     SG_REQUIRE(width >= 1, SLICEGCN_EINVAL, "spmm_slice_static: width = %d < 1", width);
     SG_REQUIRE(ldx >= width && ldy >= width, SLICEGCN_EINVAL, "spmm_slice_static: leading dimension smaller than width");
-    const Csr &m = transpose ? g->tr : g->fwd;
+    const Csr &m = (op & SLICEGCN_SPMM_TRANSPOSE) ? g->tr : g->fwd;
     const size_t need = spmm_workspace_bytes(m, width);
     SG_REQUIRE(need <= (size_t)SLICEGCN_STATIC_WS_BYTES, SLICEGCN_EWORKSPACE,
                "spmm_slice_static: this graph and width need %zu bytes of partial sums, the built-in buffer holds %zu; "
@@ -651,20 +670,22 @@ extern "C" int slicegcn_spmm_slice_static(const slicegcn_graph *g, int transpose
     void *ptr = nullptr;
     if (need > 0)
         if (int rc = static_scratch(&ptr)) return rc;
-    return launch_spmm(g, m, X, ldx, width, Y, ldy, nullptr, 0, ptr, need, as_stream(stream));
+    return launch_spmm(g, m, X, ldx, width, Y, ldy, nullptr, 0, ptr, need, as_stream(stream), (op & SLICEGCN_SPMM_PRESCALED) != 0);
 }
 
-extern "C" size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int transpose, int32_t width)
+extern "C" size_t slicegcn_spmm_workspace_bytes(const slicegcn_graph *g, int op, int32_t width)
 {
     if (!g || width < 1) return 0;
-    return spmm_workspace_bytes(transpose ? g->tr : g->fwd, width);
+    return spmm_workspace_bytes((op & SLICEGCN_SPMM_TRANSPOSE) ? g->tr : g->fwd, width);
 }
 
-extern "C" int slicegcn_spmm_slice(const slicegcn_graph *g, int transpose, const float *X, int64_t ldx,
+extern "C" int slicegcn_spmm_slice(const slicegcn_graph *g, int op, const float *X, int64_t ldx,
                                    int32_t width, float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
 {
     SG_REQUIRE(g && X && Y, SLICEGCN_EINVAL, "spmm_slice: NULL argument");
+    SG_REQUIRE((op & ~(SLICEGCN_SPMM_TRANSPOSE | SLICEGCN_SPMM_PRESCALED)) == 0, SLICEGCN_EINVAL, "spmm_slice: unknown op bits 0x%x", op);
     SG_REQUIRE(width >= 1, SLICEGCN_EINVAL, "spmm_slice: width = %d < 1", width);
     SG_REQUIRE(ldx >= width && ldy >= width, SLICEGCN_EINVAL, "spmm_slice: leading dimension smaller than width");
-    return launch_spmm(g, transpose ? g->tr : g->fwd, X, ldx, width, Y, ldy, nullptr, 0, ws, ws_bytes, as_stream(stream));
+    return launch_spmm(g, (op & SLICEGCN_SPMM_TRANSPOSE) ? g->tr : g->fwd, X, ldx, width, Y, ldy, nullptr, 0, ws, ws_bytes,
+                       as_stream(stream), (op & SLICEGCN_SPMM_PRESCALED) != 0);
 }

@@ -29,7 +29,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_symbols()
-    assert len(names) == 28 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 29 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(L, n) is not None
 

@@ -201,6 +201,55 @@ def test_build_rejects_both_orders():
     assert e.value.status == B.EINVAL
 
 
+@pytest.mark.parametrize("case", ["ragged", "hubs", "hubs_dir", "dense"])
+@pytest.mark.parametrize("width", [3, 25, 32, 100, 301])
+def test_spmm_prescaled_operand(graphs, case, width):
+    """SLICEGCN_SPMM_PRESCALED: with X' = D~^-1/2 X from slicegcn_scale_rows the call returns the same A^ X (and
+    A^^T X) without reading the stored values; slicegcn_scale_rows itself is one rounding per element."""
+    n, o, g = graphs[case]
+    rng = np.random.default_rng(width + 100)
+    X = rng.standard_normal((n, width)).astype(np.float32)
+    Xd = padded(X, padded_ld(width))
+    Xs = torch.full((n, padded_ld(width)), np.nan, dtype=torch.float32, device="cuda")
+    sg.slicegcn_scale_rows(g, Xd, Xs, width=width)
+    got_s = Xs.cpu().numpy()
+    assert_close(got_s[:, :width], o.dinv[:, None] * X.astype(np.float64), "scaled rows", tol=1e-7)
+    assert np.all(got_s[:, width:] == 0.0)
+    for tr in (False, True):
+        Y = torch.full((n, width + 1), np.nan, dtype=torch.float32, device="cuda")
+        sg.slicegcn_spmm_slice(g, Xs[:, :width], Y[:, :width], transpose=tr, prescaled=True)
+        want = oracle.spmm(o, X.astype(np.float64), transpose=tr)
+        got = Y.cpu().numpy()
+        assert_close(got[:, :width], want, f"prescaled {case} w={width} transpose={tr}")
+        assert np.all(np.isnan(got[:, width:]))
+        bound = oracle.spmm(o, np.abs(X).astype(np.float64), transpose=tr) * TOL + 1e-30
+        assert np.all(np.abs(got[:, :width] - want) <= bound)
+        Y2 = torch.empty_like(Y)
+        sg.slicegcn_spmm_slice(g, Xs[:, :width], Y2[:, :width], transpose=tr, prescaled=True)
+        assert torch.equal(Y[:, :width], Y2[:, :width])
+
+
+def test_schedule_flags_do_not_change_results():
+    """The schedule-tuning build flags move rows of 33..64 entries between the wavefront and the lane-group kernels,
+    whose summation orders differ: results stay equal within rounding."""
+    rng = np.random.default_rng(77)
+    src, dst = hub_edges(20011, 160000, hubs=[1, 5000, 20010], hub_deg=6000, rng=rng)
+    n = 20011
+    o, g0 = build_both(src, dst, n)
+    X = rng.standard_normal((n, 32)).astype(np.float32)
+    Xd = padded(X, 32)
+    Y0 = torch.empty((n, 32), dtype=torch.float32, device="cuda")
+    sg.slicegcn_spmm_slice(g0, Xd, Y0)
+    assert_close(Y0.cpu().numpy(), oracle.spmm(o, X.astype(np.float64)), "default schedule")
+    for sched in (B.SCHED_LONG_ITEMS, B.SCHED_SHORT_ITEMS):
+        _, g = build_both(src, dst, n, sched=sched)
+        Y = torch.full((n, 32), np.nan, dtype=torch.float32, device="cuda")
+        sg.slicegcn_spmm_slice(g, Xd, Y)
+        assert_close(Y.cpu().numpy(), oracle.spmm(o, X.astype(np.float64)), f"schedule flags {sched}")
+        g.destroy()
+    g0.destroy()
+
+
 def test_spmm_argument_errors(graphs):
     n, o, g = graphs["tiny"]
     X = torch.zeros((n, 8), dtype=torch.float32, device="cuda")
@@ -353,6 +402,54 @@ def test_layer_transform_first_vs_oracle(graphs, case, shape, order, act, has_se
         assert e.value.status == B.EWORKSPACE
 
 
+@pytest.mark.parametrize("case", ["ragged", "hubs", "ragged_dir"])
+@pytest.mark.parametrize("shape", [(32, 32), (25, 64), (64, 64), (301, 128), (7, 5), (33, 130)])
+@pytest.mark.parametrize("has_self,out_scaled", [(True, True), (True, False), (False, True)])
+def test_layer_scaled_layout_vs_oracle(graphs, case, shape, has_self, out_scaled):
+    """IN_SCALED / OUT_SCALED: the layer reads D~^-1/2 Hin and (optionally) writes D~^-1/2 Hout; the aggregation then
+    skips the stored values, the self term and its weight gradient undo the row scaling.  Everything is compared with
+    the oracle's layer on the unscaled tensors; gradients are those of the unscaled activations."""
+    n, o, g = graphs[case]
+    w_in, w_out = shape
+    Hin, W_agg, b, W_self, b_self = layer_inputs(n, w_in, w_out, 19 * w_in + w_out, has_self)
+    Hs32 = (o.dinv[:, None] * Hin.astype(np.float64)).astype(np.float32)     # what the library is given
+    Hin64 = Hs32.astype(np.float64) / o.dinv[:, None]                         # the unscaled input it stands for
+    want, Zo, Po = oracle.layer_fwd(o, Hin64, W_agg, b, W_self, b_self, act=1)
+    layout = B.LAYER_IN_SCALED | (B.LAYER_OUT_SCALED if out_scaled else 0)
+    f = dict(dtype=torch.float32, device="cuda")
+    Hd = padded(Hs32, padded_ld(w_in))
+    Hout = torch.full((n, w_out + 2), np.nan, **f)
+    Z = torch.empty((n, padded_ld(w_in)), **f)[:, :w_in]
+    mask = torch.full((n, (w_out + 31) // 32), -1, dtype=torch.int32, device="cuda")
+    Wa, Ws = dev(W_agg), (dev(W_self) if has_self else None)
+    sg.slicegcn_layer_fwd(g, Hd, Wa, dev(b), Ws, dev(b_self) if has_self else None, Hout[:, :w_out], Z, mask, layout=layout)
+    got = Hout.cpu().numpy()
+    assert_close(Z.cpu().numpy(), Zo, "Z (unscaled)")
+    assert_close(got[:, :w_out], o.dinv[:, None] * want if out_scaled else want, "Hout")
+    assert np.all(np.isnan(got[:, w_out:]))
+    mask_bits = (Po > 0).astype(np.uint8)
+    differ = unpack_mask(mask.cpu().numpy(), w_out) != mask_bits
+    assert np.all(np.abs(Po[differ]) <= 1e-5 * np.sqrt(np.mean(Po * Po))), "mask differs outside the rounding band"
+    mask.copy_(torch.as_tensor(pack_mask(mask_bits)))
+    rng = np.random.default_rng(w_in + 3 * w_out)
+    dHout = rng.standard_normal((n, w_out)).astype(np.float32)
+    ref = oracle.layer_bwd(o, Hin64, Zo, mask_bits, W_agg, W_self, dHout, need_dHin=True)
+    dHin = torch.full((n, padded_ld(w_in)), np.nan, **f)[:, :w_in]
+    dW_agg = torch.empty((w_in, w_out), **f); db = torch.empty(w_out, **f)
+    dW_self = torch.empty((w_in, w_out), **f) if has_self else None
+    db_self = torch.empty(w_out, **f) if has_self else None
+    ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(g, w_in, w_out, True), dtype=torch.uint8, device="cuda")
+    sg.slicegcn_layer_bwd(g, Hd, Wa, Ws, padded(Zo.astype(np.float32), padded_ld(w_in)), mask, padded(dHout, padded_ld(w_out)), dHin,
+                          dW_agg, db, dW_self, db_self, ws, layout=layout)
+    names = [("dW_agg", dW_agg), ("db", db), ("dHin", dHin)] + ([("dW_self", dW_self), ("db_self", db_self)] if has_self else [])
+    for name, t in names:
+        assert_close(t.cpu().numpy(), ref[name], name)
+    with pytest.raises(B.SliceGCNError) as e:       # the scaled layout is defined for the aggregate-first order only
+        sg.slicegcn_layer_fwd(g, Hd, Wa, dev(b), Ws, dev(b_self) if has_self else None, Hout[:, :w_out], Z, mask,
+                              layout=layout, order=B.LAYER_TRANSFORM_FIRST)
+    assert e.value.status == B.EINVAL
+
+
 def test_layer_order_flag_errors(graphs):
     n, o, g = graphs["tiny"]
     f = dict(dtype=torch.float32, device="cuda")
@@ -457,7 +554,7 @@ def test_concat_fwd_bwd():
 
 
 # ---------------------------------------------------------------------------------------
-def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0, order=0):
+def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0, order=0, scaled=True):
     """All k slices x L layers + encoding/concat, forward and backward, against the oracle.  With
     ``classifier`` the upstream gradient comes from the classifier MLP and the cross-entropy loss
     (also checked against the oracle) instead of a seeded random matrix."""
@@ -467,7 +564,7 @@ def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0
     sl, _ = sg.slicegcn_slice_strategy(w.feat, k, scale)
     assert sl == oracle.slice_strategy(w.feat, k, scale)[0]
     c = sl[0][1] - sl[0][0]  # every slice of a strategy has the same width
-    st = SliceStack(g, n, k, c, slice_hidden, L, order=order)
+    st = SliceStack(g, n, k, c, slice_hidden, L, order=order, scaled=scaled)
     X = configs.features(w)
     Xd = X.cuda()
     E = configs.normal_matrix(w.seed, configs.STREAM_E, k, slice_hidden, std=0.1)
@@ -555,6 +652,7 @@ def test_epoch_cfg1_both_hidden_readings():
     w = synth.WORKLOADS["cfg1"]
     run_epoch_parity(w, w.slice_hidden)       # hidden 64 in total: 32 per slice
     run_epoch_parity(w, 64)                   # hidden 64 per slice
+    run_epoch_parity(w, w.slice_hidden, scaled=False)   # activations kept unscaled between the layers
 
 
 def test_epoch_cfg2():
@@ -587,7 +685,7 @@ def run_epoch_feature_fusion(w):
     fp = model.fusion_params(w, c, bias_std=0.05)
     ff = FeatureFusion(n, w.feat, c)
     ff.set_params(*fp)
-    st = SliceStack(g, n, k, c, hs, L, shared_input=ff.forward(Xd))
+    st = SliceStack(g, n, k, c, hs, L, shared_input=ff.forward(Xd), scaled=True)
     E = configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, std=0.1)
     st.E.copy_(E)
     params = [[model.slice_layer_params(w, i, l, wi, wo, bias_std=0.05) for l, (wi, wo) in enumerate(st.widths)] for i in range(k)]
@@ -681,7 +779,7 @@ def test_graph_replay_matches_eager():
     g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
     k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
     sl, c = sg.slicegcn_slice_strategy(w.feat, k)
-    st = SliceStack(g, n, k, c, hs, L)
+    st = SliceStack(g, n, k, c, hs, L, scaled=True)
     Xd = configs.features(w).cuda()
     for i, (a, b_) in enumerate(sl):
         sg.slicegcn_slice_feature(Xd, a, b_, st.X[i])
@@ -704,6 +802,7 @@ def test_graph_replay_matches_eager():
         out += [st.grads[i][l][key].clone() for i in range(k) for l in range(L) for key in ("dW_agg", "db", "dW_self", "db_self")]
         return out
 
+    st.prepare_inputs()            # the slices now hold their scaled form; the variants below rewrite them in that form
     X0 = [x.clone() for x in st.X]
     step(); ref1 = snapshot()
     for x in st.X:
@@ -734,7 +833,7 @@ def test_cached_first_aggregation_equals_recomputed():
     k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
     sl, c = sg.slicegcn_slice_strategy(w.feat, k)
     Xd = configs.features(w).cuda()
-    stacks = [SliceStack(g, n, k, c, hs, L, cache_first_aggregation=flag) for flag in (False, True)]
+    stacks = [SliceStack(g, n, k, c, hs, L, cache_first_aggregation=flag, scaled=True) for flag in (False, True)]
     for st in stacks:
         for i, (a, b_) in enumerate(sl):
             sg.slicegcn_slice_feature(Xd, a, b_, st.X[i])
@@ -747,6 +846,8 @@ def test_cached_first_aggregation_equals_recomputed():
         st.Z[0][0].zero_()
     assert torch.equal(plain.forward(), ref)
     assert not torch.equal(cached.forward(), ref)
+    for i, (a, b_) in enumerate(sl):   # raw features written again (the same ones): the stack is told so
+        sg.slicegcn_slice_feature(Xd, a, b_, cached.X[i])
     cached.inputs_changed()
     assert torch.equal(cached.forward(), ref) and torch.equal(cached.forward(), ref)
     with pytest.raises(B.SliceGCNError):  # unknown flag bit
