@@ -62,6 +62,11 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads the oracle's row loops use from now on (results do not depend on it)."""
+    lib().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
 # ---------------------------------------------------------------------------------------
 def slice_strategy(in_d: int, p: int, slice_size_scale: float = 1.0):
     """Algorithm 1 of the paper: list of (start, end) and the slice size."""

@@ -356,6 +356,7 @@ int oracle_layer_bwd(int64_t n, const int64_t *rowptr, const int32_t *colidx, co
             db_self[j] = acc;
         }
     if (dW_agg)
+#pragma omp parallel for schedule(static)
         for (int32_t t = 0; t < w_in; ++t)
             for (int32_t j = 0; j < w_out; ++j) {
                 double acc = 0.0;
@@ -363,6 +364,7 @@ int oracle_layer_bwd(int64_t n, const int64_t *rowptr, const int32_t *colidx, co
                 dW_agg[(int64_t)t * w_out + j] = acc;
             }
     if (dW_self)
+#pragma omp parallel for schedule(static)
         for (int32_t t = 0; t < w_in; ++t)
             for (int32_t j = 0; j < w_out; ++j) {
                 double acc = 0.0;
@@ -373,6 +375,7 @@ int oracle_layer_bwd(int64_t n, const int64_t *rowptr, const int32_t *colidx, co
         if (ldgi < w_in) { free(dP); return ORACLE_EINVAL; }
         double *dZ = (double *)malloc((size_t)n * w_in * sizeof(double));
         if (!dZ) { free(dP); return ORACLE_ENOMEM; }
+#pragma omp parallel for schedule(static)
         for (int64_t v = 0; v < n; ++v)
             for (int32_t t = 0; t < w_in; ++t) {
                 double acc = 0.0;
@@ -383,6 +386,7 @@ int oracle_layer_bwd(int64_t n, const int64_t *rowptr, const int32_t *colidx, co
         free(dZ);
         if (rc) { free(dP); return rc; }
         if (W_self)
+#pragma omp parallel for schedule(static)
             for (int64_t v = 0; v < n; ++v)
                 for (int32_t t = 0; t < w_in; ++t) {
                     double acc = 0.0;
@@ -565,5 +569,17 @@ int oracle_num_threads(void)
     return omp_get_max_threads();
 #else
     return 1;
+#endif
+}
+
+/* Threads the row loops may use from now on (timing the oracle on one core); no arithmetic depends on it:
+ * every output element is summed by one thread in a fixed order. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
 #endif
 }
