@@ -61,6 +61,65 @@ def cpu_baseline(w, edges_src, edges_dst, slice_host, slices, width: int, frac: 
                       f"build took {t_build:.2f} s (not in the rate)"}
 
 
+def cpu_epoch(w, g, slices, hs: int, L: int):
+    """One pass of the whole hot path by the fp64 oracle (all k slices x L layers forward, encoding and concat,
+    and everything backward), timed with all host threads and with one.  Same seeded inputs as the GPU step."""
+    import numpy as np
+    import oracle
+    from synth import configs, model
+    k, n = len(slices), w.n_nodes
+    X = configs.features(w).numpy().astype(np.float64)
+    E = configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, std=0.1).numpy()
+    dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * hs).numpy().astype(np.float64)
+    params = [[[t.numpy() for t in model.slice_layer_params(w, i, l, (slices[i][1] - slices[i][0]) if l == 0 else hs, hs)]
+               for l in range(L)] for i in range(k)]
+
+    def one_pass(ids):
+        outs, saved = [], []
+        for i in ids:
+            a, b = slices[i]
+            h, keep = X[:, a:b], []
+            for l in range(L):
+                Wa, bb, Ws, bs = params[i][l]
+                hin = h
+                h, Z, P = oracle.layer_fwd(g, hin, Wa, bb, Ws, bs, act=1)
+                keep.append((hin, Z, P > 0))
+            outs.append(h)
+            saved.append(keep)
+        if len(ids) == k:
+            oracle.encode_concat(outs, E)
+            dHs, _ = oracle.encode_concat_bwd(dH, [hs] * k, want_dE=True)
+        else:
+            dHs = [np.ascontiguousarray(dH[:, i * hs:(i + 1) * hs]) for i in ids]
+        for j, i in enumerate(ids):
+            d = dHs[j]
+            for l in reversed(range(L)):
+                hin, Z, mask = saved[j][l]
+                d = oracle.layer_bwd(g, hin, Z, mask, params[i][l][0], params[i][l][2], d, need_dHin=l > 0).get("dHin")
+
+    # the oracle's weight-gradient loops are slow (seconds per layer at 10^5 nodes): above 20 000 nodes the sample
+    # is ONE slice model's pass, run once, and the epoch is k of them (every slice has the same shapes)
+    small = n <= 20_000
+    ids = list(range(k)) if small else [0]
+    times = {}
+    all_threads = oracle.num_threads()
+    for threads in (all_threads, 1):
+        oracle.set_num_threads(threads)
+        reps, t0 = 0, time.perf_counter()
+        if small:
+            one_pass(ids)                   # untimed: page in, warm the caches
+            t0 = time.perf_counter()
+        while reps < (3 if small else 1) or (small and time.perf_counter() - t0 < 2.0 and reps < 50):
+            one_pass(ids)
+            reps += 1
+        times[threads] = (time.perf_counter() - t0) / reps * (k / len(ids))
+    oracle.set_num_threads(all_threads)
+    return {"epochs_per_s": 1.0 / times[all_threads], "cores": all_threads,
+            "epochs_per_s_one_thread": 1.0 / times[1],
+            "sample": f"fp64 oracle, whole pass (forward + backward, {k} slices x {L} layers, encoding and concat)"
+                      + ("" if small else f": one slice model's pass timed once, times {k}")}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -260,9 +319,12 @@ def main():
     tfile = os.path.join(ROOT, "profiles", f"spmm_{w.name}_rocprofv3.md")
     if os.path.exists(tfile) and args.vertex_order == "permuted" and args.reorder == "none":
         import re
-        m = re.search(r"^hbm_bytes_per_launch = (\d+)", open(tfile).read(), flags=re.M)
+        # the summary holds one figure per form of the aggregation; take the one the timed launches ran in
+        factored = args.prescaled if args.spmm_only else st.in_scaled
+        key = "hbm_bytes_per_launch" if factored else "hbm_bytes_per_launch_with_values"
+        m = re.search(rf"^{key} = (\d+)", open(tfile).read(), flags=re.M)
         traffic = int(m.group(1)) if m else None
-        traffic_source = (f"profiles/spmm_{w.name}_rocprofv3.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+        traffic_source = (f"profiles/spmm_{w.name}_rocprofv3.md, {key} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
                           "`bench.py --spmm-only`, scaled by a plain copy; a stored figure, not measured in this run)")
     out = {
         "metric": "slice_spmm_gflops", "value": 2.0 * view.nnz * width / avg_s / 1e9, "unit": "GFLOP/s",
@@ -289,7 +351,9 @@ def main():
         "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source, "kernel": "slice aggregation (spmm_wave_items + spmm_group_items + spmm_tiny_rows + spmm_fix kernels of one call)",
-                     "algorithmic_bytes_per_launch": nbytes},
+                     "algorithmic_bytes_per_launch": nbytes,
+                     # what the factored form needs: no 4-byte value per stored entry, one factor per row instead
+                     "algorithmic_bytes_without_values": nbytes - 4 * view.nnz + 4 * n},
         "kernels": kernels,
     }
     out["roofline"]["stream_copy_GBps"] = stream_copy()["GBps"]   # what a plain copy reaches on this machine, for scale
@@ -300,6 +364,11 @@ def main():
                                            lambda i: configs.features(w, device=dev, col_start=slices[i][0],
                                                                       col_count=slices[i][1] - slices[i][0]).cpu().numpy(),
                                            slices, width, args.cpu_sample_frac)
+        if n <= 200_000 and not args.spmm_only and ff is None and cls is None:
+            # small workloads: the oracle's whole pass fits the time budget (seconds)
+            import oracle
+            og = oracle.build_norm_csr(src.cpu().numpy(), dst.cpu().numpy(), n)
+            out["cpu_baseline"]["epoch"] = cpu_epoch(w, og, slices, hs, L)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
