@@ -73,6 +73,15 @@ def _run(name: str, n_samples: int):
     Y2 = torch.empty_like(Y)
     sg.slicegcn_spmm_slice(g, Xs[:, :width], Y2[:, :width])
     assert torch.equal(Y[:, :width], Y2[:, :width])
+    # the factored form (operand rows carry D~^-1/2, the stored values are not read): what the default step of
+    # bench.py runs at this size.  Same rows, same oracle values.
+    sg.slicegcn_scale_rows(g, Xs[:, :width], Y2[:, :width])
+    sg.slicegcn_spmm_slice(g, Y2[:, :width], Y[:, :width], prescaled=True)
+    got = Y[:, :width][torch.as_tensor(rows, device=dev)].cpu().numpy()
+    err = float(np.max(np.abs(got - want))) / scale
+    progress(f"[fullsize] {name}: factored form, max rel err {err:.2e}")
+    assert err <= TOL
+    assert np.all(np.abs(got - want) <= bound + 1e-30)
     # invariant at full size: every row, no sampling
     s = torch.as_tensor(np.sqrt(o.deg.astype(np.float64)), dtype=torch.float32, device=dev)
     S = torch.zeros((w.n_nodes, 32), dtype=torch.float32, device=dev)
@@ -90,7 +99,12 @@ def _layer_chain(name: str, slice_id: int, n_layers: int = 2):
     per-slice hidden), forward then backward (the second layer with its input gradient, the first without, as
     in a pass over raw features), every output element against the oracle.  The backward pass differentiates
     the oracle's activation patterns on both sides.  With ``n_layers`` = 1 only the first layer runs, with its
-    input gradient (as under feature fusion)."""
+    input gradient (as under feature fusion).
+
+    The layers run in the layout the stack (and so bench.py) uses at these sizes: activations that feed an
+    aggregation are kept as D~^-1/2 H (raw slice scaled once, every layer but the last stores scaled); the
+    oracle works on the unscaled tensors, and what the library reads or writes scaled is compared through the
+    oracle's own D~^-1/2."""
     from synth import model
     from gpu_util import assert_close, pack_mask, unpack_mask
     w, g, o = _graph(name)
@@ -101,22 +115,26 @@ def _layer_chain(name: str, slice_id: int, n_layers: int = 2):
     f32 = dict(dtype=torch.float32, device=dev)
     shapes = [(width, hs), (hs, hs)][:n_layers]
     Xs = configs.features(w, device=dev, col_start=a, col_count=b - a, ld=padded_ld(width))
+    sg.slicegcn_scale_rows(g, Xs[:, :width], Xs[:, :width])        # in place, once: the raw features are constant
+    IN, OUT = sg.binding.LAYER_IN_SCALED, sg.binding.LAYER_OUT_SCALED
+    layout = [IN | (OUT if l < n_layers - 1 else 0) for l in range(n_layers)]
+    dinv = o.dinv[:, None]
     params = [model.slice_layer_params(w, slice_id, l, wi, wo, bias_std=0.05) for l, (wi, wo) in enumerate(shapes)]
     H = [Xs[:, :width], torch.empty((n, padded_ld(hs)), **f32)[:, :hs], torch.empty((n, hs), **f32)][:n_layers + 1]
     Z = [torch.empty((n, padded_ld(wi)), **f32)[:, :wi] for wi, _ in shapes]
     mask = [torch.zeros((n, (wo + 31) // 32), dtype=torch.int32, device=dev) for _, wo in shapes]
     for l in range(n_layers):
         Wa, bb, Ws, bs = (t.cuda() for t in params[l])
-        sg.slicegcn_layer_fwd(g, H[l], Wa, bb, Ws, bs, H[l + 1], Z[l], mask[l])
+        sg.slicegcn_layer_fwd(g, H[l], Wa, bb, Ws, bs, H[l + 1], Z[l], mask[l], layout=layout[l])
     progress(f"[fullsize-layer] {name}: oracle forward")
-    h64 = Xs[:, :width].cpu().numpy().astype(np.float64)
+    h64 = Xs[:, :width].cpu().numpy().astype(np.float64) / dinv      # the unscaled input the scaled fp32 rows stand for
     saved = []
     for l in range(n_layers):
         Wa, bb, Ws, bs = (t.numpy() for t in params[l])
         hin = h64
         h64, Zo, Po = oracle.layer_fwd(o, hin, Wa, bb, Ws, bs, act=1)
         e1 = assert_close(Z[l].cpu().numpy(), Zo, f"Z of layer {l + 1}")
-        e2 = assert_close(H[l + 1].cpu().numpy(), h64, f"output of layer {l + 1}")
+        e2 = assert_close(H[l + 1].cpu().numpy(), dinv * h64 if layout[l] & OUT else h64, f"output of layer {l + 1}")
         ref_mask = Po > 0
         differ = unpack_mask(mask[l].cpu().numpy(), shapes[l][1]) != ref_mask
         assert np.all(np.abs(Po[differ]) <= 1e-5 * np.sqrt(np.mean(Po * Po)))
@@ -136,7 +154,7 @@ def _layer_chain(name: str, slice_id: int, n_layers: int = 2):
         dW_agg = torch.empty((wi, wo), **f32); db = torch.empty(wo, **f32)
         dW_self = torch.empty((wi, wo), **f32); db_self = torch.empty(wo, **f32)
         ws = torch.empty(sg.slicegcn_layer_bwd_workspace_bytes(g, wi, wo, need), dtype=torch.uint8, device=dev)
-        sg.slicegcn_layer_bwd(g, H[l], Wa, Ws, Z[l], mask[l], g_out, dHin, dW_agg, db, dW_self, db_self, ws)
+        sg.slicegcn_layer_bwd(g, H[l], Wa, Ws, Z[l], mask[l], g_out, dHin, dW_agg, db, dW_self, db_self, ws, layout=layout[l])
         progress(f"[fullsize-layer] {name}: oracle backward of layer {l + 1}")
         hin, Zo, ref_mask = saved[l]
         ref = oracle.layer_bwd(o, hin, Zo, ref_mask, params[l][0].numpy(), params[l][2].numpy(), ref_out, need_dHin=need)
