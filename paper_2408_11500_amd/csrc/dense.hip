@@ -67,12 +67,14 @@ __device__ inline float pick(const float4 &v, int i) { return i == 0 ? v.x : i =
 template <int NT, bool BWD, bool TWO>
 __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_col_tiles)
 {
-    constexpr int BM = 128, KC = 32, AS = KC + 4, BN = NT * 32, BS = BN + 1;
+    constexpr int BM = 128, KC = 32, AS = KC + 4, BN = NT * 32;
     constexpr int BPT = KC * BN / 256; // B-tile elements per thread and chunk
     __shared__ __attribute__((aligned(16))) float As1[BM][AS];
     __shared__ __attribute__((aligned(16))) float As2[TWO ? BM : 1][AS];
-    __shared__ float Bs1[KC][BS];
-    __shared__ float Bs2[TWO ? KC : 1][BS];
+    // the B tiles are kept column-major ([column][k], the A tiles' row stride), so that a lane reads the four
+    // consecutive k of its column with one 16-byte LDS read, as it does for A: one LDS read per four MFMAs
+    __shared__ __attribute__((aligned(16))) float Bt1[BN][AS];
+    __shared__ __attribute__((aligned(16))) float Bt2[TWO ? BN : 1][AS];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -157,8 +159,8 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
         for (int it = 0; it < BPT; ++it) {
             const int idx = tid + it * 256;
             const int kk = BWD ? idx % KC : idx / BN, j = BWD ? idx / KC : idx % BN;
-            Bs1[kk][j] = rb1[it];
-            if (TWO) Bs2[kk][j] = rb2[it];
+            Bt1[j][kk] = rb1[it];
+            if (TWO) Bt2[j][kk] = rb2[it];
         }
     };
 
@@ -173,12 +175,14 @@ __global__ __launch_bounds__(256) void pair_mfma_kernel(const PairArgs a, int n_
             float4 a2 = a1;
             if (TWO) a2 = *reinterpret_cast<const float4 *>(&As2[wave * 32 + m][8 * j8 + 4 * h]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int kk = 8 * j8 + 4 * h + i;
+            for (int t = 0; t < NT; ++t) {
+                const float4 b1 = *reinterpret_cast<const float4 *>(&Bt1[t * 32 + m][8 * j8 + 4 * h]);
+                float4 b2 = b1;
+                if (TWO) b2 = *reinterpret_cast<const float4 *>(&Bt2[t * 32 + m][8 * j8 + 4 * h]);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1, i), Bs1[kk][t * 32 + m], acc1[t], 0, 0, 0);
-                    if (TWO) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2, i), Bs2[kk][t * 32 + m], acc2[t], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) {
+                    acc1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a1, i), pick(b1, i), acc1[t], 0, 0, 0);
+                    if (TWO) acc2[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(a2, i), pick(b2, i), acc2[t], 0, 0, 0);
                 }
             }
         }
@@ -786,7 +790,11 @@ int launch_pair(const PairArgs &a, hipStream_t stream)
     }
     // staged kernel: 1-D grid, 8 row tiles x all column tiles per group of workgroups (see the kernel)
     const bool two = a.A2 != nullptr && a.B2 != nullptr;
-    const int nt2 = (!two && a.Nout > 128) ? 8 : nt; // a single product leaves registers for 256 columns
+    // Column tiles per workgroup: 4 for a single product and 2 for a pair, which keeps two workgroups on a CU (64 and
+    // 2 x 32 accumulator registers): the other workgroup's MFMAs fill the barrier waits.  Wider tiles (256 columns,
+    // or 128 for a pair) run one workgroup per CU and are 20 % and 16 % slower on 256 -> 256 and 301 -> 128.
+    const int cap = two ? 2 : 4;
+    const int nt2 = nt > cap ? cap : nt;
     const int bn = nt2 * 32;
     const int n_col = (a.Nout + bn - 1) / bn;
     const int64_t row_tiles = (a.n + 127) / 128;
@@ -794,19 +802,14 @@ int launch_pair(const PairArgs &a, hipStream_t stream)
     SG_REQUIRE(blocks <= INT32_MAX, SLICEGCN_ERANGE, "dense product: grid too large");
     const unsigned gb = (unsigned)blocks;
     if (two) {
-        switch (nt2) {
-        case 1: pair_mfma_kernel<1, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
-        case 2: pair_mfma_kernel<2, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
-        case 3: pair_mfma_kernel<3, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
-        default: pair_mfma_kernel<4, BWD, true><<<gb, 256, 0, stream>>>(a, n_col); break;
-        }
+        if (nt2 == 1) pair_mfma_kernel<1, BWD, true><<<gb, 256, 0, stream>>>(a, n_col);
+        else pair_mfma_kernel<2, BWD, true><<<gb, 256, 0, stream>>>(a, n_col);
     } else {
         switch (nt2) {
         case 1: pair_mfma_kernel<1, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
         case 2: pair_mfma_kernel<2, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
         case 3: pair_mfma_kernel<3, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
-        case 4: pair_mfma_kernel<4, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
-        default: pair_mfma_kernel<8, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
+        default: pair_mfma_kernel<4, BWD, false><<<gb, 256, 0, stream>>>(a, n_col); break;
         }
     }
     SG_LAUNCH_CHECK();
