@@ -281,6 +281,13 @@ def main():
     prof = [e[:4] for e in prof_full]
     ms_per_step = elapsed * 1e3 / args.steps
     log(f"{args.steps} steps, {ms_per_step:.2f} ms/step")
+    # the same steps once more without the per-kernel events, to show what recording them costs
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_no_events = (time.perf_counter() - t0) * 1e3 / args.steps
 
     graph_ms = None
     if args.graph:
@@ -345,7 +352,7 @@ def main():
                    "n_nodes": n, "nnz": view.nnz, "k": k, "slice_width": width, "slice_hidden": hs, "layers": L},
         "epoch_ms": None if args.spmm_only else ms_per_step,
         "epochs_per_s": None if args.spmm_only else 1e3 / ms_per_step,
-        "graph_ms_per_step": graph_ms,
+        "ms_per_step_without_events": ms_no_events, "graph_ms_per_step": graph_ms,
         "spmm_avg_ms": avg_s * 1e3, "spmm_median_ms": kernels.get(f"spmm_w{width}", {}).get("median_ms"),
         "spmm_min_ms": kernels.get(f"spmm_w{width}", {}).get("min_ms"),
         "spmm_launches_timed": dom[0], "build_norm_csr_ms": build_ms,
