@@ -155,6 +155,10 @@ def main():
                     help="keep the activations between the layers unscaled (every forward aggregation then reads the "
                          "stored values); by default graphs of 16 M stored entries or more keep them as D~^-1/2 H "
                          "(SLICEGCN_LAYER_IN/OUT_SCALED)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="slice models in flight at a time, each on its own HIP stream (default 1: one after the other); "
+                         "pays on the small workloads, whose kernels leave most of the chip idle.  The per-kernel "
+                         "times then overlap and say little; ms_per_step is what to read")
     ap.add_argument("--reorder", choices=("none", "degree", "bfs"), default="none",
                     help="row order of the aggregation schedule (SLICEGCN_REORDER_*): by degree, or breadth first "
                          "(pays off on graphs with communities such as --workload comm, not on R-MAT)")
@@ -224,7 +228,7 @@ def main():
         ff.set_params(*model.fusion_params(w, width, device=dev))
         ff.forward(X)
     st = SliceStack(g, n, k, width, hs, L, device=dev, shared_input=ff.Xff if ff is not None else None,
-                    cache_first_aggregation=args.cache_first_agg, scaled=False if args.unscaled else None,
+                    cache_first_aggregation=args.cache_first_agg, scaled=False if args.unscaled else None, streams=args.streams,
                     order={"aggregate": 0, "transform": sg.binding.LAYER_TRANSFORM_FIRST, "auto": sg.binding.LAYER_ORDER_AUTO}[args.order])
     for i, (a, b) in enumerate(slices):
         if ff is None:
@@ -343,6 +347,7 @@ def main():
                                + (f" [rows visited in {args.reorder} order]" if args.reorder != "none" else "")
                                + (f" [layer order: {args.order}]" if args.order != "aggregate" else "")
                                + (" [activations kept as D~^-1/2 H between layers]" if st.scaled else "")
+                               + (f" [{st.lanes} slice models in flight on streams of their own]" if st.lanes > 1 else "")
                                + (" [aggregation only]" if args.spmm_only else "")
                                + (" [operands pre-scaled by D~^-1/2]" if args.spmm_only and args.prescaled else "")
 

@@ -21,7 +21,7 @@ class SliceStack:
     def __init__(self, graph: B.Graph, n_nodes: int, k: int, first_width: int, slice_hidden: int, layers: int,
                  device="cuda", slice_encoding: bool = True, act_last: int = B.ACT_RELU,
                  shared_input: torch.Tensor | None = None, cache_first_aggregation: bool = False,
-                 fuse_encoding: bool = True, order: int = 0, scaled: bool | None = None):
+                 fuse_encoding: bool = True, order: int = 0, scaled: bool | None = None, streams: int = 1):
         """``shared_input``: with feature fusion every slice model reads the same fused n x first_width
         matrix; the stack then also returns the gradient with respect to it (``dXin``).
         ``order``: 0 (aggregate first), LAYER_TRANSFORM_FIRST or LAYER_ORDER_AUTO, applied to every layer.
@@ -30,7 +30,12 @@ class SliceStack:
         ``prepare_inputs`` (call it after filling ``X``).  None = by graph size: the layout pays where the
         aggregation streams the stored entries from memory (measured: -3 % per step at 126 M and 310 M entries) and
         costs a little where the whole graph sits in cache and the dense kernels' extra row factors show
-        (+3 % at 2.5 M entries), so it is used from 16 M stored entries on."""
+        (+3 % at 2.5 M entries), so it is used from 16 M stored entries on.
+        ``streams``: how many slice models run at a time, each on a HIP stream of its own (the slice models are
+        independent between the raw features and the concatenation, and a graph handle is read-only, so they only
+        need workspaces of their own).  1 = one after the other on the caller's stream.  More pays on small graphs,
+        whose kernels leave most of the chip idle; every slice computes exactly what it computes alone, so results
+        are bitwise the same."""
         self.g, self.n, self.k, self.L = graph, n_nodes, k, layers
         self.w0, self.hs = first_width, slice_hidden
         self.dev = torch.device(device)
@@ -77,14 +82,22 @@ class SliceStack:
         # block (no encoding pass) and dE[i] is that layer's db_self (no column-sum pass over dH).
         self.fuse_encoding = fuse_encoding and slice_encoding
         self.b_eff = torch.zeros((k, slice_hidden), **f32) if self.fuse_encoding else None
-        # backward scratch
-        self.dbuf = [torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
+        # slice i runs on lane i mod lanes; a lane has its own stream, workspace and backward scratch
+        self.lanes = max(1, min(k, int(streams)))
+        self.streams = [torch.cuda.Stream(device=self.dev) for _ in range(self.lanes)] if self.lanes > 1 else []
+        self.dbuf = [[torch.empty((n_nodes, padded_ld(slice_hidden)), **f32) for _ in range(2)] if layers > 1 else []
+                     for _ in range(self.lanes)]
+        # with a shared (learned) input and several lanes every slice keeps its own input gradient until the lanes
+        # have joined; they are then added in slice order, as the one-lane pass adds them
+        self.dXs = ([torch.empty((n_nodes, padded_ld(first_width)), **f32) for _ in range(k - 1)]
+                    if self.shared and self.lanes > 1 else [])
         ws = 0
         for l, (wi, wo) in enumerate(self.widths):
             ws = max(ws, B.slicegcn_layer_fwd_workspace_bytes(graph, wi, wo, order),
                      B.slicegcn_layer_bwd_workspace_bytes(graph, wi, wo, l > 0 or self.shared, order))
         ws = max(ws, B.slicegcn_concat_bwd_workspace_bytes(n_nodes, [slice_hidden] * k))
-        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+        self.ws_lane = [torch.empty(ws, dtype=torch.uint8, device=self.dev) for _ in range(self.lanes)]
+        self.ws = self.ws_lane[0]
 
     # ---------------------------------------------------------------------------------
     def set_params(self, i: int, l: int, W_agg, b, W_self, b_self):
@@ -156,13 +169,30 @@ class SliceStack:
                 B.slicegcn_accumulate(b_self.view(1, -1), self.E[i].view(1, -1))
             B.slicegcn_layer_fwd(self.g, self.hin(i, l), p["W_agg"], p["b"], p["W_self"], b_self, self.hout(i, l),
                                  self.zbuf(i, l), self.mask[i][l], act=self.act(l),
-                                 z_valid=l == 0 and self.cache_first and self.first_valid[i], ws=self.ws, order=self.order,
-                                 layout=self.layout[l])
+                                 z_valid=l == 0 and self.cache_first and self.first_valid[i], ws=self.ws_lane[i % self.lanes],
+                                 order=self.order, layout=self.layout[l])
         self.first_valid[i] = True
 
-    def forward(self) -> torch.Tensor:
+    def _on_lanes(self, fn):
+        """fn(i) for every slice: in turn on the caller's stream, or slice i on lane i mod lanes, the lanes
+        starting after what the caller's stream holds so far and the caller's stream going on after all of them."""
+        if self.lanes == 1:
+            for i in range(self.k):
+                fn(i)
+            return
+        main = torch.cuda.current_stream()
+        for s in self.streams:
+            s.wait_stream(main)
         for i in range(self.k):
-            self.forward_slice(i)
+            with torch.cuda.stream(self.streams[i % self.lanes]):
+                fn(i)
+        for s in self.streams:
+            main.wait_stream(s)
+
+    def forward(self) -> torch.Tensor:
+        if not self.inputs_prepared:
+            self.prepare_inputs()
+        self._on_lanes(self.forward_slice)
         # the last layer of every slice already stored into its column block: encode in place, unless that is done
         if not self.encoding_fused():
             B.slicegcn_concat([self.hout(i, self.L - 1) for i in range(self.k)], self.E, self.Hcat)
@@ -172,25 +202,33 @@ class SliceStack:
         fused = self.encoding_fused()
         if self.E is not None and not fused:
             B.slicegcn_concat_bwd(dH, [self.hs] * self.k, dE=self.dE, ws=self.ws)
-        for i in range(self.k):
+        deferred = self.shared and self.lanes > 1   # the slices' input gradients are added after the lanes have joined
+
+        def backward_slice(i: int):
+            lane = i % self.lanes
             g_out = dH[:, i * self.hs:(i + 1) * self.hs]  # CONCAT backward is a column view
             for l in reversed(range(self.L)):
                 p, gr = self.params[i][l], self.grads[i][l]
                 wi = self.widths[l][0]
                 if l > 0:
-                    g_in = self.dbuf[l % 2][:, :wi]
+                    g_in = self.dbuf[lane][l % 2][:, :wi]
                 elif self.shared:  # the fused features are learned: the first slice writes, the others add
-                    g_in = (self.dXin if i == 0 else self.dXtmp)[:, :wi]
+                    g_in = (self.dXin if i == 0 else self.dXs[i - 1] if deferred else self.dXtmp)[:, :wi]
                 else:
                     g_in = None  # raw features need no gradient
                 B.slicegcn_layer_bwd(self.g, self.hin(i, l), p["W_agg"], p["W_self"], self.zbuf(i, l), self.mask[i][l],
-                                     g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws,
+                                     g_out, g_in, gr["dW_agg"], gr["db"], gr["dW_self"], gr["db_self"], self.ws_lane[lane],
                                      act=self.act(l), order=self.order, layout=self.layout[l])
-                if l == 0 and self.shared and i > 0:
+                if l == 0 and self.shared and i > 0 and not deferred:
                     B.slicegcn_accumulate(self.dXin[:, :wi], g_in)
                 if fused and l == self.L - 1:  # dE[i] = column sums of dH^i = this layer's db_self
                     B.slicegcn_slice_feature(gr["db_self"].view(1, -1), 0, self.hs, self.dE[i].view(1, -1))
                 g_out = g_in
+
+        self._on_lanes(backward_slice)
+        if deferred:
+            for i in range(1, self.k):
+                B.slicegcn_accumulate(self.dXin[:, :self.w0], self.dXs[i - 1][:, :self.w0])
 
 
 class Classifier:

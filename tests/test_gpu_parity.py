@@ -554,7 +554,7 @@ def test_concat_fwd_bwd():
 
 
 # ---------------------------------------------------------------------------------------
-def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0, order=0, scaled=True):
+def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0, order=0, scaled=True, streams=1):
     """All k slices x L layers + encoding/concat, forward and backward, against the oracle.  With
     ``classifier`` the upstream gradient comes from the classifier MLP and the cross-entropy loss
     (also checked against the oracle) instead of a seeded random matrix."""
@@ -564,7 +564,7 @@ def run_epoch_parity(w, slice_hidden, bias_std=0.05, classifier=False, scale=1.0
     sl, _ = sg.slicegcn_slice_strategy(w.feat, k, scale)
     assert sl == oracle.slice_strategy(w.feat, k, scale)[0]
     c = sl[0][1] - sl[0][0]  # every slice of a strategy has the same width
-    st = SliceStack(g, n, k, c, slice_hidden, L, order=order, scaled=scaled)
+    st = SliceStack(g, n, k, c, slice_hidden, L, order=order, scaled=scaled, streams=streams)
     X = configs.features(w)
     Xd = X.cuda()
     E = configs.normal_matrix(w.seed, configs.STREAM_E, k, slice_hidden, std=0.1)
@@ -672,7 +672,7 @@ def test_epoch_overlapping_and_scaled_slices():
     run_epoch_parity(dataclasses.replace(base, feat=50, k=2, hidden=64), 32, scale=0.5)  # 12 wide, gaps
 
 
-def run_epoch_feature_fusion(w):
+def run_epoch_feature_fusion(w, streams=1):
     """The feature-fusion variant: one shared two-layer MLP d' -> d' -> slice_size feeds every slice
     model; its gradient is the sum of the slice models' input gradients.  Forward and backward
     against the oracle (dense layers + slice layers composed)."""
@@ -685,7 +685,7 @@ def run_epoch_feature_fusion(w):
     fp = model.fusion_params(w, c, bias_std=0.05)
     ff = FeatureFusion(n, w.feat, c)
     ff.set_params(*fp)
-    st = SliceStack(g, n, k, c, hs, L, shared_input=ff.forward(Xd), scaled=True)
+    st = SliceStack(g, n, k, c, hs, L, shared_input=ff.forward(Xd), scaled=True, streams=streams)
     E = configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, std=0.1)
     st.E.copy_(E)
     params = [[model.slice_layer_params(w, i, l, wi, wo, bias_std=0.05) for l, (wi, wo) in enumerate(st.widths)] for i in range(k)]
@@ -745,6 +745,53 @@ def test_epoch_feature_fusion_cfg2_size():
     slice), the gradient accumulation over slices and the fusion MLP's backward at a size where the strip
     kernels and 1024-row gradient blocks are the ones that run."""
     run_epoch_feature_fusion(synth.WORKLOADS["cfg2"])
+
+
+def test_epoch_slices_on_streams():
+    """Slice models in flight on HIP streams of their own (one graph handle, one workspace per stream): the whole
+    pass of the 169 K-node workload with its 4 slices on 4 streams, and the feature-fusion pass (input gradients of
+    the slices added after the streams have joined) with 2 slices on 2 streams, both against the oracle."""
+    run_epoch_parity(synth.WORKLOADS["cfg2"], synth.WORKLOADS["cfg2"].slice_hidden, streams=4)
+    run_epoch_feature_fusion(synth.WORKLOADS["cfg1"], streams=2)
+
+
+def test_slices_on_streams_bitwise():
+    """Every slice computes on its own stream exactly what it computes in turn: outputs and gradients of a pass with
+    3 lanes for 5 slices equal those of the one-lane pass bit for bit, with raw and with shared (learned) inputs."""
+    import dataclasses
+    w = dataclasses.replace(synth.WORKLOADS["cfg1"], feat=160, k=5, hidden=160)
+    s_, d_ = configs.edges(w)
+    g = sg.slicegcn_build_norm_csr(s_.cuda(), d_.cuda(), w.n_nodes)
+    k, L, n, hs = w.k, w.layers, w.n_nodes, w.slice_hidden
+    sl, c = sg.slicegcn_slice_strategy(w.feat, k)
+    Xd = configs.features(w).cuda()
+    dH = configs.normal_matrix(w.seed, configs.STREAM_DH, n, k * hs).cuda()
+    for shared in (False, True):
+        runs = []
+        for lanes in (1, 3):
+            Xsh = torch.zeros((n, 64), dtype=torch.float32, device="cuda")
+            Xsh[:, :c] = Xd[:, :c]
+            st = SliceStack(g, n, k, c, hs, L, shared_input=Xsh if shared else None, streams=lanes)
+            assert st.lanes == lanes
+            st.E.copy_(configs.normal_matrix(w.seed, configs.STREAM_E, k, hs, std=0.1))
+            for i, (a, b_) in enumerate(sl):
+                if not shared:
+                    sg.slicegcn_slice_feature(Xd, a, b_, st.X[i])
+                for l, (wi, wo) in enumerate(st.widths):
+                    st.set_params(i, l, *model.slice_layer_params(w, i, l, wi, wo, bias_std=0.05))
+            for _ in range(2):      # twice: the second pass reuses every buffer while the lanes overlap
+                st.forward()
+                st.backward(dH)
+            torch.cuda.synchronize()
+            out = [st.Hcat.clone(), st.dE.clone()] + ([st.dXin.clone()] if shared else [])
+            for i in range(k):
+                for l in range(L):
+                    out += [st.grads[i][l][key].clone() for key in ("dW_agg", "db", "dW_self", "db_self")]
+            runs.append(out)
+        assert len(runs[0]) == len(runs[1])
+        for a, b_ in zip(*runs):
+            assert torch.equal(a, b_)
+    g.destroy()
 
 
 def test_epoch_ragged_slices_cfg2_size():
