@@ -53,6 +53,7 @@ struct SpmmArgs {
     int32_t n;
     int32_t n_classes;
     int32_t item_max;     // longest lane-group item of the schedule (ITEM_SHORT or ITEM_LONG)
+    int32_t ipw;          // wavefront items per wavefront (one-launch kernel: 4; otherwise 1); a workgroup takes 4 * ipw
     int32_t big_blocks;   // workgroups per class in the wavefront-item section
     int32_t small_blocks; // workgroups per class in the lane-group-item section
     int32_t slot_cols;    // floats per partial-sum slot
@@ -162,7 +163,9 @@ __device__ inline void gather_chunk(Acc<V> &acc, const SpmmArgs &a, int c_l, flo
     constexpr int U = 8;        // gathers in flight per lane
     using L = Ld<V>;
     if (cnt >= 64) {
-#pragma unroll
+        // not unrolled: with 16 or more lanes per row the unrolled loop holds the shuffled pairs of the whole chunk and
+        // halves the wavefronts per SIMD (60 registers against 81-97), which costs 1.5 % at 301 columns
+#pragma unroll 1
         for (int t = 0; t < LPR; t += U) {
             int c[U];
             float v[U];
@@ -328,6 +331,72 @@ __device__ __forceinline__ void wave_items_body(const SpmmArgs &a, int block)
     if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
 }
 
+// The same for graphs that stay in cache (the one-launch kernel below): a workgroup takes 4 * ipw consecutive items,
+// wavefront w the items w, w + 4, ... of them; the next item's descriptor is requested when an item starts and its first
+// entries during the item's last chunk.  There a call lasts tens of microseconds and is made of chains of dependent loads
+// (descriptor -> entries -> gathers), which this overlaps across items: 0.049 -> 0.043 ms per call at 2.5 M entries.  On
+// graphs that stream from memory it changes nothing and its eight extra registers cost 2 %, so they keep one item per wavefront.
+template <int LPR, int V, bool S32, bool FACT>
+__device__ __forceinline__ void wave_items_run_body(const SpmmArgs &a, int block)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cls = block % a.n_classes, j = block / a.n_classes;
+    const int ipb = 4 * a.ipw; // items per workgroup
+    const int piece_blocks = (a.big_cnt[cls] + ipb - 1) / ipb;
+    int64_t first, left;
+    if (j < piece_blocks) { // uniform per workgroup
+        first = (int64_t)j * ipb;
+        left = a.big_cnt[cls] - first;
+        first += a.big_off[cls];
+    } else {
+        first = ((int64_t)(j - piece_blocks) * a.n_classes + cls) * ipb;
+        left = a.wbig_cnt - first;
+        first += a.wbig_off;
+    }
+    const int cnt = left < ipb ? (int)left : ipb;
+    int t = wave; // this wavefront takes items wave, wave + 4, ... of the workgroup's run
+    if (t >= cnt) return;
+    const int grp = lane / LPR, sub = lane % LPR;
+    const int col = a.col0 + sub * V;
+    const bool active = col < a.col_end;
+    const int colc = active ? col : a.col0;
+    int4 s = *reinterpret_cast<const int4 *>(a.items + first + t);
+    int idx = s.y + lane;
+    int c_l = a.colidx[idx < s.z ? idx : s.y];
+    float v_l = ld_val<FACT>(a, idx < s.z ? idx : s.y);
+    for (;;) {
+        const bool more = t + 4 < cnt; // wavefront-uniform
+        // the next item's descriptor is requested now and its first entries during this item's last chunk, so
+        // that a short item does not expose the whole chain descriptor -> entries -> gathers
+        int4 sn = s;
+        if (more) sn = *reinterpret_cast<const int4 *>(a.items + first + t + 4);
+        const int beg = s.y, end = s.z;
+        Acc<V> acc;
+        for (int base = beg; base < end; base += 64) {
+            int c_n = 0;
+            float v_n = 0.f;
+            if (base + 64 < end) { // wavefront-uniform
+                idx = base + 64 + lane;
+                c_n = a.colidx[idx < end ? idx : beg];
+                v_n = ld_val<FACT>(a, idx < end ? idx : beg);
+            } else if (more) {
+                idx = sn.y + lane;
+                c_n = a.colidx[idx < sn.z ? idx : sn.y];
+                v_n = ld_val<FACT>(a, idx < sn.z ? idx : sn.y);
+            }
+            gather_chunk<LPR, V, S32, FACT>(acc, a, c_l, v_l, end - base, grp, colc);
+            c_l = c_n;
+            v_l = v_n;
+        }
+#pragma unroll
+        for (int m = LPR; m < 64; m <<= 1) acc.add(shfl_xor_acc<V>(acc, m));
+        if (grp == 0 && active) store_result<V>(acc, a, s.x, s.w, col);
+        if (!more) break;
+        s = sn;
+        t += 4;
+    }
+}
+
 // Lane-group items (whole rows and class pieces of 5..GI_MAX entries, GI_MAX = the schedule's item_max):
 // workgroup b serves class b mod n_classes.  Lane i of a wavefront
 // reads the descriptor of item i; round r hands item r * G + grp to lane group grp.  The group
@@ -454,7 +523,7 @@ template <int LPR, int V, bool S32, bool FACT>
 __global__ __launch_bounds__(256) void spmm_merged_kernel(const SpmmArgs a, int g1, int g2)
 {
     const int b = blockIdx.x; // uniform per workgroup
-    if (b < g1) wave_items_body<LPR, V, S32, FACT>(a, b);
+    if (b < g1) wave_items_run_body<LPR, V, S32, FACT>(a, b);
     else if (b < g1 + g2) group_items_body<LPR, V, S32, ITEM_SHORT, FACT>(a, b - g1);
     else tiny_rows_body<LPR, V, S32, FACT>(a, b - g1 - g2);
 }
@@ -494,7 +563,8 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
     const int64_t g2 = (int64_t)a.n_classes * a.small_blocks;
     const int64_t g3 = (a.n + units_per_block - 1) / units_per_block;
     SG_REQUIRE(g1 <= INT32_MAX && g2 <= INT32_MAX && g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
-    if (a.item_max <= ITEM_SHORT && g1 + g2 + g3 <= INT32_MAX) { // cache-resident graph: one launch
+    if (a.item_max <= ITEM_SHORT) { // cache-resident graph: one launch (big_blocks counts runs of 4 * ipw items)
+        SG_REQUIRE(g1 + g2 + g3 <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
         spmm_merged_kernel<LPR, V, S32, FACT><<<(unsigned)(g1 + g2 + g3), 256, 0, stream>>>(a, (int)g1, (int)g2);
         SG_LAUNCH_CHECK();
         return SLICEGCN_OK;
@@ -504,8 +574,7 @@ int launch_variant(const SpmmArgs &a, hipStream_t stream)
         SG_LAUNCH_CHECK();
     }
     if (g2 > 0) {
-        if (a.item_max <= ITEM_SHORT) spmm_group_items_kernel<LPR, V, S32, ITEM_SHORT, FACT><<<(unsigned)g2, 256, 0, stream>>>(a);
-        else spmm_group_items_kernel<LPR, V, S32, ITEM_LONG, FACT><<<(unsigned)g2, 256, 0, stream>>>(a);
+        spmm_group_items_kernel<LPR, V, S32, ITEM_LONG, FACT><<<(unsigned)g2, 256, 0, stream>>>(a);
         SG_LAUNCH_CHECK();
     }
     spmm_tiny_rows_kernel<LPR, V, S32, FACT><<<(unsigned)g3, 256, 0, stream>>>(a);
@@ -583,13 +652,15 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
     a.wbig_off = sc.wbig_off; a.wbig_cnt = sc.wbig_cnt;
     a.wsmall_off = sc.wsmall_off; a.wsmall_cnt = sc.wsmall_cnt;
     // workgroups per class: the class's own pieces, then its share of the whole-row chunks
-    const int64_t wbig_chunks = ((int64_t)sc.wbig_cnt + 3) / 4;
+    a.ipw = sc.item_max <= ITEM_SHORT ? 4 : 1; // the one-launch kernel works through runs of items
+    const int64_t ipb = 4 * a.ipw;
+    const int64_t wbig_chunks = ((int64_t)sc.wbig_cnt + ipb - 1) / ipb;
     int64_t big_blocks = 0;
     for (int c = 0; c < MAX_CLASSES; ++c) {
         a.big_off[c] = sc.big_off[c]; a.big_cnt[c] = sc.big_cnt[c];
         a.small_off[c] = sc.small_off[c]; a.small_cnt[c] = sc.small_cnt[c];
         if (c >= sc.n_classes) continue;
-        const int64_t b = (sc.big_cnt[c] + 3) / 4 + (wbig_chunks + sc.n_classes - 1 - c) / sc.n_classes;
+        const int64_t b = (sc.big_cnt[c] + ipb - 1) / ipb + (wbig_chunks + sc.n_classes - 1 - c) / sc.n_classes;
         big_blocks = b > big_blocks ? b : big_blocks;
     }
     SG_REQUIRE(big_blocks * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
