@@ -35,6 +35,16 @@ def spmm_bytes(n: int, nnz: int, w: int, with_add: bool = False) -> int:
     return 8 * nnz + 4 * (n + 1) + 8 * n * w + (4 * n * w if with_add else 0)
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, edges_src, edges_dst, slice_host, slices, width: int, frac: int):
     """The fp64 oracle's aggregation timed on the host: layer-1 aggregation of all k slices over the
     sub-workload made of every edge incident to the first n/frac nodes (frac = 1: the whole graph)."""
@@ -55,7 +65,7 @@ def cpu_baseline(w, edges_src, edges_dst, slice_host, slices, width: int, frac: 
         t += time.perf_counter() - t0
     what = "the whole graph" if frac == 1 else f"the sub-graph of all edges incident to nodes [0, {n_s})"
     return {"value": 2.0 * g.nnz * width * len(slices) / t / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
+            "kind": "oracle", "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
             "sample": f"fp64 oracle aggregation of all {len(slices)} slices (width {width}) over {what} "
                       f"(nnz {g.nnz} incl. self loops, {w.n_nodes} rows): {t:.2f} s in total; the oracle's own CSR "
                       f"build took {t_build:.2f} s (not in the rate)"}
@@ -379,6 +389,11 @@ def main():
                      "algorithmic_bytes_without_values": nbytes - 4 * view.nnz + 4 * n},
         "kernels": kernels,
     }
+    if traffic is not None:
+        # the second bandwidth figure: bytes the memory side moved (stored counter summary) over the measured time,
+        # and their ratio to the algorithmic bytes (1 = no gathered row fetched twice)
+        out["roofline"]["traffic_GBps"] = traffic / avg_s / 1e9
+        out["roofline"]["traffic_over_algorithmic"] = traffic / nbytes
     probe = stream_copy()   # what a plain copy and a read-only pass reach on this machine, for scale
     out["roofline"]["stream_copy_GBps"] = probe["GBps"]
     out["roofline"]["stream_read_GBps"] = probe["read_only_GBps"]
