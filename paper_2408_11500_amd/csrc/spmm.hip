@@ -398,8 +398,10 @@ __device__ __forceinline__ void wave_items_run_body(const SpmmArgs &a, int block
 }
 
 // Lane-group items (whole rows and class pieces of 5..GI_MAX entries, GI_MAX = the schedule's item_max):
-// workgroup b serves class b mod n_classes.  Lane i of a wavefront
-// reads the descriptor of item i; round r hands item r * G + grp to lane group grp.  The group
+// workgroup b serves class b mod n_classes and takes a run of 32 * G consecutive items of its list (first the
+// class's own pieces, then every n_classes-th run of the whole rows).  In round r its four wavefronts work on
+// 4 * G consecutive items of the run, lane group grp of wavefront w on item r * 4 * G + w * G + grp (lane
+// r * G + grp holds that item's descriptor).  The group
 // reads the item's (column, value) pairs with one read per LPR entries (lane `sub` holds entries
 // sub, sub + LPR, ...; the next round's pairs are requested before this round's gathers), and each
 // gather takes its pair from the holding lane by a cross-lane read, eight gathers in flight.
@@ -411,29 +413,35 @@ __device__ __forceinline__ void group_items_body(const SpmmArgs &a, int block)
     constexpr int K = LPR >= GI_MAX ? 1 : GI_MAX / LPR; // index registers per lane (K * LPR >= GI_MAX entries)
     constexpr int U = 8;
     using L = Ld<V>;
+    constexpr int RUN = 4 * UNITS;              // items per workgroup: one run of consecutive items of its list
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cls = block % a.n_classes, blk = block / a.n_classes;
-    const int w_idx = blk * 4 + wave;                            // this wavefront among its class's
-    const int piece_waves = (a.small_cnt[cls] + UNITS - 1) / UNITS;
+    const int piece_blocks = (a.small_cnt[cls] + RUN - 1) / RUN;
     int64_t first, left;
-    if (w_idx < piece_waves) { // uniform per wavefront
-        first = (int64_t)w_idx * UNITS;
+    if (blk < piece_blocks) { // uniform per workgroup
+        first = (int64_t)blk * RUN;
         left = a.small_cnt[cls] - first;
         first += a.small_off[cls];
     } else {
-        first = ((int64_t)(w_idx - piece_waves) * a.n_classes + cls) * UNITS;
+        first = ((int64_t)(blk - piece_blocks) * a.n_classes + cls) * RUN;
         left = a.wsmall_cnt - first;
         first += a.wsmall_off;
     }
-    if (left <= 0) return;
-    const int count = left < UNITS ? (int)left : UNITS;
+    const int run = left < RUN ? (int)left : RUN;
+    // Round r of the workgroup works on the 4 * G consecutive items [r * 4 * G, (r + 1) * 4 * G) of its run, wavefront w
+    // on the G of them from w * G on: what is in flight together on a CU is a window of consecutive rows, so with a row
+    // order that puts rows with common neighbours side by side their gathers meet in the caches while the rows are live.
+    if (run <= wave * G) return; // uniform per wavefront
+    const int rounds = (run - wave * G + 4 * G - 1) / (4 * G);
     int4 d = make_int4(0, 0, 0, NO_UNIT);
-    if (lane < count) d = *reinterpret_cast<const int4 *>(a.items + first + lane);
+    {
+        const int q = (lane / G) * (4 * G) + wave * G + lane % G; // lane r * G + g holds the descriptor of round r, group g
+        if (lane < 8 * G && q < run) d = *reinterpret_cast<const int4 *>(a.items + first + q);
+    }
     const int grp = lane / LPR, sub = lane % LPR, gbase = lane - sub;
     const int col = a.col0 + sub * V;
     const bool col_ok = col < a.col_end;
     const int colc = col_ok ? col : a.col0;
-    const int rounds = (count + G - 1) / G;
     int beg = __shfl(d.y, grp, 64), end = __shfl(d.z, grp, 64);
     int c_k[K];
     float v_k[K];
@@ -674,15 +682,15 @@ int launch_spmm(const slicegcn_graph *g, const Csr &m, const float *X, int64_t l
         const int lanes_needed = (a.col_end - c0 + V - 1) / V;
         int lpr = 8;
         while (lpr < lanes_needed) lpr <<= 1; // 8, 16, 32 or 64
-        const int units = 8 * (64 / lpr); // lane-group items per wavefront
-        const int64_t wsmall_chunks = ((int64_t)sc.wsmall_cnt + units - 1) / units;
-        int64_t small_waves = 0;
-        for (int c = 0; c < sc.n_classes; ++c) {
-            const int64_t wv = (sc.small_cnt[c] + units - 1) / units + (wsmall_chunks + sc.n_classes - 1 - c) / sc.n_classes;
-            small_waves = wv > small_waves ? wv : small_waves;
+        const int64_t run = 4 * 8 * (64 / lpr); // lane-group items per workgroup: runs of consecutive items
+        const int64_t wsmall_runs = ((int64_t)sc.wsmall_cnt + run - 1) / run;
+        int64_t small_blocks = 0;
+        for (int c = 0; c < sc.n_classes; ++c) { // the class's own pieces, then its share of the whole-row runs
+            const int64_t b = (sc.small_cnt[c] + run - 1) / run + (wsmall_runs + sc.n_classes - 1 - c) / sc.n_classes;
+            small_blocks = b > small_blocks ? b : small_blocks;
         }
-        SG_REQUIRE((small_waves + 3) / 4 * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
-        a.small_blocks = (int32_t)((small_waves + 3) / 4);
+        SG_REQUIRE(small_blocks * sc.n_classes <= INT32_MAX, SLICEGCN_ERANGE, "spmm: grid too large");
+        a.small_blocks = (int32_t)small_blocks;
         if (int rc = vec_load ? launch_pass<4>(a, lpr, stream) : launch_pass<1>(a, lpr, stream)) return rc;
         if (sc.n_fix > 0) {
             const int64_t threads = sc.n_fix * (int64_t)(a.col_end - c0);
