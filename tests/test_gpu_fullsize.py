@@ -1,7 +1,7 @@
 """Parity at the full size of the three large workloads (cfg3, cfg4, cfg5), in the launch configuration
 bench.py times.  The oracle builds its own CSR from the same edge list on the host (bit-exact comparison
 of the whole structure); the aggregation is compared on sampled output rows the oracle computes one by
-one, plus the fixed-point invariant A^ (D~^1/2 1) = D~^1/2 1, which holds at any size; and a chain of two
+one, plus the fixed-point invariant A^ (D~^1/2 1) = D~^1/2 1, which holds at any size; the adjoint identity <A^ X, G> = <X, A^ G> over every row with random operands; and a chain of two
 layers of one slice runs forward and backward with every output element compared with the oracle.
 """
 import numpy as np
@@ -92,6 +92,19 @@ def _run(name: str, n_samples: int):
     assert float(torch.max(torch.abs(R[:, 0] / s - 1.0))) <= TOL
     assert float(torch.max(torch.abs(R[:, 5] / (-2.0 * s) - 1.0))) <= TOL
     assert float(torch.max(torch.abs(R[:, 1]))) == 0.0
+    # adjoint identity at full size, every row with random signs: <A^ X, G> = <X, A^T G>, the right side through the
+    # transposed call.  Inner products in fp64 over the fp32 results: the two sides differ by the rounding of the
+    # n * w output elements (random signs: about 1e-7 / sqrt(n w) of |A^X| |G|, some 1e-11), whereas one output row
+    # dropped, doubled or written to the wrong place in either call shifts a side by about 1 / (n sqrt(w)) of it
+    # (2e-8 at 10 M rows x 32 columns)
+    G = configs.normal_matrix(w.seed, configs.STREAM_DH, w.n_nodes, ld, device=dev)
+    sg.slicegcn_spmm_slice(g, Xs[:, :width], Y[:, :width])
+    lhs = float((Y[:, :width].double() * G[:, :width].double()).sum())
+    sg.slicegcn_spmm_slice(g, G[:, :width], Y2[:, :width], transpose=True)
+    rhs = float((Xs[:, :width].double() * Y2[:, :width].double()).sum())
+    norm = float(Y[:, :width].double().norm() * G[:, :width].double().norm())
+    progress(f"[fullsize] {name}: adjoint identity, |lhs - rhs| / (|A^X| |G|) = {abs(lhs - rhs) / norm:.2e}")
+    assert abs(lhs - rhs) <= 2e-9 * norm
 
 
 def _layer_chain(name: str, slice_id: int, n_layers: int = 2):
@@ -187,8 +200,8 @@ def test_cfg5_full_size_sampled():
     _run("cfg5", 2000)
 
 
-def test_cfg5_full_size_layer():
-    _layer_chain("cfg5", 1, n_layers=1)     # 32 -> 32 on 10 M rows with its input gradient: the 32-wide strip kernels
+def test_cfg5_full_size_layer_chain():
+    _layer_chain("cfg5", 1)     # 32 -> 32 -> 32 on 10 M rows: the 32-wide strip kernels, scaled output of layer 1 into layer 2
 
 
 def test_release_cached_graphs():
