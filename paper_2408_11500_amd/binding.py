@@ -315,14 +315,15 @@ def slicegcn_spmm_slice(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int |
 STATIC_WS_BYTES = 16 << 20
 
 
-def slicegcn_spmm_slice_static(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False):
+def slicegcn_spmm_slice_static(g: Graph, X: torch.Tensor, Y: torch.Tensor, width: int | None = None, transpose: bool = False,
+                               prescaled: bool = False):
     """The aggregation with the library's built-in partial-sum buffer: no workspace, no allocation."""
     px, ldx = _mat(X, "X")
     py, ldy = _mat(Y, "Y")
     if X.shape[0] != Y.shape[0]:
         raise ValueError("X and Y differ in rows")
     w = int(X.shape[1] if width is None else width)
-    _check(lib().slicegcn_spmm_slice_static(g.handle, int(transpose), px, ldx, w, py, ldy, _stream()))
+    _check(lib().slicegcn_spmm_slice_static(g.handle, int(transpose) | (2 if prescaled else 0), px, ldx, w, py, ldy, _stream()))
     return Y
 
 

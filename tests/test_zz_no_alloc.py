@@ -39,6 +39,13 @@ def _case(n, m, hubs, hub_deg, width, seed, transpose):
     assert torch.cuda.memory_allocated() == before
     assert torch.equal(Y, Yref), f"static entry differs (n={n}, width={width}, transpose={transpose})"
     assert_close(Y.cpu().numpy(), oracle.spmm(o, X.astype(np.float64), transpose=transpose), "static entry vs oracle")
+    # the factored form through the same entry point (operand rows scaled by D~^-1/2 beforehand)
+    Xs = torch.empty_like(Xd)
+    sg.slicegcn_scale_rows(g, Xd, Xs, width=width)
+    sg.slicegcn_spmm_slice(g, Xs, Yref, transpose=transpose, ws=ws, prescaled=True)
+    Y.fill_(float("nan"))
+    B.slicegcn_spmm_slice_static(g, Xs, Y, transpose=transpose, prescaled=True)
+    assert torch.equal(Y, Yref)
     g.destroy()
 
 
