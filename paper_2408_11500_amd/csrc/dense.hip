@@ -1045,6 +1045,163 @@ __global__ __launch_bounds__(256) void grad_strip32_kernel(const ReduceArgs a, i
     }
 }
 
+// Backward pass of a narrow layer (w_in, w_out <= 32, self term present, input gradient wanted) in one sweep over the
+// node rows: the weight-gradient sums of grad_strip32_kernel and the two input-gradient products of
+// pair_strip32_kernel<true, true> from the same wavefront-private tiles, so that dHout (and the mask) are read once
+// instead of twice.  Per strip of 32 rows: Z, Hin and dHout go to LDS with coalesced 16-byte loads (the next strip's
+// loads in flight behind the MFMAs); the node axis is the k axis of Z^T dP and Hin^T dHout (column reads of the
+// tiles), the column axis that of dZ = dP W_agg^T and T = dHout W_self^T (row reads, weights in registers); dZ and T
+// leave through the Z and Hin tiles as 16-byte stores.  Partial sums: one per wavefront, layout of
+// grad_partial_mfma_kernel.  `a` carries the input-gradient half: B1 / B2 = W_agg / W_self (ldw), O1 = dZ (rows
+// scaled by scale_o1), O2 = T, K = w_out, Nout = w_in.
+__global__ __launch_bounds__(256, 2) void bwd_strip32_kernel(const ReduceArgs r, const PairArgs a, int64_t n_waves)
+{
+    constexpr int ST = 36; // row stride: 16-byte row reads and 4-byte column reads are both conflict free
+    __shared__ __attribute__((aligned(16))) float Zs[4][32][ST];
+    __shared__ __attribute__((aligned(16))) float Hs[4][32][ST];
+    __shared__ __attribute__((aligned(16))) float Gs[4][32][ST];
+    __shared__ uint32_t Ms[4][32];
+    __shared__ __attribute__((aligned(16))) float W1s[32][ST]; // W_agg and W_self, zero padded to 32 x 32: row i, k contiguous
+    __shared__ __attribute__((aligned(16))) float W2s[32][ST];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, h = lane >> 5;
+    const int lr = lane >> 3, lc = (lane & 7) * 4;
+    for (int idx = threadIdx.x; idx < 32 * 32; idx += 256) {
+        const int i = idx >> 5, kk = idx & 31;
+        const bool ok = i < r.w_in && kk < r.w_out;
+        W1s[i][kk] = ok ? a.B1[(int64_t)i * a.ldw + kk] : 0.f;
+        W2s[i][kk] = ok ? a.B2[(int64_t)i * a.ldw + kk] : 0.f;
+    }
+    __syncthreads(); // the only workgroup barrier: before any wavefront leaves
+    const int64_t w_id = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t n_strips = (r.n + 31) / 32, r_end = r.n;
+    if (w_id >= n_waves) return; // uniform per wavefront (n_waves <= n_strips)
+    const bool vz = aligned16(r.Z) && r.ldz % 4 == 0, vh = aligned16(r.Hin) && r.ldi % 4 == 0;
+    const bool vg = aligned16(r.dHout) && r.ldo % 4 == 0;
+    float (*zs)[ST] = Zs[wave];
+    float (*hs)[ST] = Hs[wave];
+    float (*gs)[ST] = Gs[wave];
+    uint32_t *ms = Ms[wave];
+
+    floatx16 accA, accS;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) { accA[x] = 0.f; accS[x] = 0.f; }
+    float sum_p = 0.f, sum_g = 0.f;
+
+    float4 pz[4], ph[4], pg[4];
+    float hf[4] = {1.f, 1.f, 1.f, 1.f};
+    uint32_t pw = ~0u;
+    float ps = 1.f; // scale_o1 of strip row m
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int64_t row = r0 + lr + 8 * it;
+            float4 z = make_float4(0.f, 0.f, 0.f, 0.f), hh = z, g = z;
+            if (row < r_end) {
+                if (lc < r.w_in) {
+                    z = load_k4(r.Z, r.ldz, row, lc, r.w_in, vz);
+                    hh = load_k4(r.Hin, r.ldi, row, lc, r.w_in, vh);
+                    if (r.hin_scale) hf[it] = r.hin_scale[row];
+                }
+                if (lc < r.w_out) g = load_k4(r.dHout, r.ldo, row, lc, r.w_out, vg);
+            }
+            pz[it] = z; ph[it] = hh; pg[it] = g;
+        }
+        if (lane < 32) pw = r0 + lane < r_end ? (r.mask ? r.mask[(r0 + lane) * r.mask_words] : ~0u) : 0u;
+        if (a.scale_o1) ps = r0 + m < r_end ? a.scale_o1[r0 + m] : 1.f;
+    };
+    fetch(w_id * 32);
+    for (int64_t strip = w_id; strip < n_strips; strip += n_waves) {
+        const int64_t row0 = strip * 32;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            if (r.hin_scale) scale4(ph[it], hf[it]);
+            *reinterpret_cast<float4 *>(&zs[lr + 8 * it][lc]) = pz[it];
+            *reinterpret_cast<float4 *>(&hs[lr + 8 * it][lc]) = ph[it];
+            *reinterpret_cast<float4 *>(&gs[lr + 8 * it][lc]) = pg[it];
+        }
+        if (lane < 32) ms[lane] = pw;
+        const float so = ps;
+        __builtin_amdgcn_wave_barrier();
+        if (strip + n_waves < n_strips) fetch((strip + n_waves) * 32); // flies during the MFMAs and the stores below
+#pragma unroll 4
+        for (int s2 = 0; s2 < 16; ++s2) { // node rows 2 s2 + h: Z^T dP, Hin^T dHout and the bias sums
+            const int k = 2 * s2 + h;
+            const float g = gs[k][m];
+            const float p = ((ms[k] >> m) & 1u) ? g : 0.f;
+            accA = __builtin_amdgcn_mfma_f32_32x32x2f32(zs[k][m], p, accA, 0, 0, 0);
+            accS = __builtin_amdgcn_mfma_f32_32x32x2f32(hs[k][m], g, accS, 0, 0, 0);
+            sum_p += p;
+            sum_g += g;
+        }
+        __builtin_amdgcn_sched_barrier(0); // keep the two halves apart: interleaved they do not fit the register file
+        floatx16 acc1, acc2;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) { acc1[x] = 0.f; acc2[x] = 0.f; }
+        const uint32_t word = ms[m];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { // columns 8 q + 4 h + i: dZ = dP W_agg^T and T = dHout W_self^T for strip row m
+            const float4 g4 = *reinterpret_cast<const float4 *>(&gs[m][8 * q + 4 * h]);
+            float4 p4 = g4; // dP = dHout * mask, times the row's output factor
+            const uint32_t bits = word >> (8 * q + 4 * h);
+            if (!(bits & 1u)) p4.x = 0.f;
+            if (!(bits & 2u)) p4.y = 0.f;
+            if (!(bits & 4u)) p4.z = 0.f;
+            if (!(bits & 8u)) p4.w = 0.f;
+            if (a.scale_o1) scale4(p4, so);
+            const float4 w1 = *reinterpret_cast<const float4 *>(&W1s[m][8 * q + 4 * h]);
+            const float4 w2 = *reinterpret_cast<const float4 *>(&W2s[m][8 * q + 4 * h]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(p4, i), pick(w1, i), acc1, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(pick(g4, i), pick(w2, i), acc2, 0, 0, 0);
+            }
+        }
+        // dZ leaves through the Z tile and T through the Hin tile (register x of lane (m, h) is strip row
+        // 8*(x/4) + 4*h + x%4, column m); layouts without 16-byte stores write the registers directly
+        auto store_tile = [&](const floatx16 &o, float (*t)[ST], float *O, int64_t ldo, bool vec_ok) {
+            if (vec_ok) {
+#pragma unroll
+                for (int x = 0; x < 16; ++x) t[8 * (x / 4) + 4 * h + (x % 4)][m] = o[x];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int64_t row = row0 + lr + 8 * it;
+                    if (row < r_end && lc < r.w_in)
+                        *reinterpret_cast<float4 *>(O + row * ldo + lc) = *reinterpret_cast<const float4 *>(&t[lr + 8 * it][lc]);
+                }
+            } else {
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    const int64_t orow = row0 + 8 * (x / 4) + 4 * h + (x % 4);
+                    if (orow < r_end && m < r.w_in) O[orow * ldo + m] = o[x];
+                }
+            }
+        };
+        const bool nout4 = r.w_in % 4 == 0;
+        __builtin_amdgcn_wave_barrier(); // every lane is done reading the tiles
+        store_tile(acc1, zs, a.O1, a.ldo1, nout4 && aligned16(a.O1) && a.ldo1 % 4 == 0);
+        store_tile(acc2, hs, a.O2, a.ldo2, nout4 && aligned16(a.O2) && a.ldo2 % 4 == 0);
+        __builtin_amdgcn_wave_barrier();
+    }
+    sum_p += __shfl_xor(sum_p, 32, 64);
+    sum_g += __shfl_xor(sum_g, 32, 64);
+    float *out = r.partial + w_id * r.stride;
+    const int ww = r.w_in * r.w_out;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+        const int i = 8 * (x / 4) + 4 * h + (x % 4);
+        if (i < r.w_in && m < r.w_out) {
+            out[i * r.w_out + m] = accA[x];
+            out[ww + i * r.w_out + m] = accS[x];
+        }
+    }
+    if (lane < 32 && m < r.w_out) {
+        out[2 * ww + m] = sum_p;
+        out[2 * ww + r.w_out + m] = sum_g;
+    }
+}
+
 // The same for layers up to 64 wide (w_in <= 32 * MI, w_out <= 32 * NJ, large n): a wavefront owns the
 // whole w_in x w_out gradient pair (2 * MI * NJ accumulators), so every operand row is read from
 // memory exactly once.  Strips are dealt to the wavefronts round-robin, so at any moment the chip
@@ -1758,6 +1915,26 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
     const int w_in = desc->w_in, w_out = desc->w_out;
     if (transform_first(desc)) return layer_bwd_transform_first(g, desc, params, Hin, ldi, mask, saved->mask_words, dHout, ldo, dHin, ldgi, grads, ws, stream);
 
+    // ---- input gradient, dense half: dZ = dP W_agg^T (staged, rows scaled by D~^-1/2) and T = dHout W_self^T (into dHin) ----
+    const int64_t ldz_in = round_up(w_in, 32); // rows of the gathered operand start on 128-byte boundaries
+    char *after_partials = static_cast<char *>(ws) + bwd_partial_bytes(g->n, desc);
+    float *dZ = reinterpret_cast<float *>(after_partials);
+    auto input_gradient_args = [&]() {
+        PairArgs a;
+        a.A1 = dHout; a.lda1 = ldo;
+        a.A2 = params->W_self ? dHout : nullptr; a.lda2 = ldo;
+        a.B1 = params->W_agg; a.B2 = params->W_self;
+        a.bias1 = a.bias2 = nullptr;
+        a.O1 = dZ; a.ldo1 = ldz_in;
+        a.O2 = params->W_self ? dHin : nullptr; a.ldo2 = ldgi;
+        a.mask = const_cast<uint32_t *>(mask); a.mask_words = saved->mask_words;
+        a.n = g->n; a.K = w_out; a.Nout = w_in; a.ldw = w_out; a.act = desc->act;
+        a.scale_o1 = g->dinv; // dZ is staged as D~^-1/2 dZ: its aggregation then skips the stored values
+        return a;
+    };
+    // narrow layers with a self term: the kernel that forms the weight gradients also forms dZ and T (one read of dHout)
+    const bool fused_inputs = dHin && params->W_self && w_in <= 32 && w_out <= 32 && g->n >= 65536;
+
     // ---- parameter gradients: per-row-block partial sums, then an fp64 combination ----
     float *partial = static_cast<float *>(ws);
     const int64_t nb = layer_grad_blocks(g->n, w_in, w_out); // partial sums the workspace has room for
@@ -1780,7 +1957,12 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
             const int64_t n_strips = (g->n + 31) / 32;
             if (waves > n_strips) waves = n_strips;
             n_partials = waves;
-            grad_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, waves);
+            if (fused_inputs) { // weight gradients and the two input-gradient products in one sweep over the rows
+                PairArgs a = input_gradient_args();
+                bwd_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, a, waves);
+            } else {
+                grad_strip32_kernel<<<(unsigned)((waves + 3) / 4), 256, 0, stream>>>(r, waves);
+            }
         } else if (w_in <= 64 && w_out <= 64 && g->n >= ((int64_t)1 << 21)) {
             // whole waves of resident workgroups (256 CUs x 3 workgroups x 4 wavefronts) when the workspace allows
             const int64_t resident = 3072;
@@ -1809,22 +1991,11 @@ extern "C" int slicegcn_layer_bwd(const slicegcn_graph *g, const slicegcn_layer_
 
     // ---- input gradient: dHin = A^^T (dP W_agg^T) + dHout W_self^T ----
     if (dHin) {
-        const int64_t ldz = round_up(w_in, 32); // rows of the gathered operand start on 128-byte boundaries
-        char *after_partials = static_cast<char *>(ws) + bwd_partial_bytes(g->n, desc);
-        float *dZ = reinterpret_cast<float *>(after_partials);
         void *agg_ws = after_partials + bwd_dz_bytes(g->n, desc);
         const size_t agg_ws_bytes = spmm_workspace_bytes(g->tr, w_in);
-        PairArgs a;
-        a.A1 = dHout; a.lda1 = ldo;
-        a.A2 = params->W_self ? dHout : nullptr; a.lda2 = ldo;
-        a.B1 = params->W_agg; a.B2 = params->W_self;
-        a.bias1 = a.bias2 = nullptr;
-        a.O1 = dZ; a.ldo1 = ldz;
-        a.O2 = params->W_self ? dHin : nullptr; a.ldo2 = ldgi;
-        a.mask = const_cast<uint32_t *>(mask); a.mask_words = saved->mask_words;
-        a.n = g->n; a.K = w_out; a.Nout = w_in; a.ldw = w_out; a.act = desc->act;
-        a.scale_o1 = g->dinv; // dZ is staged as D~^-1/2 dZ: its aggregation then skips the stored values
-        {
+        const int64_t ldz = ldz_in;
+        if (!fused_inputs) {
+            PairArgs a = input_gradient_args();
             ProfScope prof(SLICEGCN_PROF_DENSE_BWD, w_in, stream);
             if (int rc = launch_pair<true>(a, stream)) return rc;
         }
