@@ -927,6 +927,13 @@ def test_mid_layer_ragged_widths(shape, act, has_self):
     layer_many_rows(270001, shape, act, has_self)
 
 
+@pytest.mark.parametrize("shape,act,has_self", [((301, 128), 1, True), ((100, 130), 1, False), ((128, 70), 0, True)])
+def test_wide_layer_many_rows(shape, act, has_self):
+    """Layers wider than 64 on more than 65536 rows: the staged dense kernel (one and two column tiles per
+    workgroup) and the tiled two-product weight-gradient kernel."""
+    layer_many_rows(70001, shape, act, has_self)
+
+
 def layer_many_rows(n, shape, act, has_self):
     rng = np.random.default_rng(shape[0] * 100 + shape[1] + act)
     src = rng.integers(0, n, 3 * n); dst = rng.integers(0, n, 3 * n)
